@@ -1,0 +1,173 @@
+/*
+ * mq.h -- C boundary of the MI355X (gfx950) low-precision matrix-product library.
+ *
+ * The library implements the integer matrix-product path of arxiv 1805.12096:
+ *   quant_int  (Section 4.2, "Quantization and integer products"): a float
+ *              tensor is multiplied by a quantization multiplier and rounded to
+ *              8- or 16-bit signed integers;
+ *   dot'_int   (Section 4.3, "Memoization"): the product of two quantized
+ *              tensors, A times the transpose of B, both contiguous along the
+ *              contracted index, accumulated in 32 bits (Section 4.2);
+ *   memoized   quant_int(B^T) of a parameter is a constant of the graph and is
+ *              computed once (Section 4.3) -- here: mq_prepare_weight;
+ *   epilogue   the integer product replaces the float product (Sections 4.3,
+ *              4.4): sums are scaled back to float, the bias is added, outputs
+ *              are not clipped or quantized (Section 4.2);
+ *   arg-max    with beam size 1 no softmax is evaluated, the highest activation
+ *              wins (Section 2.3, "Decoding with small beams").
+ *
+ * General rules
+ *   - Every pointer named "dev" or documented as device memory is a HIP device
+ *     pointer on the current device.  The CALLER owns every buffer; the library
+ *     never allocates, frees, or keeps a pointer after the call returns.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and returns without synchronizing.  Results
+ *     are valid once the stream has reached that point.
+ *   - Matrices are dense and row-major.  A is [M x K]; the parameter is used
+ *     as Wt = B^T, [N x K]; outputs are [M x N].
+ *   - Quantization multipliers ("scales") live in device memory as one float
+ *     each, so that chains of calls never wait for the host.
+ *   - bits is 8 (values in [-127, 127], int8_t) or 16 ([-32767, 32767], int16_t).
+ *   - Every function returning int returns an mq_status.  Arguments are checked
+ *     before anything is enqueued; a failed check enqueues nothing.  Pointers
+ *     to float / int32 data must be 4-byte aligned, `x`, `q`, `qA`, `packed`
+ *     16-byte aligned (MQ_ERR_ALIGN otherwise).  Sizes must be non-zero and the
+ *     element counts M*K, N*K, M*N must fit in 2^40 (MQ_ERR_SHAPE otherwise).
+ *   - Inputs are expected to be finite.  A NaN never faults: it is ignored by
+ *     the abs-max and quantizes to 0.
+ *   - Integer sums are exact modulo 2^32 (two's complement wrap), independent of
+ *     tiling.  With 8-bit operands no sum can wrap for K <= 133 144.
+ */
+#ifndef MQ_H_
+#define MQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mq_status {
+  MQ_OK = 0,
+  MQ_ERR_NULL = 1,        /* a required pointer is NULL */
+  MQ_ERR_SHAPE = 2,       /* a size is zero or too large */
+  MQ_ERR_DTYPE = 3,       /* bits is not 8 or 16 (or the call supports 8 only) */
+  MQ_ERR_ALIGN = 4,       /* a pointer is not aligned as required */
+  MQ_ERR_WORKSPACE = 5,   /* workspace smaller than the *_ws_bytes query says */
+  MQ_ERR_UNSUPPORTED = 6, /* valid arguments the library cannot serve */
+  MQ_ERR_HIP = 7          /* the HIP runtime refused a launch; see mq_last_hip_error */
+} mq_status;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int mq_version(void);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* mq_status_string(int status);
+
+/* hipError_t value of the last failed HIP call made by this thread inside the
+ * library (0 if none). */
+int mq_last_hip_error(void);
+
+/* ---- quant_int (Section 4.2) -------------------------------------------- */
+
+/* amax[0] = max_i |x[i]| over n floats (NaNs skipped).  The paper uses fixed
+ * multipliers; a per-tensor multiplier Qmax / max|x| needs this reduction.
+ * x: device, 16-byte aligned.  amax: device float[1], overwritten. */
+int mq_absmax_f32(const float* x, size_t n, float* amax, void* stream);
+
+/* scale[0] = Qmax(bits) / amax[0] as one correctly rounded binary32 division;
+ * 1.0f if amax[0] is 0.  amax, scale: device float[1] (may be the same address). */
+int mq_scale_from_amax(const float* amax, int bits, float* scale, void* stream);
+
+/* quant_int: q[i] = clamp(round_half_even(x[i] * scale[0]), -Qmax, +Qmax), the
+ * product taken in binary32.  x: device float [rows x cols]; q: device
+ * int8_t / int16_t [rows x cols]; scale: device float[1].
+ * rowsum (device int32 [rows], may be NULL): receives sum_c q[r][c]; the 16-bit
+ * product needs it (see mq_gemm_i32). */
+int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                    void* q, int32_t* rowsum, void* stream);
+
+/* ---- memoized quant_int(B^T) (Section 4.3) ------------------------------ */
+
+/* Bytes of the packed parameter for an [N x K] Wt; 0 if bits is invalid or a
+ * size is zero. */
+size_t mq_packed_bytes(int bits, size_t N, size_t K);
+
+/* Quantize a float parameter, transpose it to [N x K] if needed and store it in
+ * the tile order the product kernels read.  Done once per parameter; the packed
+ * buffer is then a constant that any number of products reuse.
+ *   B: device float; b_is_transposed == 0: B is [K x N]; != 0: B is Wt, [N x K].
+ *   scale_or_null: device float[1] multiplier to use, or NULL to use
+ *     Qmax / max|B| (computed here).
+ *   scale_out: device float[1], receives the multiplier used (required).
+ *   packed: device, 16-byte aligned, mq_packed_bytes(bits, N, K) bytes, fully
+ *     overwritten (padding included), opaque but position independent: it may
+ *     be copied or saved as plain bytes. */
+int mq_prepare_weight(const float* B, int b_is_transposed, size_t N, size_t K, int bits,
+                      const float* scale_or_null, float* scale_out, void* packed, void* stream);
+
+/* Inverse of the packing, for inspection and tests: q_out receives the
+ * quantized Wt as plain row-major int8_t / int16_t [N x K] (device). */
+int mq_unpack_weight(const void* packed, int bits, size_t N, size_t K, void* q_out, void* stream);
+
+/* ---- dot'_int (Sections 4.2, 4.3) --------------------------------------- */
+
+/* C[m][n] = sum_k qA[m][k] * Wt[n][k] modulo 2^32, raw 32-bit sums.
+ *   qA: device int8_t / int16_t [M x K], row-major.
+ *   rowsumA: device int32 [M] with sum_k qA[m][k]; required for bits == 16
+ *     (the 16-bit product runs as four 8-bit products on offset byte planes and
+ *     the row sums undo the offset), ignored for bits == 8 (may be NULL).
+ *   packedW: from mq_prepare_weight with the same bits, N, K.
+ *   C: device int32 [M x N]. */
+int mq_gemm_i32(const void* qA, const int32_t* rowsumA, const void* packedW, int bits,
+                size_t M, size_t N, size_t K, int32_t* C, void* stream);
+
+/* Product with the float epilogue fused:
+ *   Y[m][n] = fma((float)acc[m][n], 1 / (sA[0] * sW[0]), bias ? bias[n] : 0),
+ *   then max(Y, 0) if relu != 0.
+ * sA, sW: device float[1] multipliers of the two operands.  bias: device float
+ * [N] or NULL.  Y: device float [M x N].
+ * out_amax: NULL, or device float[1] that the CALLER has set to 0 (or to a
+ * running maximum): on return it holds max(previous, max |Y|), so the next
+ * quant_int of Y needs no separate reduction pass. */
+int mq_gemm_dequant(const void* qA, const int32_t* rowsumA, const void* packedW, int bits,
+                    size_t M, size_t N, size_t K, const float* sA, const float* sW,
+                    const float* bias, int relu, float* Y, float* out_amax, void* stream);
+
+/* ---- greedy output layer (Section 2.3) ---------------------------------- */
+
+/* Workspace bytes mq_gemm_argmax needs for an M-row problem. */
+size_t mq_argmax_ws_bytes(size_t M, size_t N);
+
+/* 8-bit product against the (tied embedding) output matrix with the beam-1
+ * arg-max fused; the M x N logits are never written:
+ *   tok[m]      = smallest n with acc[m][n] == max_n acc[m][n]
+ *   maxlogit[m] = (float)max_n acc[m][n] * (1 / (sA[0] * sW[0]))
+ * qA: device int8_t [M x K]; packedW: 8-bit packed [N x K]; tok: device int32
+ * [M]; maxlogit: device float [M]; ws: device, 16-byte aligned, at least
+ * mq_argmax_ws_bytes(M, N) bytes, contents irrelevant on entry and undefined
+ * on return.  N must be below 2^31. */
+int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size_t K,
+                   const float* sA, const float* sW, int32_t* tok, float* maxlogit,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* ---- composition -------------------------------------------------------- */
+
+/* Workspace bytes mq_linear_f32 needs. */
+size_t mq_linear_ws_bytes(int bits, size_t M, size_t K);
+
+/* Float-in, float-out replacement for Y = A * B + bias with a prepared
+ * parameter: abs-max and quant_int of A (or quant_int with the given multiplier
+ * if sA_or_null is not NULL), then mq_gemm_dequant.  A composition of the calls
+ * above on the same stream; nothing else is computed.
+ * A: device float [M x K], 16-byte aligned.  ws as for mq_gemm_argmax. */
+int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null,
+                  const void* packedW, const float* sW, int bits, size_t N,
+                  const float* bias, int relu, float* Y, float* out_amax,
+                  void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQ_H_ */

@@ -1,0 +1,204 @@
+"""ctypes binding of libmq.so.  Argument marshalling only: every function below
+has the name and the argument order of the C entry point it calls (see
+include/mq.h) and takes torch CUDA tensors where C takes device pointers.
+PyTorch supplies device memory and the current HIP stream, nothing else.
+
+There is no fallback: if the library has not been built, importing fails with
+instructions, and every non-zero status raises MqError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+__all__ = [
+    "MqError", "lib_path", "load_library", "exported_symbols",
+    "mq_version", "mq_status_string", "mq_last_hip_error",
+    "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_packed_bytes",
+    "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
+    "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32",
+    "PreparedWeight", "prepare_weight",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmq.so")
+_lib = None
+
+MQ_OK = 0
+
+
+class MqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().mq_status_string(status).decode()
+        extra = ""
+        if status == 7:
+            extra = f" (hipError {load_library().mq_last_hip_error()})"
+        super().__init__(f"{where}: status {status}: {msg}{extra}")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def exported_symbols():
+    """Names include/mq.h declares; used by the CPU-only load test."""
+    return ["mq_version", "mq_status_string", "mq_last_hip_error", "mq_absmax_f32",
+            "mq_scale_from_amax", "mq_quantize_f32", "mq_packed_bytes", "mq_prepare_weight",
+            "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_argmax_ws_bytes",
+            "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32"]
+
+
+def load_library():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_1805_12096_amd.build` "
+            "(or __graft_entry__.build()).  There is no CPU fallback.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.mq_version.restype = ci
+    lib.mq_status_string.restype = ctypes.c_char_p
+    lib.mq_status_string.argtypes = [ci]
+    lib.mq_last_hip_error.restype = ci
+    lib.mq_absmax_f32.argtypes = [vp, sz, vp, vp]
+    lib.mq_scale_from_amax.argtypes = [vp, ci, vp, vp]
+    lib.mq_quantize_f32.argtypes = [vp, sz, sz, ci, vp, vp, vp, vp]
+    lib.mq_packed_bytes.restype = sz
+    lib.mq_packed_bytes.argtypes = [ci, sz, sz]
+    lib.mq_prepare_weight.argtypes = [vp, ci, sz, sz, ci, vp, vp, vp, vp]
+    lib.mq_unpack_weight.argtypes = [vp, ci, sz, sz, vp, vp]
+    lib.mq_gemm_i32.argtypes = [vp, vp, vp, ci, sz, sz, sz, vp, vp]
+    lib.mq_gemm_dequant.argtypes = [vp, vp, vp, ci, sz, sz, sz, vp, vp, vp, ci, vp, vp, vp]
+    lib.mq_argmax_ws_bytes.restype = sz
+    lib.mq_argmax_ws_bytes.argtypes = [sz, sz]
+    lib.mq_gemm_argmax.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.mq_linear_ws_bytes.restype = sz
+    lib.mq_linear_ws_bytes.argtypes = [ci, sz, sz]
+    lib.mq_linear_f32.argtypes = [vp, sz, sz, vp, vp, vp, ci, sz, vp, ci, vp, vp, vp, sz, vp]
+    for name in exported_symbols():
+        fn = getattr(lib, name)
+        if fn.restype is None:
+            fn.restype = ci
+    _lib = lib
+    return lib
+
+
+def _p(t):
+    """Device pointer of a tensor (None -> NULL); raw ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != MQ_OK:
+        raise MqError(status, where)
+
+
+def mq_version() -> int:
+    return int(load_library().mq_version())
+
+
+def mq_status_string(status: int) -> str:
+    return load_library().mq_status_string(int(status)).decode()
+
+
+def mq_last_hip_error() -> int:
+    return int(load_library().mq_last_hip_error())
+
+
+def mq_absmax_f32(x, n, amax, stream=None):
+    _check(load_library().mq_absmax_f32(_p(x), n, _p(amax), _stream(stream)), "mq_absmax_f32")
+
+
+def mq_scale_from_amax(amax, bits, scale, stream=None):
+    _check(load_library().mq_scale_from_amax(_p(amax), bits, _p(scale), _stream(stream)), "mq_scale_from_amax")
+
+
+def mq_quantize_f32(x, rows, cols, bits, scale, q, rowsum=None, stream=None):
+    _check(load_library().mq_quantize_f32(_p(x), rows, cols, bits, _p(scale), _p(q), _p(rowsum),
+                                          _stream(stream)), "mq_quantize_f32")
+
+
+def mq_packed_bytes(bits, N, K) -> int:
+    return int(load_library().mq_packed_bytes(bits, N, K))
+
+
+def mq_prepare_weight(B, b_is_transposed, N, K, bits, scale_or_null, scale_out, packed, stream=None):
+    _check(load_library().mq_prepare_weight(_p(B), int(b_is_transposed), N, K, bits, _p(scale_or_null),
+                                            _p(scale_out), _p(packed), _stream(stream)), "mq_prepare_weight")
+
+
+def mq_unpack_weight(packed, bits, N, K, q_out, stream=None):
+    _check(load_library().mq_unpack_weight(_p(packed), bits, N, K, _p(q_out), _stream(stream)), "mq_unpack_weight")
+
+
+def mq_gemm_i32(qA, rowsumA, packedW, bits, M, N, K, C, stream=None):
+    _check(load_library().mq_gemm_i32(_p(qA), _p(rowsumA), _p(packedW), bits, M, N, K, _p(C),
+                                      _stream(stream)), "mq_gemm_i32")
+
+
+def mq_gemm_dequant(qA, rowsumA, packedW, bits, M, N, K, sA, sW, bias, relu, Y, out_amax=None, stream=None):
+    _check(load_library().mq_gemm_dequant(_p(qA), _p(rowsumA), _p(packedW), bits, M, N, K, _p(sA), _p(sW),
+                                          _p(bias), int(relu), _p(Y), _p(out_amax), _stream(stream)),
+           "mq_gemm_dequant")
+
+
+def mq_argmax_ws_bytes(M, N) -> int:
+    return int(load_library().mq_argmax_ws_bytes(M, N))
+
+
+def mq_gemm_argmax(qA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, ws_bytes, stream=None):
+    _check(load_library().mq_gemm_argmax(_p(qA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(tok), _p(maxlogit),
+                                         _p(ws), ws_bytes, _stream(stream)), "mq_gemm_argmax")
+
+
+def mq_linear_ws_bytes(bits, M, K) -> int:
+    return int(load_library().mq_linear_ws_bytes(bits, M, K))
+
+
+def mq_linear_f32(A, M, K, sA_or_null, packedW, sW, bits, N, bias, relu, Y, out_amax, ws, ws_bytes, stream=None):
+    _check(load_library().mq_linear_f32(_p(A), M, K, _p(sA_or_null), _p(packedW), _p(sW), bits, N, _p(bias),
+                                        int(relu), _p(Y), _p(out_amax), _p(ws), ws_bytes, _stream(stream)),
+           "mq_linear_f32")
+
+
+# ---- allocation helper (no arithmetic) --------------------------------------
+
+@dataclass
+class PreparedWeight:
+    """Device buffers of one memoized parameter: packed bytes and its multiplier."""
+    packed: torch.Tensor
+    scale: torch.Tensor
+    bits: int
+    N: int
+    K: int
+
+
+def prepare_weight(W: torch.Tensor, bits: int, transposed: bool = True, scale: torch.Tensor | None = None,
+                   stream=None) -> PreparedWeight:
+    """Allocate the packed buffer and call mq_prepare_weight.  W is a float32 CUDA
+    tensor, [N x K] if transposed else [K x N]."""
+    if not W.is_cuda or W.dtype != torch.float32 or not W.is_contiguous():
+        raise ValueError("W must be a contiguous float32 CUDA tensor")
+    N, K = (W.shape if transposed else W.shape[::-1])
+    packed = torch.empty(mq_packed_bytes(bits, N, K), dtype=torch.uint8, device=W.device)
+    scale_out = torch.empty(1, dtype=torch.float32, device=W.device)
+    mq_prepare_weight(W, transposed, N, K, bits, scale, scale_out, packed, stream)
+    return PreparedWeight(packed, scale_out, bits, int(N), int(K))

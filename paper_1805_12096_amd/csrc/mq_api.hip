@@ -1,0 +1,226 @@
+// C boundary: argument checks, then launches.  Nothing here computes.
+#include "mq_internal.h"
+
+namespace mq {
+
+static thread_local int g_last_hip_error = 0;
+
+int check_hip(hipError_t e) {
+  if (e == hipSuccess) return MQ_OK;
+  g_last_hip_error = (int)e;
+  return MQ_ERR_HIP;
+}
+
+namespace {
+
+constexpr size_t kMaxElems = (size_t)1 << 40;
+constexpr size_t kMaxDim = (size_t)1 << 31;
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+bool bits_ok(int bits) { return bits == 8 || bits == 16; }
+bool dims_ok(size_t M, size_t N, size_t K) {
+  if (M == 0 || N == 0 || K == 0) return false;
+  if (M >= kMaxDim || N >= kMaxDim || K >= kMaxDim) return false;
+  if (M > kMaxElems / K || N > kMaxElems / K || M > kMaxElems / N) return false;
+  return true;
+}
+hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+// Layout of the scratch area used by mq_linear_f32 / mq_gemm_argmax.
+struct LinearWs {
+  size_t off_scale, off_rowsum, off_q, total;
+  LinearWs(int bits, size_t M, size_t K) {
+    off_scale = 0;                       // float amax/scale
+    off_rowsum = 256;                    // int32 [M]
+    off_q = round_up(off_rowsum + M * sizeof(int32_t), 256);
+    total = off_q + round_up(M * K * (size_t)(bits / 8), 256);
+  }
+};
+
+int gemm_common_checks(const void* qA, const int32_t* rowsumA, const void* packedW, int bits,
+                       size_t M, size_t N, size_t K) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (qA == nullptr || packedW == nullptr) return MQ_ERR_NULL;
+  if (bits == 16 && rowsumA == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(qA, 16) || !aligned(packedW, 16)) return MQ_ERR_ALIGN;
+  if (rowsumA != nullptr && !aligned(rowsumA, 4)) return MQ_ERR_ALIGN;
+  return MQ_OK;
+}
+
+}  // namespace
+}  // namespace mq
+
+using namespace mq;
+
+extern "C" {
+
+int mq_version(void) { return 100; }
+
+const char* mq_status_string(int status) {
+  switch (status) {
+    case MQ_OK: return "ok";
+    case MQ_ERR_NULL: return "a required pointer is NULL";
+    case MQ_ERR_SHAPE: return "a size is zero or too large";
+    case MQ_ERR_DTYPE: return "bits must be 8 or 16 (8 only for the arg-max product)";
+    case MQ_ERR_ALIGN: return "a pointer is not aligned as required";
+    case MQ_ERR_WORKSPACE: return "workspace too small";
+    case MQ_ERR_UNSUPPORTED: return "unsupported arguments";
+    case MQ_ERR_HIP: return "HIP runtime error (see mq_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int mq_last_hip_error(void) { return g_last_hip_error; }
+
+int mq_absmax_f32(const float* x, size_t n, float* amax, void* stream) {
+  if (x == nullptr || amax == nullptr) return MQ_ERR_NULL;
+  if (n == 0 || n > kMaxElems) return MQ_ERR_SHAPE;
+  if (!aligned(x, 16) || !aligned(amax, 4)) return MQ_ERR_ALIGN;
+  return launch_absmax(x, n, amax, as_stream(stream));
+}
+
+int mq_scale_from_amax(const float* amax, int bits, float* scale, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (amax == nullptr || scale == nullptr) return MQ_ERR_NULL;
+  if (!aligned(amax, 4) || !aligned(scale, 4)) return MQ_ERR_ALIGN;
+  return launch_scale(amax, bits, scale, as_stream(stream));
+}
+
+int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale, void* q,
+                    int32_t* rowsum, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (x == nullptr || scale == nullptr || q == nullptr) return MQ_ERR_NULL;
+  if (rows == 0 || cols == 0 || rows >= kMaxDim || cols >= kMaxDim || rows > kMaxElems / cols)
+    return MQ_ERR_SHAPE;
+  if (!aligned(x, 16) || !aligned(q, 16) || !aligned(scale, 4)) return MQ_ERR_ALIGN;
+  if (rowsum != nullptr && !aligned(rowsum, 4)) return MQ_ERR_ALIGN;
+  return launch_quantize(x, rows, cols, bits, scale, q, rowsum, as_stream(stream));
+}
+
+size_t mq_packed_bytes(int bits, size_t N, size_t K) {
+  if (!bits_ok(bits) || N == 0 || K == 0 || N >= kMaxDim || K >= kMaxDim) return 0;
+  return PackedDims(bits, N, K).total_bytes();
+}
+
+int mq_prepare_weight(const float* B, int b_is_transposed, size_t N, size_t K, int bits,
+                      const float* scale_or_null, float* scale_out, void* packed, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (B == nullptr || scale_out == nullptr || packed == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(1, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(B, 16) || !aligned(packed, 16) || !aligned(scale_out, 4)) return MQ_ERR_ALIGN;
+  if (scale_or_null != nullptr && !aligned(scale_or_null, 4)) return MQ_ERR_ALIGN;
+  hipStream_t s = as_stream(stream);
+  if (scale_or_null == nullptr) {
+    int rc = launch_absmax(B, N * K, scale_out, s);
+    if (rc != MQ_OK) return rc;
+    rc = launch_scale(scale_out, bits, scale_out, s);
+    if (rc != MQ_OK) return rc;
+  } else if (scale_or_null != scale_out) {
+    int rc = check_hip(hipMemcpyAsync(scale_out, scale_or_null, sizeof(float), hipMemcpyDeviceToDevice, s));
+    if (rc != MQ_OK) return rc;
+  }
+  return launch_prepare(B, b_is_transposed != 0, N, K, bits, scale_out, packed, s);
+}
+
+int mq_unpack_weight(const void* packed, int bits, size_t N, size_t K, void* q_out, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (packed == nullptr || q_out == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(1, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packed, 16) || !aligned(q_out, 2)) return MQ_ERR_ALIGN;
+  return launch_unpack(packed, bits, N, K, q_out, as_stream(stream));
+}
+
+int mq_gemm_i32(const void* qA, const int32_t* rowsumA, const void* packedW, int bits, size_t M,
+                size_t N, size_t K, int32_t* C, void* stream) {
+  int rc = gemm_common_checks(qA, rowsumA, packedW, bits, M, N, K);
+  if (rc != MQ_OK) return rc;
+  if (C == nullptr) return MQ_ERR_NULL;
+  if (!aligned(C, 4)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = qA; a.rowsumA = rowsumA; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K; a.C = C;
+  return launch_gemm(a, kEpiRaw, as_stream(stream));
+}
+
+int mq_gemm_dequant(const void* qA, const int32_t* rowsumA, const void* packedW, int bits, size_t M,
+                    size_t N, size_t K, const float* sA, const float* sW, const float* bias, int relu,
+                    float* Y, float* out_amax, void* stream) {
+  int rc = gemm_common_checks(qA, rowsumA, packedW, bits, M, N, K);
+  if (rc != MQ_OK) return rc;
+  if (sA == nullptr || sW == nullptr || Y == nullptr) return MQ_ERR_NULL;
+  if (!aligned(sA, 4) || !aligned(sW, 4) || !aligned(Y, 4)) return MQ_ERR_ALIGN;
+  if ((bias != nullptr && !aligned(bias, 4)) || (out_amax != nullptr && !aligned(out_amax, 4)))
+    return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = qA; a.rowsumA = rowsumA; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
+  return launch_gemm(a, kEpiDequant, as_stream(stream));
+}
+
+size_t mq_argmax_ws_bytes(size_t M, size_t N) {
+  if (M == 0 || N == 0 || M >= kMaxDim || N >= kMaxDim) return 0;
+  return round_up(M * sizeof(unsigned long long), 256);
+}
+
+int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                   const float* sW, int32_t* tok, float* maxlogit, void* ws, size_t ws_bytes,
+                   void* stream) {
+  int rc = gemm_common_checks(qA, nullptr, packedW, 8, M, N, K);
+  if (rc != MQ_OK) return rc;
+  if (sA == nullptr || sW == nullptr || tok == nullptr || maxlogit == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!aligned(sA, 4) || !aligned(sW, 4) || !aligned(tok, 4) || !aligned(maxlogit, 4) || !aligned(ws, 16))
+    return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_argmax_ws_bytes(M, N)) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  unsigned long long* keys = static_cast<unsigned long long*>(ws);
+  rc = launch_argmax_init(keys, M, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs a{};
+  a.qA = qA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K; a.keys = keys;
+  rc = launch_gemm(a, kEpiArgmax, s);
+  if (rc != MQ_OK) return rc;
+  return launch_argmax_finish(keys, M, sA, sW, tok, maxlogit, s);
+}
+
+size_t mq_linear_ws_bytes(int bits, size_t M, size_t K) {
+  if (!bits_ok(bits) || M == 0 || K == 0 || M >= kMaxDim || K >= kMaxDim || M > kMaxElems / K) return 0;
+  return LinearWs(bits, M, K).total;
+}
+
+int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null, const void* packedW,
+                  const float* sW, int bits, size_t N, const float* bias, int relu, float* Y,
+                  float* out_amax, void* ws, size_t ws_bytes, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (A == nullptr || packedW == nullptr || sW == nullptr || Y == nullptr || ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(packedW, 16) || !aligned(ws, 16) || !aligned(sW, 4) || !aligned(Y, 4))
+    return MQ_ERR_ALIGN;
+  if ((sA_or_null != nullptr && !aligned(sA_or_null, 4)) || (bias != nullptr && !aligned(bias, 4)) ||
+      (out_amax != nullptr && !aligned(out_amax, 4)))
+    return MQ_ERR_ALIGN;
+  const LinearWs L(bits, M, K);
+  if (ws_bytes < L.total) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  float* scale = reinterpret_cast<float*>(base + L.off_scale);
+  int32_t* rowsum = reinterpret_cast<int32_t*>(base + L.off_rowsum);
+  void* q = base + L.off_q;
+  const float* sA = sA_or_null;
+  int rc;
+  if (sA == nullptr) {
+    rc = launch_absmax(A, M * K, scale, s);
+    if (rc != MQ_OK) return rc;
+    rc = launch_scale(scale, bits, scale, s);
+    if (rc != MQ_OK) return rc;
+    sA = scale;
+  }
+  rc = launch_quantize(A, M, K, bits, sA, q, bits == 16 ? rowsum : nullptr, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs a{};
+  a.qA = q; a.rowsumA = rowsum; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
+  return launch_gemm(a, kEpiDequant, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Internal declarations shared by the library's translation units (not part of
+// the C boundary, not used by the CPU oracle).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mq.h"
+
+namespace mq {
+
+constexpr int kWave = 64;          // wavefront width on gfx950
+constexpr int kFragRows = 32;      // rows of Wt (or of A) per MFMA operand fragment
+constexpr int kFragK = 32;         // contracted elements per v_mfma_i32_32x32x32_i8
+constexpr int kFragBytes = 1024;   // 64 lanes x 16 bytes
+constexpr int kKPad = 64;          // packed K is padded to this (two MFMA steps)
+
+__host__ __device__ inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// Packed parameter geometry.  The quantized Wt [N x K] is cut into fragments of
+// 32 rows x 32 contracted elements; fragment (nb, kb) holds, for lane l, the 16
+// bytes Wt[32 nb + l % 32][32 kb + 16 (l / 32) + 0..15] at byte offset 16 l.
+// Fragments of one row block follow each other along K, row blocks follow each
+// other.  16-bit parameters store two byte planes per fragment (high byte, then
+// low byte with its top bit flipped) and append sum_k Wt[n][k] as int32 [Np].
+// Rows n >= N and elements k >= K are zero bytes in every plane.
+struct PackedDims {
+  size_t Np, Kp, nblocks, kfrags;
+  int planes;
+  __host__ __device__ PackedDims(int bits, size_t N, size_t K)
+      : Np(round_up(N, kFragRows)), Kp(round_up(K, kKPad)), nblocks(Np / kFragRows),
+        kfrags(Kp / kFragK), planes(bits == 16 ? 2 : 1) {}
+  __host__ __device__ size_t frag_offset(size_t nb, size_t kb) const {
+    return (nb * kfrags + kb) * (size_t)kFragBytes * planes;
+  }
+  __host__ __device__ size_t plane_bytes() const { return Np * Kp * planes; }
+  __host__ __device__ size_t total_bytes() const {
+    return plane_bytes() + (planes == 2 ? Np * sizeof(int32_t) : 0);
+  }
+};
+
+// Records a HIP error for mq_last_hip_error and maps it to a status.
+int check_hip(hipError_t e);
+
+inline int qmax_of(int bits) { return bits == 8 ? 127 : (bits == 16 ? 32767 : 0); }
+
+// Kernel launchers (each enqueues on `s` and returns an mq_status).
+int launch_absmax(const float* x, size_t n, float* amax, hipStream_t s);
+int launch_scale(const float* amax, int bits, float* scale, hipStream_t s);
+int launch_quantize(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                    void* q, int32_t* rowsum, hipStream_t s);
+int launch_prepare(const float* B, int transposed, size_t N, size_t K, int bits,
+                   const float* scale, void* packed, hipStream_t s);
+int launch_unpack(const void* packed, int bits, size_t N, size_t K, void* q, hipStream_t s);
+
+enum Epilogue { kEpiRaw = 0, kEpiDequant = 1, kEpiArgmax = 2 };
+
+struct GemmArgs {
+  const void* qA;
+  const int32_t* rowsumA;
+  const void* packedW;
+  int bits;
+  size_t M, N, K;
+  // raw
+  int32_t* C;
+  // dequant
+  const float* sA;
+  const float* sW;
+  const float* bias;
+  int relu;
+  float* Y;
+  float* out_amax;
+  // argmax
+  unsigned long long* keys;  // [M] packed (sum, ~index) maxima
+};
+int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
+int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
+int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* sA, const float* sW,
+                         int32_t* tok, float* maxlogit, hipStream_t s);
+
+}  // namespace mq

@@ -1,0 +1,214 @@
+// quant_int on gfx950: per-tensor abs-max, multiplier, and the float -> int8 /
+// int16 conversion (arxiv 1805.12096, Section 4.2).  All three are bound by HBM
+// traffic: wide coalesced loads, one pass each.
+#include "mq_internal.h"
+
+namespace mq {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
+
+// |x| of a non-NaN float orders like its bit pattern, so the grid-wide maximum
+// is an integer atomicMax.  fmaxf drops NaN operands.
+__global__ __launch_bounds__(kThreads) void k_absmax(const float* __restrict__ x, size_t n,
+                                                     uint32_t* __restrict__ amax_bits) {
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const size_t nvec = n / 4;
+  const float4* xv = reinterpret_cast<const float4*>(x);
+  float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
+  size_t i = tid;
+  for (; i + 3 * nthreads < nvec; i += 4 * nthreads) {
+    float4 a = xv[i], b = xv[i + nthreads], c = xv[i + 2 * nthreads], d = xv[i + 3 * nthreads];
+    m0 = fmaxf(m0, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    m1 = fmaxf(m1, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+    m2 = fmaxf(m2, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
+    m3 = fmaxf(m3, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+  }
+  for (; i < nvec; i += nthreads) {
+    float4 a = xv[i];
+    m0 = fmaxf(m0, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+  }
+  for (size_t j = nvec * 4 + tid; j < n; j += nthreads) m1 = fmaxf(m1, fabsf(x[j]));
+  float m = wave_max(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3)));
+  __shared__ float part[kThreads / kWave];
+  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
+  if (lane == 0) part[w] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float r = part[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / kWave; ++k) r = fmaxf(r, part[k]);
+    atomicMax(amax_bits, __float_as_uint(r));
+  }
+}
+
+__global__ void k_scale(const float* __restrict__ amax, float qmax, float* __restrict__ scale) {
+  const float a = *amax;
+  *scale = (a > 0.0f) ? __fdiv_rn(qmax, a) : 1.0f;
+}
+
+// One element of quant_int: binary32 multiply, round half to even, symmetric
+// clamp; NaN becomes 0.
+__device__ __forceinline__ int quant1(float x, float s, float lim) {
+  const float r = rintf(__fmul_rn(x, s));
+  const float c = fminf(fmaxf(r, -lim), lim);
+  return (r != r) ? 0 : (int)c;
+}
+
+__device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
+  return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) |
+         ((uint32_t)(d & 0xFF) << 24);
+}
+__device__ __forceinline__ uint32_t pack2_i16(int a, int b) {
+  return (uint32_t)(a & 0xFFFF) | ((uint32_t)(b & 0xFFFF) << 16);
+}
+
+// Flat conversion, 8 elements per thread and step: two 16-byte loads, one 8-byte
+// (int8) or 16-byte (int16) store.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void k_quantize_flat(const float* __restrict__ x, size_t n,
+                                                            const float* __restrict__ scale,
+                                                            void* __restrict__ qv) {
+  const float s = *scale;
+  const float lim = BITS == 8 ? 127.0f : 32767.0f;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const size_t nvec = n / 8;
+  const float4* xv = reinterpret_cast<const float4*>(x);
+  for (size_t i = tid; i < nvec; i += nthreads) {
+    const float4 a = xv[2 * i], b = xv[2 * i + 1];
+    const int q0 = quant1(a.x, s, lim), q1 = quant1(a.y, s, lim), q2 = quant1(a.z, s, lim),
+              q3 = quant1(a.w, s, lim), q4 = quant1(b.x, s, lim), q5 = quant1(b.y, s, lim),
+              q6 = quant1(b.z, s, lim), q7 = quant1(b.w, s, lim);
+    if (BITS == 8) {
+      uint2 o;
+      o.x = pack4_i8(q0, q1, q2, q3);
+      o.y = pack4_i8(q4, q5, q6, q7);
+      reinterpret_cast<uint2*>(qv)[i] = o;
+    } else {
+      uint4 o;
+      o.x = pack2_i16(q0, q1);
+      o.y = pack2_i16(q2, q3);
+      o.z = pack2_i16(q4, q5);
+      o.w = pack2_i16(q6, q7);
+      reinterpret_cast<uint4*>(qv)[i] = o;
+    }
+  }
+  for (size_t j = nvec * 8 + tid; j < n; j += nthreads) {
+    const int q = quant1(x[j], s, lim);
+    if (BITS == 8) reinterpret_cast<int8_t*>(qv)[j] = (int8_t)q;
+    else reinterpret_cast<int16_t*>(qv)[j] = (int16_t)q;
+  }
+}
+
+// Row-wise conversion that also produces sum_c q[r][c]: one wavefront per row.
+template <int BITS, bool VEC>
+__global__ __launch_bounds__(kThreads) void k_quantize_rows(const float* __restrict__ x, size_t rows,
+                                                            size_t cols, const float* __restrict__ scale,
+                                                            void* __restrict__ qv,
+                                                            int32_t* __restrict__ rowsum) {
+  const float s = *scale;
+  const float lim = BITS == 8 ? 127.0f : 32767.0f;
+  const int lane = threadIdx.x % kWave;
+  const size_t wave = (size_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+  const size_t nwaves = (size_t)gridDim.x * (kThreads / kWave);
+  for (size_t r = wave; r < rows; r += nwaves) {
+    const float* xr = x + r * cols;
+    int sum = 0;
+    if (VEC) {  // cols % 8 == 0 and 16-byte aligned rows
+      const float4* xv = reinterpret_cast<const float4*>(xr);
+      for (size_t i = lane; i < cols / 8; i += kWave) {
+        const float4 a = xv[2 * i], b = xv[2 * i + 1];
+        const int q0 = quant1(a.x, s, lim), q1 = quant1(a.y, s, lim), q2 = quant1(a.z, s, lim),
+                  q3 = quant1(a.w, s, lim), q4 = quant1(b.x, s, lim), q5 = quant1(b.y, s, lim),
+                  q6 = quant1(b.z, s, lim), q7 = quant1(b.w, s, lim);
+        sum += q0 + q1 + q2 + q3 + q4 + q5 + q6 + q7;
+        if (BITS == 8) {
+          uint2 o;
+          o.x = pack4_i8(q0, q1, q2, q3);
+          o.y = pack4_i8(q4, q5, q6, q7);
+          reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(qv) + r * cols)[i] = o;
+        } else {
+          uint4 o;
+          o.x = pack2_i16(q0, q1);
+          o.y = pack2_i16(q2, q3);
+          o.z = pack2_i16(q4, q5);
+          o.w = pack2_i16(q6, q7);
+          reinterpret_cast<uint4*>(reinterpret_cast<int16_t*>(qv) + r * cols)[i] = o;
+        }
+      }
+    } else {
+      for (size_t c = lane; c < cols; c += kWave) {
+        const int q = quant1(xr[c], s, lim);
+        sum += q;
+        if (BITS == 8) reinterpret_cast<int8_t*>(qv)[r * cols + c] = (int8_t)q;
+        else reinterpret_cast<int16_t*>(qv)[r * cols + c] = (int16_t)q;
+      }
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) rowsum[r] = sum;
+  }
+}
+
+unsigned grid_for(size_t work_items, size_t per_block, unsigned cap) {
+  size_t g = (work_items + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (unsigned)g;
+}
+
+}  // namespace
+
+int launch_absmax(const float* x, size_t n, float* amax, hipStream_t s) {
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(1), 0, s, reinterpret_cast<uint32_t*>(amax), 0u);
+  // 16 floats per thread and pass; cap the grid at 8 blocks per compute unit
+  const unsigned grid = grid_for(n, (size_t)kThreads * 16, 2048);
+  hipLaunchKernelGGL(k_absmax, dim3(grid), dim3(kThreads), 0, s, x, n, reinterpret_cast<uint32_t*>(amax));
+  return check_hip(hipGetLastError());
+}
+
+int launch_scale(const float* amax, int bits, float* scale, hipStream_t s) {
+  hipLaunchKernelGGL(k_scale, dim3(1), dim3(1), 0, s, amax, (float)qmax_of(bits), scale);
+  return check_hip(hipGetLastError());
+}
+
+int launch_quantize(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                    void* q, int32_t* rowsum, hipStream_t s) {
+  if (rowsum == nullptr) {
+    const size_t n = rows * cols;
+    const unsigned grid = grid_for(n, (size_t)kThreads * 8, 4096);
+    if (bits == 8)
+      hipLaunchKernelGGL(k_quantize_flat<8>, dim3(grid), dim3(kThreads), 0, s, x, n, scale, q);
+    else
+      hipLaunchKernelGGL(k_quantize_flat<16>, dim3(grid), dim3(kThreads), 0, s, x, n, scale, q);
+  } else {
+    const bool vec = (cols % 8 == 0);
+    const unsigned grid = grid_for(rows, kThreads / kWave, 4096);
+    if (bits == 8) {
+      if (vec) hipLaunchKernelGGL((k_quantize_rows<8, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, q, rowsum);
+      else hipLaunchKernelGGL((k_quantize_rows<8, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, q, rowsum);
+    } else {
+      if (vec) hipLaunchKernelGGL((k_quantize_rows<16, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, q, rowsum);
+      else hipLaunchKernelGGL((k_quantize_rows<16, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, q, rowsum);
+    }
+  }
+  return check_hip(hipGetLastError());
+}
+
+}  // namespace mq
