@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized matrix-product path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch that is
+already resident in HBM: abs-max and quant_int of the activations, dot'_int on
+the int8 matrix cores with the dequantize + bias + ReLU epilogue, re-quantization
+of the intermediate, the second product (arxiv 1805.12096, Sections 4.2-4.3).
+The default workload is the Transformer-base FFN block in int8 at M = 8192
+tokens (the paper's GPU batch size, Section 2.3; widths from Table 1).  Parameter
+preparation is memoized (Section 4.3) and therefore outside the timed region.
+
+Prints ONE JSON line.  `value` is useful integer operations (2 M N K per
+product) per second for the whole step.  Beside it: the roofline position of
+the longest-running kernel (durations measured here with HIP events on the
+launch stream), the greedy output-layer workload (tokens/s, GB/s), the int16
+Transformer-big FFN, and the CPU oracle timed on this host on a bounded sample
+of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
+# None until measured for the kernel/workload in question.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extras", action="store_true", help="skip the output-layer and int16 side workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the workload the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1805_12096_amd as mq
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    mq.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    QT = {8: torch.int8, 16: torch.int16}
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    def time_events(fn, iters, warm):
+        """Average duration of fn in microseconds, HIP events on the launch stream."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    def graphed(fn):
+        """Capture fn into a HIP graph; returns a replay callable (or fn itself)."""
+        if args.no_graph:
+            return fn
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
+    # ------------------------------------------------------------ FFN workloads
+    class FFN:
+        def __init__(self, c, bits):
+            self.bits = bits
+            self.A = to_dev(c["A"])
+            self.M, self.d = self.A.shape
+            self.f = c["W1t"].shape[0]
+            self.p1 = mq.prepare_weight(to_dev(c["W1t"]), bits)
+            self.p2 = mq.prepare_weight(to_dev(c["W2t"]), bits)
+            self.b1, self.b2 = to_dev(c["b1"]), to_dev(c["b2"])
+            M, d, f = self.M, self.d, self.f
+            self.s1 = torch.empty(1, dtype=torch.float32, device=dev)
+            self.s2 = torch.empty(1, dtype=torch.float32, device=dev)
+            self.hmax = torch.zeros(1, dtype=torch.float32, device=dev)
+            self.q1 = torch.empty((M, d), dtype=QT[bits], device=dev)
+            self.q2 = torch.empty((M, f), dtype=QT[bits], device=dev)
+            self.r1 = torch.empty(M, dtype=torch.int32, device=dev) if bits == 16 else None
+            self.r2 = torch.empty(M, dtype=torch.int32, device=dev) if bits == 16 else None
+            self.H = torch.empty((M, f), dtype=torch.float32, device=dev)
+            self.Y = torch.empty((M, d), dtype=torch.float32, device=dev)
+            self.ops = 2 * (2 * M * d * f)
+
+        # the individual launches, so each can be timed alone
+        def k_absmax(self):
+            mq.mq_absmax_f32(self.A, self.A.numel(), self.s1)
+
+        def k_scale1(self):
+            mq.mq_scale_from_amax(self.s1, self.bits, self.s1)
+
+        def k_quant1(self):
+            mq.mq_quantize_f32(self.A, self.M, self.d, self.bits, self.s1, self.q1, self.r1)
+
+        def k_gemm1(self):
+            mq.mq_gemm_dequant(self.q1, self.r1, self.p1.packed, self.bits, self.M, self.f, self.d, self.s1,
+                               self.p1.scale, self.b1, True, self.H, self.hmax)
+
+        def k_scale2(self):
+            mq.mq_scale_from_amax(self.hmax, self.bits, self.s2)
+
+        def k_quant2(self):
+            mq.mq_quantize_f32(self.H, self.M, self.f, self.bits, self.s2, self.q2, self.r2)
+
+        def k_gemm2(self):
+            mq.mq_gemm_dequant(self.q2, self.r2, self.p2.packed, self.bits, self.M, self.d, self.f, self.s2,
+                               self.p2.scale, self.b2, False, self.Y, None)
+
+        def step(self):
+            self.k_absmax()
+            self.k_scale1()
+            self.k_quant1()
+            self.hmax.zero_()
+            self.k_gemm1()
+            self.k_scale2()
+            self.k_quant2()
+            self.k_gemm2()
+
+        def kernel_table(self):
+            """name -> (callable, algorithmic HBM bytes, integer ops issued on the matrix cores)."""
+            M, d, f, e = self.M, self.d, self.f, self.bits // 8
+            mfma_mult = 4 if self.bits == 16 else 1       # int16 = four int8 products
+            return {
+                "absmax(A)": (self.k_absmax, 4 * M * d, 0),
+                "quant_int(A)": (self.k_quant1, 4 * M * d + e * M * d, 0),
+                "gemm1+bias+relu+amax": (self.k_gemm1, e * M * d + e * d * f + 4 * M * f, 2 * M * d * f * mfma_mult),
+                "quant_int(H)": (self.k_quant2, 4 * M * f + e * M * f, 0),
+                "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, 2 * M * d * f * mfma_mult),
+            }
+
+    def run_ffn(c, bits, steps, warmup, name):
+        w = FFN(c, bits)
+        w.step()
+        torch.cuda.synchronize()
+        replay = graphed(w.step)
+        us = time_events(replay, steps, warmup)
+        per_kernel = {}
+        for kname, (fn, nbytes, mops) in w.kernel_table().items():
+            kus = time_events(fn, max(20, steps // 4), 5)
+            per_kernel[kname] = {"us": round(kus, 2), "alg_bytes": nbytes, "GBps": round(nbytes / kus / 1e3, 1),
+                                 "mfma_TOPS": round(mops / kus / 1e6, 1)}
+        return w, us, per_kernel
+
+    # ----------------------------------------------------------------- config 2
+    c2 = workloads.config2()
+    w2, us2, pk2 = run_ffn(c2, 8, args.steps, args.warmup, "ffn-base-int8")
+    tops2 = w2.ops / us2 / 1e6
+
+    dom = max(pk2, key=lambda k: pk2[k]["us"])
+    dk = pk2[dom]
+    hbm_frac = dk["GBps"] / PEAK_HBM_GBS
+    mfma_frac = dk["mfma_TOPS"] / PEAK_INT8_TOPS
+    # the roof that binds this kernel at its algorithmic traffic / op count
+    t_hbm = dk["alg_bytes"] / (PEAK_HBM_GBS * 1e3)
+    t_mfma = (dk["mfma_TOPS"] * dk["us"]) / PEAK_INT8_TOPS
+    if t_hbm >= t_mfma:
+        roofline = {"bound": "hbm", "achieved": dk["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(hbm_frac, 4)}
+    else:
+        roofline = {"bound": "mfma", "achieved": dk["mfma_TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                    "frac": round(mfma_frac, 4)}
+    roofline.update({"kernel": dom, "us": dk["us"], "traffic": MEASURED_TRAFFIC.get(dom)})
+
+    result = {
+        "metric": "int8 GEMM TOPS (useful 2MNK ops of the FFN block / step time)",
+        "value": round(tops2, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us2 / 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "transformer-base FFN int8: [8192x512]x[512x2048]+bias+ReLU, requantize, "
+                               "[8192x2048]x[2048x512]+bias; per-tensor abs-max scales",
+                   "M": w2.M, "d": w2.d, "ffn": w2.f, "graph": not args.no_graph},
+        "pct_int8_mfma_peak": round(100 * tops2 / PEAK_INT8_TOPS, 2),
+        "roofline": roofline,
+        "kernels": pk2,
+    }
+
+    # ------------------------------------------------------------------- extras
+    if not args.no_extras:
+        extras = {}
+        # greedy output layer (one decode step, 300 sentences, 36000-word tied embedding)
+        c3 = workloads.config3()
+        Hd = to_dev(c3["Hd"])
+        M, d = Hd.shape
+        V = c3["E"].shape[0]
+        pe = mq.prepare_weight(to_dev(c3["E"]), 8)
+        s = torch.empty(1, dtype=torch.float32, device=dev)
+        q = torch.empty((M, d), dtype=torch.int8, device=dev)
+        nws = mq.mq_argmax_ws_bytes(M, V)
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        tok = torch.empty(M, dtype=torch.int32, device=dev)
+        val = torch.empty(M, dtype=torch.float32, device=dev)
+
+        def out_step():
+            mq.mq_absmax_f32(Hd, Hd.numel(), s)
+            mq.mq_scale_from_amax(s, 8, s)
+            mq.mq_quantize_f32(Hd, M, d, 8, s, q, None)
+            mq.mq_gemm_argmax(q, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
+
+        out_step()
+        us3 = time_events(graphed(out_step), args.steps, args.warmup)
+        us3k = time_events(lambda: mq.mq_gemm_argmax(q, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws),
+                           args.steps, args.warmup)
+        alg3 = V * d + 4 * M * d + 8 * M
+        extras["output_layer_argmax"] = {
+            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, fused arg-max, cache-warm",
+            "us_per_step": round(us3, 2), "tokens_per_s": round(M / us3 * 1e6, 0),
+            "GBps_alg": round(alg3 / us3 / 1e3, 1), "TOPS": round(2 * M * V * d / us3 / 1e6, 1),
+            "gemm_argmax_us": round(us3k, 2)}
+        # int16 Transformer-big FFN
+        c4 = workloads.config4()
+        w4, us4, pk4 = run_ffn(c4, 16, max(10, args.steps // 10), max(3, args.warmup // 5), "ffn-big-int16")
+        extras["ffn_big_int16"] = {
+            "workload": "[8192x1024]x[1024x4096]+bias+ReLU, requantize, [8192x4096]x[4096x1024]+bias, int16",
+            "us_per_step": round(us4, 1), "TOPS_useful": round(w4.ops / us4 / 1e6, 1),
+            "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / us4 / 1e6 / PEAK_INT8_TOPS, 2),
+            "kernels": pk4}
+        del w4
+        result["extras"] = extras
+
+    # ------------------------------------------------------------- CPU baseline
+    if not args.no_cpu:
+        import oracle
+        rows = min(args.cpu_rows, c2["A"].shape[0])
+        A = c2["A"][:rows]
+        qW1, sW1 = oracle.quant_int_absmax(c2["W1t"], 8)      # memoized, not timed
+        qW2, sW2 = oracle.quant_int_absmax(c2["W2t"], 8)
+        t0 = time.perf_counter()
+        qA, sA = oracle.quant_int_absmax(A, 8)
+        Hh = oracle.dequant_bias(oracle.dot_int(qA, qW1), sA, sW1, c2["b1"], True)
+        qH, sH = oracle.quant_int_absmax(Hh, 8)
+        oracle.dequant_bias(oracle.dot_int(qH, qW2), sH, sW2, c2["b2"], False)
+        dt = time.perf_counter() - t0
+        ops = 2 * (2 * rows * w2.d * w2.f)
+        result["cpu_baseline"] = {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "seconds": round(dt, 2),
+                                  "sample": f"first {rows} of {w2.M} token rows of the same FFN workload, "
+                                            "weights pre-quantized (memoized)"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -298,9 +298,21 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm(const Params p) {
       }
   }
   if (EPI == kEpiDequant && p.out_amax != nullptr) {
+    // block-wide maximum, then at most one atomic per block; the running
+    // maximum only grows, so a block that cannot raise it skips the atomic.
+    __shared__ float wave_amax[WM * WN];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
-    if (lane == 0) atomicMax(reinterpret_cast<unsigned*>(p.out_amax), __float_as_uint(local_amax));
+    if (lane == 0) wave_amax[wave] = local_amax;
+    __syncthreads();
+    if (tid == 0) {
+      float m = wave_amax[0];
+#pragma unroll
+      for (int w = 1; w < WM * WN; ++w) m = fmaxf(m, wave_amax[w]);
+      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+      const unsigned bits = __float_as_uint(m);
+      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+    }
   }
 }
 
