@@ -69,6 +69,15 @@ const char* mq_status_string(int status);
  * library (0 if none). */
 int mq_last_hip_error(void);
 
+/* Tuning knob for measurements in the spirit of the paper's auto-tuner (Section
+ * 4.4: alternative implementations are timed per shape and the fastest is
+ * kept).  variant 0 (default) lets the library choose the tile configuration of
+ * the product kernels from the problem shape; 1..4 force one configuration for
+ * every following product of this process (results are identical, only speed
+ * changes; a variant that does not exist for the operand width makes the
+ * product calls return MQ_ERR_UNSUPPORTED).  Not thread safe. */
+int mq_set_gemm_variant(int variant);
+
 /* ---- quant_int (Section 4.2) -------------------------------------------- */
 
 /* amax[0] = max_i |x[i]| over n floats (NaNs skipped).  The paper uses fixed
@@ -87,6 +96,17 @@ int mq_scale_from_amax(const float* amax, int bits, float* scale, void* stream);
  * product needs it (see mq_gemm_i32). */
 int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                     void* q, int32_t* rowsum, void* stream);
+
+/* quant_int straight into the packed layout of mq_prepare_weight (the packed
+ * layout is the same for both operands of dot'_int): packed receives
+ * mq_packed_bytes(bits, rows, cols) bytes, padding included; for bits == 16 the
+ * row sums the product needs are stored inside the buffer.  This is the fast
+ * path for activations: the packed product kernels stream such a buffer into
+ * LDS with linear copies.  x: device float [rows x cols]; scale: device float[1];
+ * packed: device, 16-byte aligned.  mq_unpack_weight(packed, bits, rows, cols, q)
+ * recovers the plain row-major integers. */
+int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                         void* packed, void* stream);
 
 /* ---- memoized quant_int(B^T) (Section 4.3) ------------------------------ */
 
@@ -134,6 +154,16 @@ int mq_gemm_i32(const void* qA, const int32_t* rowsumA, const void* packedW, int
 int mq_gemm_dequant(const void* qA, const int32_t* rowsumA, const void* packedW, int bits,
                     size_t M, size_t N, size_t K, const float* sA, const float* sW,
                     const float* bias, int relu, float* Y, float* out_amax, void* stream);
+
+/* The same two products with the activations packed by mq_quantize_pack_f32
+ * (packedA: [M x K], same bits as packedW).  Results are identical to the
+ * row-major calls; these are the fast kernels (direct-to-LDS loads of both
+ * operands, several K steps in flight). */
+int mq_gemm_i32_packed(const void* packedA, const void* packedW, int bits, size_t M, size_t N, size_t K,
+                       int32_t* C, void* stream);
+int mq_gemm_dequant_packed(const void* packedA, const void* packedW, int bits, size_t M, size_t N, size_t K,
+                           const float* sA, const float* sW, const float* bias, int relu, float* Y,
+                           float* out_amax, void* stream);
 
 /* ---- greedy output layer (Section 2.3) ---------------------------------- */
 

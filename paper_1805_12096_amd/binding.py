@@ -16,10 +16,10 @@ import torch
 
 __all__ = [
     "MqError", "lib_path", "load_library", "exported_symbols",
-    "mq_version", "mq_status_string", "mq_last_hip_error",
-    "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_packed_bytes",
+    "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
+    "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32",
     "PreparedWeight", "prepare_weight",
 ]
 
@@ -46,9 +46,10 @@ def lib_path() -> str:
 
 def exported_symbols():
     """Names include/mq.h declares; used by the CPU-only load test."""
-    return ["mq_version", "mq_status_string", "mq_last_hip_error", "mq_absmax_f32",
-            "mq_scale_from_amax", "mq_quantize_f32", "mq_packed_bytes", "mq_prepare_weight",
-            "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_argmax_ws_bytes",
+    return ["mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant", "mq_absmax_f32",
+            "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
+            "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
+            "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
             "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32"]
 
 
@@ -66,9 +67,13 @@ def load_library():
     lib.mq_status_string.restype = ctypes.c_char_p
     lib.mq_status_string.argtypes = [ci]
     lib.mq_last_hip_error.restype = ci
+    lib.mq_set_gemm_variant.argtypes = [ci]
     lib.mq_absmax_f32.argtypes = [vp, sz, vp, vp]
     lib.mq_scale_from_amax.argtypes = [vp, ci, vp, vp]
     lib.mq_quantize_f32.argtypes = [vp, sz, sz, ci, vp, vp, vp, vp]
+    lib.mq_quantize_pack_f32.argtypes = [vp, sz, sz, ci, vp, vp, vp]
+    lib.mq_gemm_i32_packed.argtypes = [vp, vp, ci, sz, sz, sz, vp, vp]
+    lib.mq_gemm_dequant_packed.argtypes = [vp, vp, ci, sz, sz, sz, vp, vp, vp, ci, vp, vp, vp]
     lib.mq_packed_bytes.restype = sz
     lib.mq_packed_bytes.argtypes = [ci, sz, sz]
     lib.mq_prepare_weight.argtypes = [vp, ci, sz, sz, ci, vp, vp, vp, vp]
@@ -123,6 +128,10 @@ def mq_last_hip_error() -> int:
     return int(load_library().mq_last_hip_error())
 
 
+def mq_set_gemm_variant(variant: int) -> None:
+    _check(load_library().mq_set_gemm_variant(int(variant)), "mq_set_gemm_variant")
+
+
 def mq_absmax_f32(x, n, amax, stream=None):
     _check(load_library().mq_absmax_f32(_p(x), n, _p(amax), _stream(stream)), "mq_absmax_f32")
 
@@ -134,6 +143,22 @@ def mq_scale_from_amax(amax, bits, scale, stream=None):
 def mq_quantize_f32(x, rows, cols, bits, scale, q, rowsum=None, stream=None):
     _check(load_library().mq_quantize_f32(_p(x), rows, cols, bits, _p(scale), _p(q), _p(rowsum),
                                           _stream(stream)), "mq_quantize_f32")
+
+
+def mq_quantize_pack_f32(x, rows, cols, bits, scale, packed, stream=None):
+    _check(load_library().mq_quantize_pack_f32(_p(x), rows, cols, bits, _p(scale), _p(packed), _stream(stream)),
+           "mq_quantize_pack_f32")
+
+
+def mq_gemm_i32_packed(packedA, packedW, bits, M, N, K, C, stream=None):
+    _check(load_library().mq_gemm_i32_packed(_p(packedA), _p(packedW), bits, M, N, K, _p(C), _stream(stream)),
+           "mq_gemm_i32_packed")
+
+
+def mq_gemm_dequant_packed(packedA, packedW, bits, M, N, K, sA, sW, bias, relu, Y, out_amax=None, stream=None):
+    _check(load_library().mq_gemm_dequant_packed(_p(packedA), _p(packedW), bits, M, N, K, _p(sA), _p(sW), _p(bias),
+                                                 int(relu), _p(Y), _p(out_amax), _stream(stream)),
+           "mq_gemm_dequant_packed")
 
 
 def mq_packed_bytes(bits, N, K) -> int:

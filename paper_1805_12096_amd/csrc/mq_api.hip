@@ -73,6 +73,12 @@ const char* mq_status_string(int status) {
 
 int mq_last_hip_error(void) { return g_last_hip_error; }
 
+int mq_set_gemm_variant(int variant) {
+  if (variant < 0 || variant > 8) return MQ_ERR_UNSUPPORTED;
+  set_forced_variant(variant);
+  return MQ_OK;
+}
+
 int mq_absmax_f32(const float* x, size_t n, float* amax, void* stream) {
   if (x == nullptr || amax == nullptr) return MQ_ERR_NULL;
   if (n == 0 || n > kMaxElems) return MQ_ERR_SHAPE;
@@ -96,6 +102,15 @@ int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const fl
   if (!aligned(x, 16) || !aligned(q, 16) || !aligned(scale, 4)) return MQ_ERR_ALIGN;
   if (rowsum != nullptr && !aligned(rowsum, 4)) return MQ_ERR_ALIGN;
   return launch_quantize(x, rows, cols, bits, scale, q, rowsum, as_stream(stream));
+}
+
+int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                         void* packed, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (x == nullptr || scale == nullptr || packed == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(1, rows, cols)) return MQ_ERR_SHAPE;
+  if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(scale, 4)) return MQ_ERR_ALIGN;
+  return launch_quantize_pack(x, rows, cols, bits, scale, packed, as_stream(stream));
 }
 
 size_t mq_packed_bytes(int bits, size_t N, size_t K) {
@@ -155,6 +170,33 @@ int mq_gemm_dequant(const void* qA, const int32_t* rowsumA, const void* packedW,
   a.qA = qA; a.rowsumA = rowsumA; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
   a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
   return launch_gemm(a, kEpiDequant, as_stream(stream));
+}
+
+int mq_gemm_i32_packed(const void* packedA, const void* packedW, int bits, size_t M, size_t N, size_t K,
+                       int32_t* C, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (packedA == nullptr || packedW == nullptr || C == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(C, 4)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K; a.C = C;
+  return launch_gemm_packed(a, kEpiRaw, as_stream(stream));
+}
+
+int mq_gemm_dequant_packed(const void* packedA, const void* packedW, int bits, size_t M, size_t N, size_t K,
+                           const float* sA, const float* sW, const float* bias, int relu, float* Y,
+                           float* out_amax, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || Y == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(Y, 4))
+    return MQ_ERR_ALIGN;
+  if ((bias != nullptr && !aligned(bias, 4)) || (out_amax != nullptr && !aligned(out_amax, 4)))
+    return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
+  return launch_gemm_packed(a, kEpiDequant, as_stream(stream));
 }
 
 size_t mq_argmax_ws_bytes(size_t M, size_t N) {

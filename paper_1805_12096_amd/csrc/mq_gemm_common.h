@@ -1,0 +1,107 @@
+// Pieces shared by the product kernels: register vector types, kernel
+// parameters, the block-to-tile map and the store epilogues.
+#pragma once
+
+#include "mq_internal.h"
+
+namespace mq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));   // 16 bytes as a first-class register value
+
+struct Params {
+  const uint8_t* qA;        // row-major activations (row-major kernel) or packed activations (packed kernel)
+  const int32_t* rowsumA;   // 16 bit: sum_k qA[m][k]
+  const uint8_t* packedW;
+  unsigned M, N, K;
+  unsigned tiles_n;
+  int32_t* C;
+  const float* sA;
+  const float* sW;
+  const float* bias;
+  int relu;
+  float* Y;
+  float* out_amax;
+  unsigned long long* keys;
+  // re-quantizing epilogue (packed kernel only)
+  const float* s_out;       // multiplier of the output tensor
+  uint8_t* packed_out;      // output written as packed 8-bit activations [M x N]
+};
+
+__device__ __forceinline__ v4i as_v4i(u4 v) { return __builtin_bit_cast(v4i, v); }
+
+// Block index -> tile.  Workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2; giving every XCD one contiguous run of tiles (n fastest)
+// makes the blocks that run together on an XCD share A row panels and the
+// parameter in that XCD's L2.
+__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned total) {
+  const unsigned q = total / 8, r = total % 8, x = bid % 8, idx = bid / 8;
+  return x * q + (x < r ? x : r) + idx;
+}
+
+// Raw-sum and dequantizing epilogues for a wave that holds TM x TN result tiles
+// of the 32x32 MFMA with (a = activations, b = parameter): register r of lane l
+// is element (i, j) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32) of its tile, i
+// along M, j along N.  wave_m0 / wave_n0 are the wave's first row / column.
+// 16-bit sums are recombined here from the three partial accumulators:
+//   acc = 2^16 hh + 2^8 mid + ll + 128 (rowsum[m] + colsum[n]) - 16384 K  (mod 2^32).
+template <int BITS, int TM, int TN, int NACC, int EPI, int NWAVES>
+__device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const Params& p, unsigned wave_m0,
+                                               unsigned wave_n0, const int32_t* rowsum, const int32_t* colsum) {
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  const int lj = lane % 32, lh = lane / 32;
+  float u = 0.f, local_amax = 0.f;
+  if (EPI == kEpiDequant) u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+#pragma unroll
+  for (int nt = 0; nt < TN; ++nt) {
+    const unsigned n = wave_n0 + nt * 32 + lj;
+    const bool n_ok = n < p.N;
+    float bias = 0.f;
+    unsigned corr_n = 0;
+    if (EPI == kEpiDequant && p.bias != nullptr && n_ok) bias = p.bias[n];
+    if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const unsigned m = wave_m0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
+        if (!n_ok || m >= p.M) continue;
+        int v;
+        if constexpr (BITS == 8) {
+          v = acc[mt][nt][0][r];
+        } else {
+          const unsigned t = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
+                             (unsigned)acc[mt][nt][NACC - 1][r] + 128u * (unsigned)rowsum[m] + corr_n;
+          v = (int)t;
+        }
+        if (EPI == kEpiRaw) {
+          p.C[(size_t)m * p.N + n] = v;
+        } else {
+          float y = fmaf((float)v, u, bias);
+          if (p.relu) y = (y > 0.0f) ? y : 0.0f;
+          p.Y[(size_t)m * p.N + n] = y;
+          local_amax = fmaxf(local_amax, fabsf(y));
+        }
+      }
+  }
+  if (EPI == kEpiDequant && p.out_amax != nullptr) {
+    // block-wide maximum, then at most one atomic per block; the running
+    // maximum only grows, so a block that cannot raise it skips the atomic.
+    __shared__ float wave_amax[NWAVES];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
+    if (lane == 0) wave_amax[wave] = local_amax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float m = wave_amax[0];
+#pragma unroll
+      for (int w = 1; w < NWAVES; ++w) m = fmaxf(m, wave_amax[w]);
+      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+      const unsigned bits = __float_as_uint(m);
+      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+    }
+  }
+}
+
+}  // namespace mq

@@ -1,0 +1,222 @@
+// dot'_int with BOTH operands in fragment order (arxiv 1805.12096, Section 4.3:
+// the product takes two already quantized tensors, each contiguous along K).
+// Because activations and parameter share one packed layout, a stage of either
+// is a run of 1 KB fragments that the CDNA4 direct-to-LDS load
+// (global_load_lds_dwordx4: 64 lanes x 16 bytes land at consecutive LDS
+// addresses) copies without touching registers.  That makes a deep software
+// pipeline affordable: S stages of LDS, S - 1 of them in flight, which is what
+// it takes to cover HBM latency with one or two waves per SIMD.
+//
+// Synchronisation per K step (one barrier):
+//   wait until this wave's loads of stage kt have landed (vmcnt counts the
+//   younger stages that may still be in flight), barrier (now everybody's have,
+//   and everybody is done reading stage kt - 1), issue the loads that overwrite
+//   stage kt - 1's slot, multiply stage kt.
+// The compiler does not track LDS written by these loads, so the waits are
+// explicit and the barrier is fenced against compile-time motion by hand.
+#include "mq_gemm_common.h"
+
+namespace mq {
+
+namespace {
+
+enum PackedEpilogue { kPRaw = 0, kPDequant = 1 };
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+  // s_waitcnt with only vmcnt active: vmcnt is split over bits [3:0] and [15:14]
+  switch (n) {
+#define MQ_CASE(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | 0x0F70); break;
+    MQ_CASE(0) MQ_CASE(1) MQ_CASE(2) MQ_CASE(3) MQ_CASE(4) MQ_CASE(5) MQ_CASE(6) MQ_CASE(7) MQ_CASE(8)
+    MQ_CASE(9) MQ_CASE(10) MQ_CASE(11) MQ_CASE(12) MQ_CASE(13) MQ_CASE(14) MQ_CASE(15) MQ_CASE(16)
+    MQ_CASE(18) MQ_CASE(20) MQ_CASE(24)
+#undef MQ_CASE
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
+}
+
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI>
+__global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
+  constexpr int NW = WM * WN;
+  constexpr int NPL = BITS == 16 ? 2 : 1;
+  constexpr int TM = BM / WM / 32;
+  constexpr int TN = BN / WN / 32;
+  constexpr int NACC = BITS == 16 ? 3 : 1;
+  constexpr int FPB = 2 * NPL;                 // fragments per 32-row block and 64-element K step
+  constexpr int FA = (BM / 32) * FPB;          // fragments of A per stage
+  constexpr int FB = (BN / 32) * FPB;
+  constexpr int L = (FA + FB) / NW;            // direct-to-LDS loads per wave and stage
+  constexpr int STAGE = (FA + FB) * kFragBytes;
+  static_assert((FA + FB) % NW == 0, "stage must divide evenly over the waves");
+  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile shape");
+  static_assert(S >= 2 && (S - 2) * L <= 24, "wait_vmcnt table");
+
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid % 64;
+  const int wave = tid / 64;
+  const int wm = wave / WN, wn = wave % WN;
+  const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
+  const PackedDims dA(BITS, p.M, p.K), dW(BITS, p.N, p.K);
+  const unsigned KT = (unsigned)(dA.Kp / 64);
+
+  // Source of this wave's j-th load of a stage: fragment i = wave * L + j of the
+  // stage; fragments [0, FA) are A's, the rest the parameter's.  Row blocks past
+  // the end are clamped (their results are masked in the epilogue).
+  const uint8_t* src[L];
+#pragma unroll
+  for (int j = 0; j < L; ++j) {
+    const int i = wave * L + j;
+    if (i < FA) {
+      size_t blk = (size_t)m0 / 32 + i / FPB;
+      if (blk >= dA.nblocks) blk = dA.nblocks - 1;
+      src[j] = p.qA + dA.frag_offset(blk, 0) + (size_t)(i % FPB) * kFragBytes + lane * 16;
+    } else {
+      size_t blk = (size_t)n0 / 32 + (i - FA) / FPB;
+      if (blk >= dW.nblocks) blk = dW.nblocks - 1;
+      src[j] = p.packedW + dW.frag_offset(blk, 0) + (size_t)((i - FA) % FPB) * kFragBytes + lane * 16;
+    }
+  }
+  auto issue = [&](unsigned kt) {
+    uint8_t* dst = smem + (kt % S) * STAGE + wave * L * kFragBytes;
+#pragma unroll
+    for (int j = 0; j < L; ++j)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[j] + (size_t)kt * (FPB * kFragBytes)),
+          (__attribute__((address_space(3))) void*)(dst + j * kFragBytes), 16, 0, 0);
+  };
+
+  v16i acc[TM][TN][NACC];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int c = 0; c < NACC; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][b][c][r] = 0;
+
+  auto compute = [&](unsigned kt) {
+    const uint8_t* st = smem + (kt % S) * STAGE + lane * 16;
+    const uint8_t* a_base = st + (wm * TM) * FPB * kFragBytes;
+    const uint8_t* b_base = st + (FA + (wn * TN) * FPB) * kFragBytes;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      v4i af[TM][NPL], bf[TN][NPL];
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int pl = 0; pl < NPL; ++pl)
+          af[mt][pl] = as_v4i(*reinterpret_cast<const u4*>(a_base + ((mt * 2 + ks) * NPL + pl) * kFragBytes));
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+        for (int pl = 0; pl < NPL; ++pl)
+          bf[nt][pl] = as_v4i(*reinterpret_cast<const u4*>(b_base + ((nt * 2 + ks) * NPL + pl) * kFragBytes));
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < TN; ++nt) {
+          if constexpr (BITS == 8) {
+            acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt][0], bf[nt][0], acc[mt][nt][0], 0, 0, 0);
+          } else {
+            const v4i ah = af[mt][0], al = af[mt][NPL - 1];
+            const v4i bh = bf[nt][0], bl = bf[nt][NPL - 1];
+            acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bh, acc[mt][nt][0], 0, 0, 0);
+            acc[mt][nt][NACC - 2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bl, acc[mt][nt][NACC - 2], 0, 0, 0);
+            acc[mt][nt][NACC - 2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bh, acc[mt][nt][NACC - 2], 0, 0, 0);
+            acc[mt][nt][NACC - 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bl, acc[mt][nt][NACC - 1], 0, 0, 0);
+          }
+        }
+    }
+  };
+
+#pragma unroll
+  for (int st = 0; st < S - 1; ++st)
+    if ((unsigned)st < KT) issue(st);
+  for (unsigned kt = 0; kt < KT; ++kt) {
+    // stages kt + 1 .. kt + S - 2 may stay in flight; in the tail fewer exist, so wait for all
+    if (kt + S - 2 < KT) wait_vmcnt((S - 2) * L);
+    else wait_vmcnt(0);
+    block_barrier();
+    if (kt + S - 1 < KT) issue(kt + S - 1);
+    compute(kt);
+  }
+
+  const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
+  const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
+  store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
+      acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum);
+}
+
+template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI>
+int launch_pp(const GemmArgs& a, hipStream_t s) {
+  constexpr int NPL = BITS == 16 ? 2 : 1;
+  constexpr size_t smem = (size_t)S * ((BM / 32) + (BN / 32)) * 2 * NPL * kFragBytes;
+  static_assert(smem <= 160 * 1024, "LDS budget");
+  Params p{};
+  p.qA = static_cast<const uint8_t*>(a.qA);
+  p.packedW = static_cast<const uint8_t*>(a.packedW);
+  p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
+  const size_t tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  p.tiles_n = (unsigned)tiles_n;
+  p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
+  auto kern = k_gemm_pp<BITS, BM, BN, WM, WN, S, EPI>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    if (rc != MQ_OK) return rc;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), smem, s, p);
+  return check_hip(hipGetLastError());
+}
+
+template <int BITS, int EPI>
+int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
+  if constexpr (BITS == 8) {
+    switch (variant) {
+      case 1: return launch_pp<8, 256, 256, 2, 4, 4, EPI>(a, s);   // 8 waves, 128x64 per wave
+      case 2: return launch_pp<8, 256, 256, 2, 2, 4, EPI>(a, s);   // 4 waves, 128x128 per wave
+      case 3: return launch_pp<8, 128, 128, 2, 2, 4, EPI>(a, s);   // small tile, 64x64 per wave
+      case 4: return launch_pp<8, 256, 128, 4, 2, 4, EPI>(a, s);   // 8 waves, 64x64 per wave
+      default: return MQ_ERR_UNSUPPORTED;
+    }
+  } else {
+    switch (variant) {
+      case 1: return launch_pp<16, 256, 128, 4, 2, 3, EPI>(a, s);  // 8 waves, 64x64 per wave
+      case 2: return launch_pp<16, 128, 128, 2, 2, 4, EPI>(a, s);  // 4 waves, 64x64 per wave
+      case 3: return launch_pp<16, 128, 128, 4, 2, 4, EPI>(a, s);  // 8 waves, 32x64 per wave
+      default: return MQ_ERR_UNSUPPORTED;
+    }
+  }
+}
+
+}  // namespace
+
+int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
+  int v = forced_variant();
+  if (v <= 0) {
+    if (a.bits == 16) {
+      v = 1;
+    } else {
+      const size_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+      v = t256 >= 200 ? 1 : 3;
+    }
+  }
+  if (a.bits == 8)
+    return epi == kEpiRaw ? launch_pp_variant<8, kPRaw>(a, v, s) : launch_pp_variant<8, kPDequant>(a, v, s);
+  return epi == kEpiRaw ? launch_pp_variant<16, kPRaw>(a, v, s) : launch_pp_variant<16, kPDequant>(a, v, s);
+}
+
+}  // namespace mq

@@ -75,6 +75,12 @@ struct GemmArgs {
   unsigned long long* keys;  // [M] packed (sum, ~index) maxima
 };
 int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
+void set_forced_variant(int v);
+int forced_variant();
+// Both operands packed (activations from launch_quantize_pack); a.qA is the packed activation buffer.
+int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s);
+int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                         void* packed, hipStream_t s);
 int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
 int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* sA, const float* sW,
                          int32_t* tok, float* maxlogit, hipStream_t s);

@@ -212,3 +212,93 @@ int launch_quantize(const float* x, size_t rows, size_t cols, int bits, const fl
 }
 
 }  // namespace mq
+
+// ---------------------------------------------------------------------------
+// quant_int straight into the fragment order the product kernels read (the
+// same layout as a prepared parameter, see PackedDims): the activations then
+// reach LDS by plain linear copies.  Eight lanes share a row and walk along K
+// four floats at a time, so reads are whole 128-byte lines and each store
+// instruction writes two 128-byte runs.
+namespace mq {
+namespace {
+
+template <int BITS, bool VEC>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restrict__ x, size_t rows,
+                                                            size_t cols, const float* __restrict__ scale,
+                                                            uint8_t* __restrict__ packed, unsigned ksplit) {
+  const PackedDims d(BITS, rows, cols);
+  const float s = *scale;
+  const float lim = BITS == 8 ? 127.0f : 32767.0f;
+  const int lane = threadIdx.x % kWave;
+  const int sub = lane % 8;                       // which 4 floats of a 32-element fragment row
+  const size_t wave = (size_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+  const size_t nwaves = (size_t)gridDim.x * (kThreads / kWave);
+  const size_t row_groups = d.Np / 8;
+  const size_t per = (d.kfrags + ksplit - 1) / ksplit;   // fragments along K per work item
+  for (size_t item = wave; item < row_groups * ksplit; item += nwaves) {
+    const size_t rg = item / ksplit, part = item % ksplit;
+    const size_t row = rg * 8 + lane / 8;
+    const size_t kb_end = (part + 1) * per < d.kfrags ? (part + 1) * per : d.kfrags;
+    const size_t nb = row / kFragRows;
+    const int slot = (int)(row % kFragRows) + 32 * (sub / 4);
+    int sum = 0;
+    for (size_t kb = part * per; kb < kb_end; ++kb) {
+      const size_t k = kb * kFragK + 4 * sub;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < rows) {
+        if (VEC) {
+          if (k < cols) v = *reinterpret_cast<const float4*>(x + row * cols + k);
+        } else {
+          const float* xr = x + row * cols;
+          if (k + 0 < cols) v.x = xr[k + 0];
+          if (k + 1 < cols) v.y = xr[k + 1];
+          if (k + 2 < cols) v.z = xr[k + 2];
+          if (k + 3 < cols) v.w = xr[k + 3];
+        }
+      }
+      const int q0 = quant1(v.x, s, lim), q1 = quant1(v.y, s, lim), q2 = quant1(v.z, s, lim),
+                q3 = quant1(v.w, s, lim);
+      uint8_t* dst = packed + d.frag_offset(nb, kb) + (size_t)slot * 16 + 4 * (sub % 4);
+      if (BITS == 8) {
+        *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0, q1, q2, q3);
+      } else {
+        sum += q0 + q1 + q2 + q3;
+        // q = 256 h + l + 128: high bytes, and low bytes with the top bit flipped
+        *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0 >> 8, q1 >> 8, q2 >> 8, q3 >> 8);
+        *reinterpret_cast<uint32_t*>(dst + kFragBytes) = pack4_i8(q0, q1, q2, q3) ^ 0x80808080u;
+      }
+    }
+    if (BITS == 16) {  // ksplit is 1 for 16 bit: one wave owns whole rows
+      sum += __shfl_xor(sum, 1, kWave);
+      sum += __shfl_xor(sum, 2, kWave);
+      sum += __shfl_xor(sum, 4, kWave);
+      if (sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
+    }
+  }
+}
+
+}  // namespace
+
+int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
+                         void* packed, hipStream_t s) {
+  const PackedDims d(bits, rows, cols);
+  const size_t row_groups = d.Np / 8;
+  // 8-bit: split K so that even a 300-row batch fills the chip; 16-bit keeps rows whole for the row sums
+  unsigned ksplit = 1;
+  if (bits == 8) {
+    while (row_groups * ksplit < 2048 && ksplit * 4 <= d.kfrags) ksplit *= 2;
+  }
+  const unsigned grid = grid_for(row_groups * ksplit, kThreads / kWave, 8192);
+  uint8_t* p = static_cast<uint8_t*>(packed);
+  const bool vec = cols % 4 == 0;
+  if (bits == 8) {
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<8, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+    else hipLaunchKernelGGL((k_quantize_pack<8, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+  } else {
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<16, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+    else hipLaunchKernelGGL((k_quantize_pack<16, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+  }
+  return check_hip(hipGetLastError());
+}
+
+}  // namespace mq

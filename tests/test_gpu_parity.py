@@ -380,3 +380,96 @@ def test_config5_decode_step_products():
     o = oracle.greedy_output_layer(out["Hd"], out["E"])
     tok, val = gpu_greedy(out["Hd"], out["E"])
     assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
+
+
+# ------------------------------------------- packed activations + packed product
+
+def gpu_quantize_pack(x, bits, scale=None):
+    xd = dev(x)
+    rows, cols = xd.shape
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    if scale is None:
+        mq.mq_absmax_f32(xd, xd.numel(), s)
+        mq.mq_scale_from_amax(s, bits, s)
+    else:
+        s.fill_(float(scale))
+    packed = torch.full((mq.mq_packed_bytes(bits, rows, cols),), 0x5A, dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_pack_f32(xd, rows, cols, bits, s, packed)
+    return packed, s
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+@pytest.mark.parametrize("shape", [(1, 1), (3, 7), (33, 65), (300, 512), (70, 2048), (257, 100), (8, 4099)])
+def test_quantize_pack_matches_oracle(bits, shape):
+    rng = np.random.default_rng(shape[0] * 131 + shape[1] + bits)
+    x = rng.standard_normal(shape, dtype=np.float32) * np.float32(1.3)
+    packed, s = gpu_quantize_pack(x, bits)
+    oq, os_ = oracle.quant_int_absmax(x, bits)
+    assert host(s)[0] == os_
+    q = torch.empty(shape, dtype=QT[bits], device=DEV)
+    mq.mq_unpack_weight(packed, bits, shape[0], shape[1], q)
+    assert np.array_equal(host(q), oq)
+    if bits == 16:
+        Mp = (shape[0] + 31) // 32 * 32
+        sums = host(packed)[-4 * Mp:].view(np.int32)
+        assert np.array_equal(sums[:shape[0]], oq.astype(np.int64).sum(1).astype(np.int32))
+
+
+def gpu_dot_int_packed(qA, qB):
+    bits = 8 if qA.dtype == np.int8 else 16
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    pw = mq.prepare_weight(dev(qB.astype(np.float32)), bits, transposed=True, scale=one)
+    pa, _ = gpu_quantize_pack(qA.astype(np.float32), bits, scale=1.0)
+    M, K = qA.shape
+    N = qB.shape[0]
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    mq.mq_gemm_i32_packed(pa, pw.packed, bits, M, N, K, C)
+    return host(C)
+
+
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4], 16: [0, 1, 2, 3]}
+
+
+@pytest.mark.parametrize("dtype", [np.int8, np.int16])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (33, 31, 65), (129, 130, 80), (300, 70, 512), (260, 517, 96),
+                                   (2, 1000, 2048), (513, 258, 320)])
+def test_gemm_packed_full_range_all_variants(dtype, M, N, K):
+    rng = np.random.default_rng(M * 1000003 + N * 1009 + K + 1)
+    lim = 127 if dtype == np.int8 else 32767
+    qA = rng.integers(-lim, lim + 1, size=(M, K)).astype(dtype)
+    qB = rng.integers(-lim, lim + 1, size=(N, K)).astype(dtype)
+    want = oracle.dot_int(qA, qB)
+    try:
+        for v in PACKED_VARIANTS[8 if dtype == np.int8 else 16]:
+            mq.mq_set_gemm_variant(v)
+            assert np.array_equal(gpu_dot_int_packed(qA, qB), want), f"variant {v}"
+    finally:
+        mq.mq_set_gemm_variant(0)
+
+
+def test_gemm_packed_one_hot_layout():
+    # one non-zero per operand: checks where the direct-to-LDS copy puts each lane's bytes
+    for dtype in (np.int8, np.int16):
+        M, N, K = 70, 90, 200
+        for (m, n, k) in [(0, 0, 0), (69, 89, 199), (31, 32, 15), (32, 31, 16), (40, 64, 63), (5, 70, 64), (63, 33, 127)]:
+            qA = np.zeros((M, K), dtype=dtype)
+            qB = np.zeros((N, K), dtype=dtype)
+            qA[m, k] = 3
+            qB[n, k] = -5
+            want = np.zeros((M, N), dtype=np.int32)
+            want[m, n] = -15
+            assert np.array_equal(gpu_dot_int_packed(qA, qB), want), (dtype, m, n, k)
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+@pytest.mark.parametrize("M,N,K,relu", [(37, 53, 129, True), (300, 512, 512, True), (520, 300, 1024, False)])
+def test_linear_pipeline_packed(bits, M, N, K, relu):
+    p = workloads.random_problem(M + N + K + bits + 3, M, N, K)
+    o = oracle.linear(p["A"], p["Wt"], bits, p["bias"], relu)
+    pw = mq.prepare_weight(dev(p["Wt"]), bits)
+    pa, s = gpu_quantize_pack(p["A"], bits)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    mq.mq_gemm_dequant_packed(pa, pw.packed, bits, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, am)
+    assert np.array_equal(host(Y), o["Y"])
+    assert host(am)[0] == np.abs(o["Y"]).max()
