@@ -115,10 +115,9 @@ def main():
             self.s1 = torch.empty(1, dtype=torch.float32, device=dev)
             self.s2 = torch.empty(1, dtype=torch.float32, device=dev)
             self.hmax = torch.zeros(1, dtype=torch.float32, device=dev)
-            self.q1 = torch.empty((M, d), dtype=QT[bits], device=dev)
-            self.q2 = torch.empty((M, f), dtype=QT[bits], device=dev)
-            self.r1 = torch.empty(M, dtype=torch.int32, device=dev) if bits == 16 else None
-            self.r2 = torch.empty(M, dtype=torch.int32, device=dev) if bits == 16 else None
+            # activations live in the packed (fragment-order) layout the product kernels stream
+            self.q1 = torch.empty(mq.mq_packed_bytes(bits, M, d), dtype=torch.uint8, device=dev)
+            self.q2 = torch.empty(mq.mq_packed_bytes(bits, M, f), dtype=torch.uint8, device=dev)
             self.H = torch.empty((M, f), dtype=torch.float32, device=dev)
             self.Y = torch.empty((M, d), dtype=torch.float32, device=dev)
             self.ops = 2 * (2 * M * d * f)
@@ -131,21 +130,21 @@ def main():
             mq.mq_scale_from_amax(self.s1, self.bits, self.s1)
 
         def k_quant1(self):
-            mq.mq_quantize_f32(self.A, self.M, self.d, self.bits, self.s1, self.q1, self.r1)
+            mq.mq_quantize_pack_f32(self.A, self.M, self.d, self.bits, self.s1, self.q1)
 
         def k_gemm1(self):
-            mq.mq_gemm_dequant(self.q1, self.r1, self.p1.packed, self.bits, self.M, self.f, self.d, self.s1,
-                               self.p1.scale, self.b1, True, self.H, self.hmax)
+            mq.mq_gemm_dequant_packed(self.q1, self.p1.packed, self.bits, self.M, self.f, self.d, self.s1,
+                                      self.p1.scale, self.b1, True, self.H, self.hmax)
 
         def k_scale2(self):
             mq.mq_scale_from_amax(self.hmax, self.bits, self.s2)
 
         def k_quant2(self):
-            mq.mq_quantize_f32(self.H, self.M, self.f, self.bits, self.s2, self.q2, self.r2)
+            mq.mq_quantize_pack_f32(self.H, self.M, self.f, self.bits, self.s2, self.q2)
 
         def k_gemm2(self):
-            mq.mq_gemm_dequant(self.q2, self.r2, self.p2.packed, self.bits, self.M, self.d, self.f, self.s2,
-                               self.p2.scale, self.b2, False, self.Y, None)
+            mq.mq_gemm_dequant_packed(self.q2, self.p2.packed, self.bits, self.M, self.d, self.f, self.s2,
+                                      self.p2.scale, self.b2, False, self.Y, None)
 
         def step(self):
             self.k_absmax()

@@ -63,8 +63,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm(const Params p) {
   const int lane = tid % 64;
   const int wave = tid / 64;
   const int wm = wave / WN, wn = wave % WN;
-  const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
-  const unsigned tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  unsigned tile_m, tile_n;
+  tile_coords(p.tiles_m, p.tiles_n, BM >= 1024 ? 1u : 1024u / BM, tile_m, tile_n);
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
   const PackedDims d(BITS, p.N, p.K);
   const unsigned KT = (unsigned)(d.Kp / kBK);
@@ -315,6 +315,7 @@ int launch_tiles(const GemmArgs& a, hipStream_t s) {
   p.packedW = static_cast<const uint8_t*>(a.packedW);
   p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
   const size_t tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y;
   p.out_amax = a.out_amax; p.keys = a.keys; p.s_out = nullptr; p.packed_out = nullptr;

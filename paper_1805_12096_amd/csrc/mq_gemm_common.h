@@ -15,7 +15,7 @@ struct Params {
   const int32_t* rowsumA;   // 16 bit: sum_k qA[m][k]
   const uint8_t* packedW;
   unsigned M, N, K;
-  unsigned tiles_n;
+  unsigned tiles_m, tiles_n;
   int32_t* C;
   const float* sA;
   const float* sW;
@@ -38,6 +38,21 @@ __device__ __forceinline__ v4i as_v4i(u4 v) { return __builtin_bit_cast(v4i, v);
 __device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned total) {
   const unsigned q = total / 8, r = total % 8, x = bid % 8, idx = bid / 8;
   return x * q + (x < r ? x : r) + idx;
+}
+
+// Tile coordinates of a block.  After the XCD remap, consecutive tile numbers
+// walk down a band of GM tile rows before moving to the next tile column, so
+// the ~32 blocks resident on one XCD cover a GM x (32 / GM) patch of the
+// result: each A row panel and each parameter panel they stream is then shared
+// by several of them in that XCD's L2 instead of being fetched once per block.
+__device__ __forceinline__ void tile_coords(unsigned tiles_m, unsigned tiles_n, unsigned GM, unsigned& tile_m,
+                                            unsigned& tile_n) {
+  const unsigned t = xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned band = t / (GM * tiles_n), in_band = t % (GM * tiles_n);
+  const unsigned first = band * GM;
+  const unsigned rows = tiles_m - first < GM ? tiles_m - first : GM;
+  tile_m = first + in_band % rows;
+  tile_n = in_band / rows;
 }
 
 // Raw-sum and dequantizing epilogues for a wave that holds TM x TN result tiles

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   constexpr int STAGE = (FA + FB) * kFragBytes;
   static_assert((FA + FB) % NW == 0, "stage must divide evenly over the waves");
   static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile shape");
-  static_assert(S >= 2 && (S - 2) * L <= 24, "wait_vmcnt table");
+  static_assert(S >= 3 && (S - 2) * L <= 24, "wait_vmcnt table");
 
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
@@ -62,8 +62,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   const int lane = tid % 64;
   const int wave = tid / 64;
   const int wm = wave / WN, wn = wave % WN;
-  const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
-  const unsigned tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  unsigned tile_m, tile_n;
+  tile_coords(p.tiles_m, p.tiles_n, BM >= 1024 ? 1u : 1024u / BM, tile_m, tile_n);
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
   const PackedDims dA(BITS, p.M, p.K), dW(BITS, p.N, p.K);
   const unsigned KT = (unsigned)(dA.Kp / 64);
@@ -104,51 +104,83 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[a][b][c][r] = 0;
 
-  auto compute = [&](unsigned kt) {
-    const uint8_t* st = smem + (kt % S) * STAGE + lane * 16;
+  // Fragment registers of one 32-element K slice: TM operand fragments of A
+  // and TN of the parameter (times two byte planes for 16 bit).
+  struct Frags {
+    v4i a[TM][NPL];
+    v4i b[TN][NPL];
+  };
+  constexpr int PR = BITS == 16 ? 4 : 1;          // 8-bit products per result tile and K slice
+  constexpr int R = (TM + TN) * NPL;              // fragment reads per K slice
+  constexpr int NM = TM * TN * PR;                // MFMAs per K slice
+  static_assert(R <= NM, "one fragment read is paired with each of the first R MFMAs");
+
+  // r-th fragment read of slice ks of a stage, in the order the MFMAs need them:
+  // A block 0, every parameter block, then the other A blocks.
+  auto read_one = [&](Frags& F, const uint8_t* st, int ks, int r) {
     const uint8_t* a_base = st + (wm * TM) * FPB * kFragBytes;
     const uint8_t* b_base = st + (FA + (wn * TN) * FPB) * kFragBytes;
+    if (r < NPL) {
+      F.a[0][r] = as_v4i(*reinterpret_cast<const u4*>(a_base + (ks * NPL + r) * kFragBytes));
+    } else if (r < NPL + TN * NPL) {
+      const int q = r - NPL, nt = q / NPL, pl = q % NPL;
+      F.b[nt][pl] = as_v4i(*reinterpret_cast<const u4*>(b_base + ((nt * 2 + ks) * NPL + pl) * kFragBytes));
+    } else {
+      const int q = r - NPL - TN * NPL, mt = 1 + q / NPL, pl = q % NPL;
+      F.a[mt][pl] = as_v4i(*reinterpret_cast<const u4*>(a_base + ((mt * 2 + ks) * NPL + pl) * kFragBytes));
+    }
+  };
+  // i-th MFMA of a slice.  The product index is the slowest, so consecutive
+  // instructions never accumulate into the same registers.
+  auto mfma_one = [&](const Frags& F, int i) {
+    const int pr = i / (TM * TN), mt = (i / TN) % TM, nt = i % TN;
+    if constexpr (BITS == 8) {
+      acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][0], F.b[nt][0], acc[mt][nt][0], 0, 0, 0);
+    } else {
+      const int pa = (pr == 0 || pr == 1) ? 0 : NPL - 1;          // hh, hl, lh, ll
+      const int pb = (pr == 0 || pr == 2) ? 0 : NPL - 1;
+      const int ai = pr == 0 ? 0 : (pr == 3 ? NACC - 1 : NACC - 2);
+      acc[mt][nt][ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][pa], F.b[nt][pb], acc[mt][nt][ai], 0, 0, 0);
+    }
+  };
+  // Multiply one slice out of `cur` while the reads of the next slice fill `nxt`:
+  // one LDS read rides behind each of the first R MFMAs, and the scheduling
+  // fences keep the compiler from regrouping them, so LDS latency hides behind
+  // the matrix pipeline instead of stalling it.
+  auto slice = [&](const Frags& cur, Frags& nxt, const uint8_t* next_stage, int next_ks) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      v4i af[TM][NPL], bf[TN][NPL];
-#pragma unroll
-      for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-        for (int pl = 0; pl < NPL; ++pl)
-          af[mt][pl] = as_v4i(*reinterpret_cast<const u4*>(a_base + ((mt * 2 + ks) * NPL + pl) * kFragBytes));
-#pragma unroll
-      for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-        for (int pl = 0; pl < NPL; ++pl)
-          bf[nt][pl] = as_v4i(*reinterpret_cast<const u4*>(b_base + ((nt * 2 + ks) * NPL + pl) * kFragBytes));
-#pragma unroll
-      for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < TN; ++nt) {
-          if constexpr (BITS == 8) {
-            acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[mt][0], bf[nt][0], acc[mt][nt][0], 0, 0, 0);
-          } else {
-            const v4i ah = af[mt][0], al = af[mt][NPL - 1];
-            const v4i bh = bf[nt][0], bl = bf[nt][NPL - 1];
-            acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bh, acc[mt][nt][0], 0, 0, 0);
-            acc[mt][nt][NACC - 2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bl, acc[mt][nt][NACC - 2], 0, 0, 0);
-            acc[mt][nt][NACC - 2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bh, acc[mt][nt][NACC - 2], 0, 0, 0);
-            acc[mt][nt][NACC - 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bl, acc[mt][nt][NACC - 1], 0, 0, 0);
-          }
-        }
+    for (int i = 0; i < NM; ++i) {
+      mfma_one(cur, i);
+      if (i < R) read_one(nxt, next_stage, next_ks, i);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
+  Frags f0, f1;
 #pragma unroll
   for (int st = 0; st < S - 1; ++st)
     if ((unsigned)st < KT) issue(st);
+  if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
+  else wait_vmcnt(0);
+  block_barrier();
+#pragma unroll
+  for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
+
   for (unsigned kt = 0; kt < KT; ++kt) {
-    // stages kt + 1 .. kt + S - 2 may stay in flight; in the tail fewer exist, so wait for all
-    if (kt + S - 2 < KT) wait_vmcnt((S - 2) * L);
+    const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
+    const uint8_t* nxt = smem + ((kt + 1) % S) * STAGE + lane * 16;
+    // slice 0 of stage kt; slice 1's fragments stream in behind it
+    slice(f0, f1, cur, 1);
+    // stage kt + 1 must have landed for everybody before its first fragments are
+    // read; stages kt + 2 .. kt + S - 2 may stay in flight (none in the tail)
+    if (kt + S - 2 < KT) wait_vmcnt((S - 3) * L);
     else wait_vmcnt(0);
     block_barrier();
+    // every wave is past slice 0 of stage kt, so stage kt - 1's slot is free
     if (kt + S - 1 < KT) issue(kt + S - 1);
-    compute(kt);
+    // slice 1 of stage kt; slice 0 of stage kt + 1 streams in behind it (after
+    // the last stage this reads a finished slot again and the result is unused)
+    slice(f1, f0, nxt, 0);
   }
 
   const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
@@ -167,6 +199,7 @@ int launch_pp(const GemmArgs& a, hipStream_t s) {
   p.packedW = static_cast<const uint8_t*>(a.packedW);
   p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
   const size_t tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
@@ -194,9 +227,9 @@ int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
     }
   } else {
     switch (variant) {
-      case 1: return launch_pp<16, 256, 128, 4, 2, 3, EPI>(a, s);  // 8 waves, 64x64 per wave
+      case 1: return launch_pp<16, 128, 128, 4, 2, 4, EPI>(a, s);  // 8 waves, 32x64 per wave
       case 2: return launch_pp<16, 128, 128, 2, 2, 4, EPI>(a, s);  // 4 waves, 64x64 per wave
-      case 3: return launch_pp<16, 128, 128, 4, 2, 4, EPI>(a, s);  // 8 waves, 32x64 per wave
+      case 3: return launch_pp<16, 64, 128, 2, 2, 4, EPI>(a, s);   // small tile, 32x64 per wave
       default: return MQ_ERR_UNSUPPORTED;
     }
   }

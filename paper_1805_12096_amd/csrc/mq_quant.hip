@@ -54,7 +54,9 @@ __global__ __launch_bounds__(kThreads) void k_absmax(const float* __restrict__ x
     float r = part[0];
 #pragma unroll
     for (int k = 1; k < kThreads / kWave; ++k) r = fmaxf(r, part[k]);
-    atomicMax(amax_bits, __float_as_uint(r));
+    // the running maximum only grows: a block that cannot raise it skips the (serialising) atomic
+    const uint32_t bits = __float_as_uint(r);
+    if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, bits);
   }
 }
 

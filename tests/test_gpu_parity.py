@@ -305,17 +305,25 @@ def gpu_ffn(c, bits):
     p1 = mq.prepare_weight(dev(c["W1t"]), bits)
     p2 = mq.prepare_weight(dev(c["W2t"]), bits)
     b1, b2 = dev(c["b1"]), dev(c["b2"])
-    q1, s1, r1 = gpu_quantize(A, bits)
+    s1 = torch.empty(1, dtype=torch.float32, device=DEV)
+    mq.mq_absmax_f32(A, A.numel(), s1)
+    mq.mq_scale_from_amax(s1, bits, s1)
+    p_q1 = torch.empty(mq.mq_packed_bytes(bits, M, d), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_pack_f32(A, M, d, bits, s1, p_q1)
     H = torch.empty((M, f), dtype=torch.float32, device=DEV)
     hmax = torch.zeros(1, dtype=torch.float32, device=DEV)
-    mq.mq_gemm_dequant(q1, r1, p1.packed, bits, M, f, d, s1, p1.scale, b1, True, H, hmax)
+    mq.mq_gemm_dequant_packed(p_q1, p1.packed, bits, M, f, d, s1, p1.scale, b1, True, H, hmax)
     s2 = torch.empty(1, dtype=torch.float32, device=DEV)
     mq.mq_scale_from_amax(hmax, bits, s2)
-    q2 = torch.empty((M, f), dtype=QT[bits], device=DEV)
-    r2 = torch.empty(M, dtype=torch.int32, device=DEV) if bits == 16 else None
-    mq.mq_quantize_f32(H, M, f, bits, s2, q2, r2)
+    p_q2 = torch.empty(mq.mq_packed_bytes(bits, M, f), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_pack_f32(H, M, f, bits, s2, p_q2)
     Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
-    mq.mq_gemm_dequant(q2, r2, p2.packed, bits, M, d, f, s2, p2.scale, b2, False, Y, None)
+    mq.mq_gemm_dequant_packed(p_q2, p2.packed, bits, M, d, f, s2, p2.scale, b2, False, Y, None)
+    # plain row-major views of the packed activations, for comparison with the oracle
+    q1 = torch.empty((M, d), dtype=QT[bits], device=DEV)
+    q2 = torch.empty((M, f), dtype=QT[bits], device=DEV)
+    mq.mq_unpack_weight(p_q1, bits, M, d, q1)
+    mq.mq_unpack_weight(p_q2, bits, M, f, q2)
     return {"q1": q1, "H": H, "s2": s2, "q2": q2, "Y": Y}
 
 
