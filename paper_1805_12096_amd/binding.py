@@ -19,7 +19,7 @@ __all__ = [
     "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32",
     "PreparedWeight", "prepare_weight",
 ]
 
@@ -50,7 +50,7 @@ def exported_symbols():
             "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
-            "mq_gemm_argmax", "mq_linear_ws_bytes", "mq_linear_f32"]
+            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32"]
 
 
 def load_library():
@@ -83,6 +83,7 @@ def load_library():
     lib.mq_argmax_ws_bytes.restype = sz
     lib.mq_argmax_ws_bytes.argtypes = [sz, sz]
     lib.mq_gemm_argmax.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.mq_gemm_argmax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_linear_ws_bytes.restype = sz
     lib.mq_linear_ws_bytes.argtypes = [ci, sz, sz]
     lib.mq_linear_f32.argtypes = [vp, sz, sz, vp, vp, vp, ci, sz, vp, ci, vp, vp, vp, sz, vp]
@@ -192,6 +193,12 @@ def mq_argmax_ws_bytes(M, N) -> int:
 def mq_gemm_argmax(qA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, ws_bytes, stream=None):
     _check(load_library().mq_gemm_argmax(_p(qA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(tok), _p(maxlogit),
                                          _p(ws), ws_bytes, _stream(stream)), "mq_gemm_argmax")
+
+
+def mq_gemm_argmax_packed(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, ws_bytes, stream=None):
+    _check(load_library().mq_gemm_argmax_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(tok),
+                                                _p(maxlogit), _p(ws), ws_bytes, _stream(stream)),
+           "mq_gemm_argmax_packed")
 
 
 def mq_linear_ws_bytes(bits, M, K) -> int:

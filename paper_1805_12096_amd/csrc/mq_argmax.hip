@@ -1,0 +1,297 @@
+// Greedy output layer of a decode step (arxiv 1805.12096, Section 2.3: with beam
+// size 1 no softmax is evaluated, the word with the highest activation wins;
+// Section 2.1: the output matrix is the tied 36 000-entry embedding).
+//
+// Shape of the problem: a few hundred sentences (M) against tens of thousands
+// of vocabulary rows (N) at K = model size.  Per step the whole embedding has to
+// stream through the chip once (N * K bytes) while the M x N logits never need
+// to exist.  So:
+//   * work is cut into units of 16 vocabulary rows (all of K), dealt round-robin
+//     to one workgroup per compute unit; 36 000 rows give 2250 units, 8.8 per CU;
+//   * the matrix instruction is v_mfma_i32_16x16x64_i8 with the embedding as
+//     operand `a` and the hidden states as operand `b`: lane l then holds four
+//     candidate words for ONE sentence (l % 16), so the running maxima are
+//     plain per-lane registers and nothing crosses lanes until the very end;
+//   * the quantized hidden states (M x K, a few 100 KB) are loaded once per
+//     workgroup into REGISTERS as operand fragments, split over the four waves
+//     by 16-sentence tile;
+//   * the packed embedding streams through LDS with direct-to-LDS loads: each
+//     load instruction gathers, for one 64-element K group, the 16 rows of the
+//     unit out of two 32-row fragments, so that LDS receives exactly the
+//     operand image (lane l at byte 16 l); many stages are in flight;
+//   * sums of 8-bit products over K <= 512 stay below 2^23, so (sum << 8 |
+//     255 - stage) is a 32-bit key whose integer maximum is the arg-max with
+//     the earliest stage winning ties: two VALU operations per candidate;
+//   * every workgroup writes one 64-bit (sum, index) key per sentence; a second
+//     small kernel reduces them and decodes.  No atomics, no initialisation.
+// 64-bit keys order by sum first and by smaller index second:
+//   key = (sum ^ 0x80000000) << 32 | (0xFFFFFFFF - n);  0 means "no candidate".
+#include "mq_gemm_common.h"
+
+namespace mq {
+
+namespace {
+
+constexpr int kWaves = 8;             // two per SIMD: one wave's waits hide behind the other's MFMAs
+constexpr int kKG = 8;                // 64-element K groups per unit (K <= 512)
+constexpr int kStages = 10;           // 80 KB of LDS, 8 stages in flight
+constexpr int kMaxBlocks = 1024;      // upper bound on workgroups (columns of the partials array)
+
+__device__ __forceinline__ void wait_vmcnt_n(int n) {
+  switch (n) {
+#define MQ_CASE(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | 0x0F70); break;
+    MQ_CASE(0) MQ_CASE(1) MQ_CASE(2) MQ_CASE(3) MQ_CASE(4) MQ_CASE(5) MQ_CASE(6) MQ_CASE(7) MQ_CASE(8) MQ_CASE(9)
+    MQ_CASE(10) MQ_CASE(12) MQ_CASE(13) MQ_CASE(14) MQ_CASE(15) MQ_CASE(16)
+#undef MQ_CASE
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
+}
+
+struct ArgmaxParams {
+  const uint8_t* packedA;   // hidden states, packed 8 bit [M x K]
+  const uint8_t* packedW;   // embedding, packed 8 bit [N x K]
+  unsigned M, N, K;
+  unsigned long long* partial;   // [M][gridDim.x]
+};
+
+// What lane l feeds to the 16x16x64 MFMA for rows 16 u .. 16 u + 15 of a packed
+// 8-bit operand and K group g (64 elements): K quarter l / 16 of the group lives
+// in fragment 2 g + l / 32, half (l / 16) % 2, row slot (u % 2) 16 + l % 16.
+// The offset splits into a per-lane constant and a wave-uniform part.
+__device__ __forceinline__ unsigned operand16_lane_offset(int lane) {
+  return (unsigned)(lane / 32) * kFragBytes + (unsigned)(((lane / 16) % 2) * 32 + lane % 16) * 16;
+}
+__device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, size_t unit, unsigned g) {
+  return d.frag_offset(unit / 2, 2 * g) + (unit % 2) * 256;
+}
+
+// TPW: 16-sentence tiles per wave (8 * TPW * 16 >= M).
+template <int TPW>
+__global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p) {
+  constexpr int KG = kKG, S = kStages;
+  constexpr int STAGE = KG * kFragBytes;
+  static_assert(KG == kWaves, "one direct-to-LDS load per wave and stage");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const int lane = threadIdx.x % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
+  const unsigned kgroups = (unsigned)(dW.kfrags / 2);          // real K groups (<= KG)
+  const unsigned nunits = (unsigned)(dW.nblocks * 2);          // 16-row units of the (padded) embedding
+  const unsigned first = blockIdx.x, stride = gridDim.x;
+  const unsigned nlocal = first < nunits ? (nunits - first + stride - 1) / stride : 0;
+  const unsigned lane_off = operand16_lane_offset(lane);
+
+  // stage s of the pipeline = this workgroup's s-th unit, all of K; wave w copies K group w
+  // (K shorter than 512: a real group is copied again and its products are zeroed through `hid`)
+  const unsigned my_group = (unsigned)wave < kgroups ? (unsigned)wave : kgroups - 1;
+  const uint8_t* src_lane = p.packedW + lane_off;
+  auto issue = [&](unsigned s) {
+    const size_t unit = (size_t)first + (size_t)s * stride;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src_lane + operand16_uniform_offset(dW, unit, my_group)),
+        (__attribute__((address_space(3))) void*)(smem + (s % S) * STAGE + wave * kFragBytes), 16, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if ((unsigned)s < nlocal) issue(s);
+
+  // hidden-state operands of this wave's sentence tiles: tile t = wave + 8 i covers sentences 16 t .. 16 t + 15
+  v4i hid[TPW][KG];
+  const size_t tiles_avail = dA.nblocks * 2;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    size_t t = (size_t)wave + kWaves * i;
+    if (t >= tiles_avail) t = tiles_avail - 1;   // tile past the end: computed on a copy, never written out
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+      const bool real = (unsigned)g < kgroups;
+      const u4 v = *reinterpret_cast<const u4*>(p.packedA + lane_off + operand16_uniform_offset(dA, t, real ? g : 0));
+      hid[i][g] = real ? as_v4i(v) : v4i{0, 0, 0, 0};
+    }
+  }
+  // vmcnt counts ordinary and direct-to-LDS loads alike: drain everything once (stages 0 .. S-2 included)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+
+  // running maxima, one per accumulator register: (sum << 8) | (255 - stage).  Real sums exceed
+  // -2^23, so a key whose sum field is -2^23 means "no candidate yet".
+  constexpr int kNone = (int)0x80000000;
+  int best[TPW][4];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) best[i][r] = kNone;
+
+  // One stage: the unit's K groups against this wave's sentence tiles into `cur`, while the
+  // maxima are updated from `prev` (the sums of the stage before).  The update's VALU work is
+  // cut into slices that sit between the MFMA groups, so it runs while the matrix pipeline is
+  // busy instead of after it; the scheduling fences keep that order.
+  auto stage = [&](unsigned s, v4i (&cur)[TPW], const v4i (&prev)[TPW]) {
+    if (s == 0) {
+      // drained above
+    } else if (s + S - 2 < nlocal) {
+      wait_vmcnt_n(S - 2);                      // stages s+1 .. s+S-2 may stay in flight (one load each)
+    } else {
+      wait_vmcnt_n(0);
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    // everybody is past stage s - 1, so its slot can be refilled
+    if (s + S - 1 < nlocal) issue(s + S - 1);
+
+    const uint8_t* st = smem + (s % S) * STAGE + lane * 16;
+    v4i e[KG];
+#pragma unroll
+    for (int g = 0; g < KG; ++g) e[g] = as_v4i(*reinterpret_cast<const u4*>(st + g * kFragBytes));
+    const int prev_tag = 256 - (int)s;          // 255 - (s - 1); unused garbage for s == 0 (prev holds "none")
+    constexpr int ITEMS = TPW * 4, PER = (ITEMS + KG - 1) / KG;
+    const v4i zero = {0, 0, 0, 0};
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+#pragma unroll
+      for (int i = 0; i < TPW; ++i)
+        cur[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(e[g], hid[i][g], g == 0 ? zero : cur[i], 0, 0, 0);
+#pragma unroll
+      for (int j = g * PER; j < (g + 1) * PER && j < ITEMS; ++j)
+        best[j / 4][j % 4] = max(best[j / 4][j % 4], (prev[j / 4][j % 4] << 8) | (prev_tag & 255));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // two stages per trip so the two accumulator sets swap roles without copies
+  v4i acc0[TPW], acc1[TPW];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) acc1[i] = v4i{-8388608, -8388608, -8388608, -8388608};   // "none" for stage 0's update
+  for (unsigned s = 0; s < nlocal; s += 2) {
+    stage(s, acc0, acc1);
+    if (s + 1 < nlocal) stage(s + 1, acc1, acc0);
+  }
+  // the last stage's sums are still pending; only a workgroup's last unit can reach past N, where
+  // the rows are padding and must not compete (needs at least two workgroups, which the launcher
+  // guarantees whenever there is more than one unit)
+  if (nlocal > 0) {
+    const unsigned sl = nlocal - 1;
+    const unsigned unit0 = (first + sl * stride) * 16 + 4 * (lane / 16);
+    const int tag = 255 - (int)sl;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int v = (sl % 2 == 0) ? acc0[i][r] : acc1[i][r];
+        if (unit0 + r < p.N) best[i][r] = max(best[i][r], (v << 8) | tag);
+      }
+  }
+
+  // decode the per-register winners, pick the best of the four (smaller word index on ties), merge the
+  // four lane groups that share a sentence, and write one key per sentence
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    unsigned long long key = 0ull;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int sum = best[i][r] >> 8;
+      if (sum != -8388608) {
+        const unsigned s = 255u - (unsigned)(best[i][r] & 255);
+        const unsigned n = (first + s * stride) * 16 + 4 * (lane / 16) + r;
+        const unsigned long long k =
+            ((unsigned long long)((unsigned)sum ^ 0x80000000u) << 32) | (unsigned long long)(0xFFFFFFFFu - n);
+        if (k > key) key = k;
+      }
+    }
+    unsigned long long o = __shfl_xor(key, 16, 64);
+    if (o > key) key = o;
+    o = __shfl_xor(key, 32, 64);
+    if (o > key) key = o;
+    const unsigned m = (wave + kWaves * i) * 16 + lane % 16;
+    if (lane < 16 && m < p.M) p.partial[(size_t)m * gridDim.x + blockIdx.x] = key;
+  }
+}
+
+// One wave per sentence: maximum over the per-workgroup keys, then decode.
+__global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long* __restrict__ partial, unsigned cols,
+                                                       unsigned M, const float* __restrict__ sA,
+                                                       const float* __restrict__ sW, int32_t* __restrict__ tok,
+                                                       float* __restrict__ maxlogit) {
+  const int lane = threadIdx.x % 64;
+  const unsigned m = blockIdx.x * 4 + threadIdx.x / 64;
+  if (m >= M) return;
+  const unsigned long long* row = partial + (size_t)m * cols;
+  unsigned long long key = 0ull;
+  for (unsigned g = lane; g < cols; g += 64) {
+    const unsigned long long k = row[g];
+    if (k > key) key = k;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(key, off, 64);
+    if (o > key) key = o;
+  }
+  if (lane == 0) {
+    const float u = __fdiv_rn(1.0f, __fmul_rn(*sA, *sW));
+    const int best = (int)((unsigned)(key >> 32) ^ 0x80000000u);
+    tok[m] = (int32_t)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+    maxlogit[m] = __fmul_rn((float)best, u);
+  }
+}
+
+template <int TPW>
+int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
+  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes;
+  auto kern = k_argmax_stream<TPW>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    if (rc != MQ_OK) return rc;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), smem, s, p);
+  return check_hip(hipGetLastError());
+}
+
+}  // namespace
+
+size_t argmax_stream_ws_bytes(size_t M) { return (size_t)kMaxBlocks * M * sizeof(unsigned long long); }
+
+// Limits: 3 tiles of 16 sentences per wave; sums must fit 24 bits (127^2 K < 2^23); at most 255 stages per workgroup.
+bool argmax_stream_supported(size_t M, size_t N, size_t K) {
+  return M <= (size_t)kWaves * 3 * 16 && K <= 64 * kKG && N <= (size_t)255 * 256 * 16;
+}
+
+int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                         const float* sW, int32_t* tok, float* maxlogit, void* ws, hipStream_t s) {
+  if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
+  ArgmaxParams p;
+  p.packedA = static_cast<const uint8_t*>(packedA);
+  p.packedW = static_cast<const uint8_t*>(packedW);
+  p.M = (unsigned)M; p.N = (unsigned)N; p.K = (unsigned)K;
+  p.partial = static_cast<unsigned long long*>(ws);
+  const PackedDims dW(8, N, K);
+  static int cus = 0;               // compute units of the device, asked once
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+  }
+  const size_t units = dW.nblocks * 2;
+  unsigned grid = (unsigned)(units < (size_t)cus ? units : (size_t)cus);
+  if (grid > (unsigned)kMaxBlocks) grid = kMaxBlocks;
+  if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
+  const size_t tiles = (M + 15) / 16;
+  const int tpw = (int)((tiles + kWaves - 1) / kWaves);
+  int rc;
+  switch (tpw) {
+    case 1: rc = launch_stream<1>(p, grid, s); break;
+    case 2: rc = launch_stream<2>(p, grid, s); break;
+    default: rc = launch_stream<3>(p, grid, s); break;
+  }
+  if (rc != MQ_OK) return rc;
+  hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, p.partial, grid, (unsigned)M,
+                     sA, sW, tok, maxlogit);
+  return check_hip(hipGetLastError());
+}
+
+}  // namespace mq

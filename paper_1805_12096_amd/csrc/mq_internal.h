@@ -85,4 +85,10 @@ int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
 int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* sA, const float* sW,
                          int32_t* tok, float* maxlogit, hipStream_t s);
 
+// Streaming arg-max product for decode-sized batches (both operands packed, 8 bit).
+size_t argmax_stream_ws_bytes(size_t M);
+bool argmax_stream_supported(size_t M, size_t N, size_t K);
+int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                         const float* sW, int32_t* tok, float* maxlogit, void* ws, hipStream_t s);
+
 }  // namespace mq

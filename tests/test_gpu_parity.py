@@ -481,3 +481,68 @@ def test_linear_pipeline_packed(bits, M, N, K, relu):
     mq.mq_gemm_dequant_packed(pa, pw.packed, bits, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, am)
     assert np.array_equal(host(Y), o["Y"])
     assert host(am)[0] == np.abs(o["Y"]).max()
+
+
+# ------------------------------------------------ decode-step arg-max kernel
+
+def gpu_greedy_packed(Hd, E):
+    pw = mq.prepare_weight(dev(E), 8)
+    pa, s = gpu_quantize_pack(Hd, 8)
+    M, K = Hd.shape
+    N = E.shape[0]
+    nbytes = mq.mq_argmax_ws_bytes(M, N)
+    ws = torch.full((nbytes,), 0xCD, dtype=torch.uint8, device=DEV)     # contents must not matter
+    tok = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+    val = torch.empty(M, dtype=torch.float32, device=DEV)
+    mq.mq_gemm_argmax_packed(pa, pw.packed, M, N, K, s, pw.scale, tok, val, ws, nbytes)
+    return host(tok), host(val)
+
+
+@pytest.mark.parametrize("M,V,d", [(1, 1, 1), (3, 17, 8), (12, 777, 64), (33, 4100, 96), (130, 129, 512), (300, 3000, 512),
+                                   (384, 9000, 192), (97, 20000, 128), (257, 33, 300)])
+def test_greedy_packed_small(M, V, d):
+    c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + 5)
+    o = oracle.greedy_output_layer(c["Hd"], c["E"])
+    tok, val = gpu_greedy_packed(c["Hd"], c["E"])
+    assert np.array_equal(tok, o["tok"])
+    assert np.array_equal(val, o["maxlogit"])
+
+
+def test_greedy_packed_ties_padding_and_limits():
+    c = workloads.config3(M=40, V=9000, d=128, seed_extra=11)
+    Hd, E = c["Hd"].copy(), c["E"].copy()
+    emax = np.abs(E).max()
+    for m, j in [(0, 8999), (7, 5), (39, 4096)]:
+        E[j] = Hd[m] * (emax / np.abs(Hd[m]).max()) * np.float32(0.999)
+    E[3] = E[4096]          # duplicates in other vocabulary blocks, handled by other workgroups
+    E[8990] = E[4096]
+    E[1] = E[8999]
+    o = oracle.greedy_output_layer(Hd, E)
+    assert o["tok"][0] == 1 and o["tok"][7] == 5 and o["tok"][39] == 3
+    tok, val = gpu_greedy_packed(Hd, E)
+    assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
+    tok, val = gpu_greedy_packed(np.zeros((5, 128), dtype=np.float32), E)
+    assert not tok.any() and not val.any()
+    Hneg, Eneg = np.abs(Hd[:4]), -np.abs(E[:70])      # all sums negative: zero padding must never win
+    o = oracle.greedy_output_layer(Hneg, Eneg)
+    tok, val = gpu_greedy_packed(Hneg, Eneg)
+    assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
+    # beyond the kernel's limits the call refuses instead of computing something else
+    pw = mq.prepare_weight(dev(E[:64]), 8)
+    big = np.zeros((385, 128), dtype=np.float32)
+    pa, s = gpu_quantize_pack(big, 8)
+    nbytes = mq.mq_argmax_ws_bytes(385, 64)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    tok_t = torch.empty(385, dtype=torch.int32, device=DEV)
+    val_t = torch.empty(385, dtype=torch.float32, device=DEV)
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_gemm_argmax_packed(pa, pw.packed, 385, 64, 128, s, pw.scale, tok_t, val_t, ws, nbytes)
+    assert e.value.status == 6
+
+
+def test_config3_output_layer_full_packed():
+    c = workloads.config3()
+    o = oracle.greedy_output_layer(c["Hd"], c["E"])
+    tok, val = gpu_greedy_packed(c["Hd"], c["E"])
+    assert np.array_equal(tok, o["tok"])
+    assert np.array_equal(val, o["maxlogit"])
