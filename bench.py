@@ -85,10 +85,10 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
-    def graphed(fn):
-        """Capture fn into a HIP graph; returns a replay callable (or fn itself)."""
+    def graphed(fn, reps=1):
+        """Capture `reps` calls of fn into a HIP graph; returns a replay callable (or a plain loop)."""
         if args.no_graph:
-            return fn
+            return (lambda: [fn() for _ in range(reps)])
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -98,8 +98,14 @@ def main():
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            fn()
+            for _ in range(reps):
+                fn()
         return g.replay
+
+    def time_kernel(fn, reps=10, iters=20):
+        """Average duration of one call of fn (us): `reps` back-to-back copies replayed as one graph, so
+        that host launch overhead does not hide kernels of a few microseconds."""
+        return time_events(graphed(fn, reps), iters, 3) / reps
 
     # ------------------------------------------------------------ FFN workloads
     class FFN:
@@ -121,6 +127,10 @@ def main():
             self.H = torch.empty((M, f), dtype=torch.float32, device=dev)
             self.Y = torch.empty((M, d), dtype=torch.float32, device=dev)
             self.ops = 2 * (2 * M * d * f)
+            self.ws_bytes = mq.mq_ffn_ws_bytes(M, d, f) if bits == 8 else 0
+            self.ws = torch.empty(max(self.ws_bytes, 4096), dtype=torch.uint8, device=dev)
+            self.part_bytes = mq.mq_gemm_amax_ws_bytes(M, f)
+            self.part = torch.empty(self.part_bytes, dtype=torch.uint8, device=dev)
 
         # the individual launches, so each can be timed alone
         def k_absmax(self):
@@ -146,6 +156,10 @@ def main():
             mq.mq_gemm_dequant_packed(self.q2, self.p2.packed, self.bits, self.M, self.d, self.f, self.s2,
                                       self.p2.scale, self.b2, False, self.Y, None)
 
+        def fused_step(self):
+            mq.mq_ffn_i8_f32(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
+                             self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws, self.ws_bytes)
+
         def step(self):
             self.k_absmax()
             self.k_scale1()
@@ -156,35 +170,57 @@ def main():
             self.k_quant2()
             self.k_gemm2()
 
-        def kernel_table(self):
+        # building blocks of the fused step, for per-kernel timing
+        def k_absmax_quant1(self):
+            mq.mq_quantize_absmax_pack_f32(self.A, self.M, self.d, self.bits, self.q1, self.s1, self.ws, 4096)
+
+        def k_gemm1_amax(self):
+            mq.mq_gemm_amax_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1, self.p1.scale,
+                                   self.b1, True, self.part, self.part_bytes)
+
+        def k_gemm1_requant(self):
+            mq.mq_gemm_requant_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1, self.p1.scale,
+                                      self.b1, True, self.part, self.part_bytes, self.s2, self.q2)
+
+        def kernel_table(self, fused):
             """name -> (callable, algorithmic HBM bytes, integer ops issued on the matrix cores)."""
             M, d, f, e = self.M, self.d, self.f, self.bits // 8
-            mfma_mult = 4 if self.bits == 16 else 1       # int16 = four int8 products
+            mm = 2 * M * d * f * (4 if self.bits == 16 else 1)       # int16 = four int8 products
+            if fused:
+                return {
+                    "absmax+quant_int(A) [2 launches]": (self.k_absmax_quant1, 2 * 4 * M * d + e * M * d, 0),
+                    "gemm1 pass 1: bias+relu -> max|H|": (self.k_gemm1_amax, e * M * d + e * d * f, mm),
+                    "gemm1 pass 2: bias+relu -> quant_int(H)": (self.k_gemm1_requant, e * M * d + e * d * f + e * M * f, mm),
+                    "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, mm),
+                }
             return {
                 "absmax(A)": (self.k_absmax, 4 * M * d, 0),
                 "quant_int(A)": (self.k_quant1, 4 * M * d + e * M * d, 0),
-                "gemm1+bias+relu+amax": (self.k_gemm1, e * M * d + e * d * f + 4 * M * f, 2 * M * d * f * mfma_mult),
+                "gemm1+bias+relu+amax": (self.k_gemm1, e * M * d + e * d * f + 4 * M * f, mm),
                 "quant_int(H)": (self.k_quant2, 4 * M * f + e * M * f, 0),
-                "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, 2 * M * d * f * mfma_mult),
+                "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, mm),
             }
 
-    def run_ffn(c, bits, steps, warmup, name):
+    def run_ffn(c, bits, steps, warmup, fused):
         w = FFN(c, bits)
-        w.step()
+        step = w.fused_step if fused else w.step
+        step()
         torch.cuda.synchronize()
-        replay = graphed(w.step)
-        us = time_events(replay, steps, warmup)
+        us = time_events(graphed(step), steps, warmup)
+        if fused:
+            w.step()            # leaves s2 / q2 of the unfused chain in place for the gemm2 timing
         per_kernel = {}
-        for kname, (fn, nbytes, mops) in w.kernel_table().items():
-            kus = time_events(fn, max(20, steps // 4), 5)
+        for kname, (fn, nbytes, mops) in w.kernel_table(fused).items():
+            kus = time_kernel(fn)
             per_kernel[kname] = {"us": round(kus, 2), "alg_bytes": nbytes, "GBps": round(nbytes / kus / 1e3, 1),
                                  "mfma_TOPS": round(mops / kus / 1e6, 1)}
         return w, us, per_kernel
 
     # ----------------------------------------------------------------- config 2
     c2 = workloads.config2()
-    w2, us2, pk2 = run_ffn(c2, 8, args.steps, args.warmup, "ffn-base-int8")
+    w2, us2, pk2 = run_ffn(c2, 8, args.steps, args.warmup, fused=True)
     tops2 = w2.ops / us2 / 1e6
+    us2_chain = time_events(graphed(w2.step), args.steps, args.warmup)     # the same block call by call, H in fp32
 
     dom = max(pk2, key=lambda k: pk2[k]["us"])
     dk = pk2[dom]
@@ -208,7 +244,11 @@ def main():
         "dtype": "i8", "data": "synthetic",
         "config": {"workload": "transformer-base FFN int8: [8192x512]x[512x2048]+bias+ReLU, requantize, "
                                "[8192x2048]x[2048x512]+bias; per-tensor abs-max scales",
-                   "M": w2.M, "d": w2.d, "ffn": w2.f, "graph": not args.no_graph},
+                   "M": w2.M, "d": w2.d, "ffn": w2.f, "graph": not args.no_graph,
+                   "path": "mq_ffn_i8_f32 (5 launches, H never stored in fp32)"},
+        "unfused_chain": {"us_per_step": round(us2_chain, 2), "TOPS": round(w2.ops / us2_chain / 1e6, 2),
+                          "what": "abs-max, scale, quant_int, product(+max|H|), scale, quant_int, product as 9 launches, "
+                                  "H stored and re-read in fp32"},
         "pct_int8_mfma_peak": round(100 * tops2 / PEAK_INT8_TOPS, 2),
         "roofline": roofline,
         "kernels": pk2,
@@ -230,25 +270,37 @@ def main():
         tok = torch.empty(M, dtype=torch.int32, device=dev)
         val = torch.empty(M, dtype=torch.float32, device=dev)
 
+        qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
+        qws = torch.empty(4096, dtype=torch.uint8, device=dev)
+
         def out_step():
-            mq.mq_absmax_f32(Hd, Hd.numel(), s)
-            mq.mq_scale_from_amax(s, 8, s)
-            mq.mq_quantize_f32(Hd, M, d, 8, s, q, None)
-            mq.mq_gemm_argmax(q, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
+            mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, 4096)
+            mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
 
         out_step()
         us3 = time_events(graphed(out_step), args.steps, args.warmup)
-        us3k = time_events(lambda: mq.mq_gemm_argmax(q, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws),
-                           args.steps, args.warmup)
+        us3k = time_kernel(lambda: mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws))
+        # cold: 16 distinct embeddings (295 MB) in rotation, so the 256 MB last-level cache cannot hold them
+        pes = [pe] + [mq.prepare_weight(torch.randn(V, d, device=dev) * 0.05, 8) for _ in range(15)]
+
+        def cold_round():
+            for q_ in pes:
+                mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, 4096)
+                mq.mq_gemm_argmax_packed(qp, q_.packed, M, V, d, s, q_.scale, tok, val, ws, nws)
+
+        us3c = time_events(graphed(cold_round), max(5, args.steps // 10), 2) / len(pes)
+        del pes
         alg3 = V * d + 4 * M * d + 8 * M
         extras["output_layer_argmax"] = {
-            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, fused arg-max, cache-warm",
-            "us_per_step": round(us3, 2), "tokens_per_s": round(M / us3 * 1e6, 0),
-            "GBps_alg": round(alg3 / us3 / 1e3, 1), "TOPS": round(2 * M * V * d / us3 / 1e6, 1),
-            "gemm_argmax_us": round(us3k, 2)}
+            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, abs-max + quant_int + fused arg-max",
+            "us_per_step_warm": round(us3, 2), "tokens_per_s_warm": round(M / us3 * 1e6, 0),
+            "GBps_alg_warm": round(alg3 / us3 / 1e3, 1),
+            "us_per_step_cold": round(us3c, 2), "tokens_per_s_cold": round(M / us3c * 1e6, 0),
+            "GBps_alg_cold": round(alg3 / us3c / 1e3, 1), "pct_hbm_peak_cold": round(100 * alg3 / us3c / 1e3 / PEAK_HBM_GBS, 1),
+            "TOPS_warm": round(2 * M * V * d / us3 / 1e6, 1), "argmax_product_only_us": round(us3k, 2)}
         # int16 Transformer-big FFN
         c4 = workloads.config4()
-        w4, us4, pk4 = run_ffn(c4, 16, max(10, args.steps // 10), max(3, args.warmup // 5), "ffn-big-int16")
+        w4, us4, pk4 = run_ffn(c4, 16, max(10, args.steps // 10), max(3, args.warmup // 5), fused=False)
         extras["ffn_big_int16"] = {
             "workload": "[8192x1024]x[1024x4096]+bias+ReLU, requantize, [8192x4096]x[4096x1024]+bias, int16",
             "us_per_step": round(us4, 1), "TOPS_useful": round(w4.ops / us4 / 1e6, 1),

@@ -108,6 +108,15 @@ int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const fl
 int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                          void* packed, void* stream);
 
+/* Abs-max and quant_int into the packed layout in two launches with no atomics
+ * and no initialisation pass: per-block partial maxima go to ws, the quantizing
+ * kernel forms Qmax / max from them (one correctly rounded division) and stores
+ * it in scale_out[0].  Same results as mq_absmax_f32 + mq_scale_from_amax +
+ * mq_quantize_pack_f32.  ws: device, 16-byte aligned, mq_quantize_absmax_ws_bytes(). */
+size_t mq_quantize_absmax_ws_bytes(void);
+int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
+                                float* scale_out, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- memoized quant_int(B^T) (Section 4.3) ------------------------------ */
 
 /* Bytes of the packed parameter for an [N x K] Wt; 0 if bits is invalid or a
@@ -165,6 +174,24 @@ int mq_gemm_dequant_packed(const void* packedA, const void* packedW, int bits, s
                            const float* sA, const float* sW, const float* bias, int relu, float* Y,
                            float* out_amax, void* stream);
 
+/* Two-pass re-quantizing product (8 bit), the building block of mq_ffn_i8_f32:
+ * pass 1 computes y = fma((float)acc, 1/(sA sW), bias) (+ReLU) exactly like
+ * mq_gemm_dequant_packed but only writes one partial max|y| per tile to ws;
+ * pass 2 computes the same y again, forms s = 127 / max|y| from the partials
+ * (1 if the maximum is 0), stores it in scale_out[0] and writes
+ * quant_int(y, s) as packed 8-bit activations [M x N] (mq_packed_bytes(8, M, N)
+ * bytes) ready to be the A operand of the next product.  The float tensor y is
+ * never stored.  Both passes must see the same arguments (and the same
+ * mq_set_gemm_variant setting).  ws: device, 16-byte aligned,
+ * mq_gemm_amax_ws_bytes(M, N) bytes. */
+size_t mq_gemm_amax_ws_bytes(size_t M, size_t N);
+int mq_gemm_amax_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                        const float* sA, const float* sW, const float* bias, int relu,
+                        void* ws, size_t ws_bytes, void* stream);
+int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                           const float* sA, const float* sW, const float* bias, int relu,
+                           const void* ws, size_t ws_bytes, float* scale_out, void* packed_out, void* stream);
+
 /* ---- greedy output layer (Section 2.3) ---------------------------------- */
 
 /* Workspace bytes mq_gemm_argmax needs for an M-row problem. */
@@ -205,6 +232,28 @@ size_t mq_linear_ws_bytes(int bits, size_t M, size_t K);
 int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null,
                   const void* packedW, const float* sW, int bits, size_t N,
                   const float* bias, int relu, float* Y, float* out_amax,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace bytes mq_ffn_i8_f32 needs (0 for invalid sizes). */
+size_t mq_ffn_ws_bytes(size_t M, size_t d, size_t f);
+
+/* Transformer feed-forward block (Table 1: d -> f -> d) in 8 bit with per-tensor
+ * abs-max multipliers, the hot path in one call:
+ *   H = relu(dequant(dot'_int(quant_int(A), W1)) + b1),  Y = dequant(dot'_int(quant_int(H), W2)) + b2.
+ * Every step is the one defined above (same quant_int, same sums, same fma), so Y
+ * is bit-identical to the chain mq_absmax_f32 / mq_scale_from_amax /
+ * mq_quantize_pack_f32 / mq_gemm_dequant_packed(out_amax) / ... -- but the float
+ * intermediate H never goes to memory: the first product runs twice, once
+ * reduced to max|H| and once re-quantized with the multiplier that maximum
+ * gives, which is cheaper on this machine than writing and re-reading 4 M f bytes.
+ * Five launches, no atomics, no host synchronisation.
+ *   A: device float [M x d], 16-byte aligned.  packedW1: 8-bit packed [f x d];
+ *   packedW2: 8-bit packed [d x f]; sW1, sW2: their multipliers (device float[1]);
+ *   b1: device float [f] or NULL; b2: device float [d] or NULL; Y: device float [M x d];
+ *   ws: device, 256-byte aligned, mq_ffn_ws_bytes(M, d, f) bytes, contents
+ *   irrelevant on entry, undefined on return. */
+int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                  const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                   void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus

@@ -19,8 +19,9 @@ __all__ = [
     "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32",
-    "PreparedWeight", "prepare_weight",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32",
+    "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
+    "mq_gemm_requant_packed", "PreparedWeight", "prepare_weight",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -50,7 +51,9 @@ def exported_symbols():
             "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
-            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32"]
+            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32",
+            "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
+            "mq_gemm_amax_packed", "mq_gemm_requant_packed"]
 
 
 def load_library():
@@ -84,6 +87,16 @@ def load_library():
     lib.mq_argmax_ws_bytes.argtypes = [sz, sz]
     lib.mq_gemm_argmax.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_gemm_argmax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.mq_quantize_absmax_ws_bytes.restype = sz
+    lib.mq_quantize_absmax_ws_bytes.argtypes = []
+    lib.mq_quantize_absmax_pack_f32.argtypes = [vp, sz, sz, ci, vp, vp, vp, sz, vp]
+    lib.mq_gemm_amax_ws_bytes.restype = sz
+    lib.mq_gemm_amax_ws_bytes.argtypes = [sz, sz]
+    lib.mq_gemm_amax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp]
+    lib.mq_gemm_requant_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp, vp, vp]
+    lib.mq_ffn_ws_bytes.restype = sz
+    lib.mq_ffn_ws_bytes.argtypes = [sz, sz, sz]
+    lib.mq_ffn_i8_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_linear_ws_bytes.restype = sz
     lib.mq_linear_ws_bytes.argtypes = [ci, sz, sz]
     lib.mq_linear_f32.argtypes = [vp, sz, sz, vp, vp, vp, ci, sz, vp, ci, vp, vp, vp, sz, vp]
@@ -209,6 +222,40 @@ def mq_linear_f32(A, M, K, sA_or_null, packedW, sW, bits, N, bias, relu, Y, out_
     _check(load_library().mq_linear_f32(_p(A), M, K, _p(sA_or_null), _p(packedW), _p(sW), bits, N, _p(bias),
                                         int(relu), _p(Y), _p(out_amax), _p(ws), ws_bytes, _stream(stream)),
            "mq_linear_f32")
+
+
+def mq_quantize_absmax_ws_bytes() -> int:
+    return int(load_library().mq_quantize_absmax_ws_bytes())
+
+
+def mq_quantize_absmax_pack_f32(x, rows, cols, bits, packed, scale_out, ws, ws_bytes, stream=None):
+    _check(load_library().mq_quantize_absmax_pack_f32(_p(x), rows, cols, bits, _p(packed), _p(scale_out), _p(ws),
+                                                      ws_bytes, _stream(stream)), "mq_quantize_absmax_pack_f32")
+
+
+def mq_gemm_amax_ws_bytes(M, N) -> int:
+    return int(load_library().mq_gemm_amax_ws_bytes(M, N))
+
+
+def mq_gemm_amax_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, ws, ws_bytes, stream=None):
+    _check(load_library().mq_gemm_amax_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(bias),
+                                              int(relu), _p(ws), ws_bytes, _stream(stream)), "mq_gemm_amax_packed")
+
+
+def mq_gemm_requant_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, ws, ws_bytes, scale_out, packed_out,
+                           stream=None):
+    _check(load_library().mq_gemm_requant_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(bias),
+                                                 int(relu), _p(ws), ws_bytes, _p(scale_out), _p(packed_out),
+                                                 _stream(stream)), "mq_gemm_requant_packed")
+
+
+def mq_ffn_ws_bytes(M, d, f) -> int:
+    return int(load_library().mq_ffn_ws_bytes(M, d, f))
+
+
+def mq_ffn_i8_f32(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_bytes, stream=None):
+    _check(load_library().mq_ffn_i8_f32(_p(A), M, d, f, _p(packedW1), _p(sW1), _p(b1), _p(packedW2), _p(sW2),
+                                        _p(b2), _p(Y), _p(ws), ws_bytes, _stream(stream)), "mq_ffn_i8_f32")
 
 
 # ---- allocation helper (no arithmetic) --------------------------------------

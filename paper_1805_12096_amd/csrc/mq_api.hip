@@ -113,6 +113,19 @@ int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, con
   return launch_quantize_pack(x, rows, cols, bits, scale, packed, as_stream(stream));
 }
 
+size_t mq_quantize_absmax_ws_bytes(void) { return kAbsmaxPartials * sizeof(float); }
+
+int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
+                                float* scale_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (x == nullptr || scale_out == nullptr || packed == nullptr || ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(1, rows, cols)) return MQ_ERR_SHAPE;
+  if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(scale_out, 4) || !aligned(ws, 16)) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_quantize_absmax_ws_bytes()) return MQ_ERR_WORKSPACE;
+  return launch_absmax_quantize_pack(x, rows, cols, bits, static_cast<float*>(ws), scale_out, packed,
+                                     as_stream(stream));
+}
+
 size_t mq_packed_bytes(int bits, size_t N, size_t K) {
   if (!bits_ok(bits) || N == 0 || K == 0 || N >= kMaxDim || K >= kMaxDim) return 0;
   return PackedDims(bits, N, K).total_bytes();
@@ -199,6 +212,47 @@ int mq_gemm_dequant_packed(const void* packedA, const void* packedW, int bits, s
   return launch_gemm_packed(a, kEpiDequant, as_stream(stream));
 }
 
+size_t mq_gemm_amax_ws_bytes(size_t M, size_t N) {
+  if (M == 0 || N == 0 || M >= kMaxDim || N >= kMaxDim) return 0;
+  return round_up(gemm_amax_partials(M, N) * sizeof(float), 256);
+}
+
+namespace {
+int fused_pass_checks(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                      const float* sW, const float* bias, const void* ws, size_t ws_bytes) {
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(ws, 16))
+    return MQ_ERR_ALIGN;
+  if (bias != nullptr && !aligned(bias, 4)) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_gemm_amax_ws_bytes(M, N)) return MQ_ERR_WORKSPACE;
+  return MQ_OK;
+}
+}  // namespace
+
+int mq_gemm_amax_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                        const float* sW, const float* bias, int relu, void* ws, size_t ws_bytes, void* stream) {
+  int rc = fused_pass_checks(packedA, packedW, M, N, K, sA, sW, bias, ws, ws_bytes);
+  if (rc != MQ_OK) return rc;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
+  return launch_gemm_amax_partial(a, static_cast<float*>(ws), as_stream(stream));
+}
+
+int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                           const float* sA, const float* sW, const float* bias, int relu, const void* ws,
+                           size_t ws_bytes, float* scale_out, void* packed_out, void* stream) {
+  int rc = fused_pass_checks(packedA, packedW, M, N, K, sA, sW, bias, ws, ws_bytes);
+  if (rc != MQ_OK) return rc;
+  if (scale_out == nullptr || packed_out == nullptr) return MQ_ERR_NULL;
+  if (!aligned(scale_out, 4) || !aligned(packed_out, 16)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
+  return launch_gemm_requant(a, static_cast<const float*>(ws), scale_out, packed_out, as_stream(stream));
+}
+
 size_t mq_argmax_ws_bytes(size_t M, size_t N) {
   if (M == 0 || N == 0 || M >= kMaxDim || N >= kMaxDim) return 0;
   const size_t general = round_up(M * sizeof(unsigned long long), 256);
@@ -240,6 +294,68 @@ int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size
   rc = launch_gemm(a, kEpiArgmax, s);
   if (rc != MQ_OK) return rc;
   return launch_argmax_finish(keys, M, sA, sW, tok, maxlogit, s);
+}
+
+namespace mq {
+namespace {
+// Scratch layout of mq_ffn_i8_f32.
+struct FfnWs {
+  size_t off_part1, off_part2, off_scal, off_qA, off_qH, total;
+  FfnWs(size_t M, size_t d, size_t f) {
+    off_part1 = 0;
+    off_part2 = round_up(off_part1 + kAbsmaxPartials * sizeof(float), 256);
+    off_scal = round_up(off_part2 + gemm_amax_partials(M, f) * sizeof(float), 256);
+    off_qA = off_scal + 256;
+    off_qH = round_up(off_qA + PackedDims(8, M, d).total_bytes(), 256);
+    total = round_up(off_qH + PackedDims(8, M, f).total_bytes(), 256);
+  }
+};
+}  // namespace
+}  // namespace mq
+
+size_t mq_ffn_ws_bytes(size_t M, size_t d, size_t f) {
+  if (!dims_ok(M, f, d)) return 0;
+  return FfnWs(M, d, f).total;
+}
+
+int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                  const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                  void* ws, size_t ws_bytes, void* stream) {
+  if (A == nullptr || packedW1 == nullptr || sW1 == nullptr || packedW2 == nullptr || sW2 == nullptr ||
+      Y == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, f, d)) return MQ_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(packedW1, 16) || !aligned(packedW2, 16) || !aligned(ws, 256) ||
+      !aligned(sW1, 4) || !aligned(sW2, 4) || !aligned(Y, 4))
+    return MQ_ERR_ALIGN;
+  if ((b1 != nullptr && !aligned(b1, 4)) || (b2 != nullptr && !aligned(b2, 4))) return MQ_ERR_ALIGN;
+  const FfnWs L(M, d, f);
+  if (ws_bytes < L.total) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  float* part1 = reinterpret_cast<float*>(base + L.off_part1);
+  float* part2 = reinterpret_cast<float*>(base + L.off_part2);
+  float* sA = reinterpret_cast<float*>(base + L.off_scal);
+  float* sH = sA + 1;
+  void* qA = base + L.off_qA;
+  void* qH = base + L.off_qH;
+  // a1 + a2: abs-max and quant_int of the input (two launches, no atomics)
+  int rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s);
+  if (rc != MQ_OK) return rc;
+  // a4 + a5, first pass: only the abs-max of relu(A W1 + b1) leaves the chip
+  GemmArgs g1{};
+  g1.qA = qA; g1.packedW = packedW1; g1.bits = 8; g1.M = M; g1.N = f; g1.K = d;
+  g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1;
+  rc = launch_gemm_amax_partial(g1, part2, s);
+  if (rc != MQ_OK) return rc;
+  // second pass: the same sums again, quantized with the multiplier now known, stored as packed int8
+  rc = launch_gemm_requant(g1, part2, sH, qH, s);
+  if (rc != MQ_OK) return rc;
+  // second product with the float epilogue
+  GemmArgs g2{};
+  g2.qA = qH; g2.packedW = packedW2; g2.bits = 8; g2.M = M; g2.N = d; g2.K = f;
+  g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
+  return launch_gemm_packed(g2, kEpiDequant, s);
 }
 
 size_t mq_linear_ws_bytes(int bits, size_t M, size_t K) {

@@ -318,7 +318,7 @@ int launch_tiles(const GemmArgs& a, hipStream_t s) {
   p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y;
-  p.out_amax = a.out_amax; p.keys = a.keys; p.s_out = nullptr; p.packed_out = nullptr;
+  p.out_amax = a.out_amax; p.keys = a.keys; p.partial = nullptr; p.npartial = 0; p.s_out = nullptr; p.packed_out = nullptr;
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
   const dim3 grid((unsigned)(tiles_m * tiles_n));
   if (a.K % 16 == 0) return launch_one<BITS, BM, BN, WM, WN, EPI, true>(p, grid, s);

@@ -24,8 +24,10 @@ struct Params {
   float* Y;
   float* out_amax;
   unsigned long long* keys;
-  // re-quantizing epilogue (packed kernel only)
-  const float* s_out;       // multiplier of the output tensor
+  // fused-FFN epilogues (packed kernel only)
+  float* partial;           // abs-max partials: written (one per block) or read (npartial of them)
+  unsigned npartial;
+  float* s_out;             // multiplier formed from the partials, published by block 0
   uint8_t* packed_out;      // output written as packed 8-bit activations [M x N]
 };
 

@@ -20,7 +20,14 @@ namespace mq {
 
 namespace {
 
-enum PackedEpilogue { kPRaw = 0, kPDequant = 1 };
+enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3 };
+
+// One element of quant_int (8 bit): binary32 multiply, round half to even, clamp, NaN -> 0.
+__device__ __forceinline__ int quant8(float x, float s) {
+  const float r = rintf(__fmul_rn(x, s));
+  const float c = fminf(fmaxf(r, -127.0f), 127.0f);
+  return (r != r) ? 0 : (int)c;
+}
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
   // s_waitcnt with only vmcnt active: vmcnt is split over bits [3:0] and [15:14]
@@ -135,7 +142,11 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   auto mfma_one = [&](const Frags& F, int i) {
     const int pr = i / (TM * TN), mt = (i / TN) % TM, nt = i % TN;
     if constexpr (BITS == 8) {
-      acc[mt][nt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][0], F.b[nt][0], acc[mt][nt][0], 0, 0, 0);
+      // the re-quantizing epilogue wants consecutive n in one lane (4 bytes = one store), i.e. the
+      // parameter as operand `a`; everything else wants consecutive n across lanes
+      acc[mt][nt][0] = EPI == kPRequant
+                           ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[nt][0], F.a[mt][0], acc[mt][nt][0], 0, 0, 0)
+                           : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][0], F.b[nt][0], acc[mt][nt][0], 0, 0, 0);
     } else {
       const int pa = (pr == 0 || pr == 1) ? 0 : NPL - 1;          // hh, hl, lh, ll
       const int pb = (pr == 0 || pr == 2) ? 0 : NPL - 1;
@@ -183,10 +194,89 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     slice(f1, f0, nxt, 0);
   }
 
-  const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
-  const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
-  store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
-      acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum);
+  if constexpr (EPI == kPAmax || EPI == kPRequant) {
+    static_assert(BITS == 8 || (EPI != kPAmax && EPI != kPRequant), "fused epilogues are 8 bit");
+    __shared__ float red[NW];
+    const int lj = lane % 32, lh = lane / 32;
+    const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+    const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
+    if constexpr (EPI == kPAmax) {
+      // y = relu?(fma(acc, u, bias)) as in the storing epilogue, reduced to this block's abs-max
+      float local = 0.f;
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) {
+        const unsigned n = wn0 + nt * 32 + lj;
+        const bool n_ok = n < p.N;
+        const float bias = (p.bias != nullptr && n_ok) ? p.bias[n] : 0.f;
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const unsigned m = wm0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
+            float y = fmaf((float)acc[mt][nt][0][r], u, bias);
+            if (p.relu) y = (y > 0.0f) ? y : 0.0f;
+            if (n_ok && m < p.M) local = fmaxf(local, fabsf(y));
+          }
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) local = fmaxf(local, __shfl_xor(local, off, 64));
+      if (lane == 0) red[wave] = local;
+      __syncthreads();
+      if (tid == 0) {
+        float m = red[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
+        p.partial[blockIdx.x] = m;
+      }
+    } else {
+      // multiplier of the output from the partial maxima of the first pass (every block forms it)
+      float amax = 0.f;
+      for (unsigned i = tid; i < p.npartial; i += NW * 64) amax = fmaxf(amax, p.partial[i]);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+      if (lane == 0) red[wave] = amax;
+      __syncthreads();
+      amax = red[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) amax = fmaxf(amax, red[w]);
+      const float s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
+      if (blockIdx.x == 0 && tid == 0) *p.s_out = s2;
+      // operands were swapped: register r of lane l is (n, m) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32),
+      // so r = 4 q .. 4 q + 3 are four consecutive n of one row m: one dword of the packed output
+      const PackedDims dO(8, p.M, p.N);
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        const unsigned m = wm0 + mt * 32 + lj;
+#pragma unroll
+        for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const unsigned n4 = wn0 + nt * 32 + 8 * q + 4 * lh;
+            int qv[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const unsigned n = n4 + t;
+              const float bias = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
+              float y = fmaf((float)acc[mt][nt][0][4 * q + t], u, bias);
+              if (p.relu) y = (y > 0.0f) ? y : 0.0f;
+              qv[t] = (n < p.N && m < p.M) ? quant8(y, s2) : 0;     // padding stays zero
+            }
+            if (m < dO.Np && n4 < dO.Kp) {
+              const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
+                                    ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
+              uint8_t* dst = p.packed_out + dO.frag_offset(m / 32, n4 / 32) +
+                             (size_t)((m % 32) + 32 * ((n4 % 32) / 16)) * 16 + n4 % 16;
+              *reinterpret_cast<uint32_t*>(dst) = word;
+            }
+          }
+      }
+    }
+  } else {
+    const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
+    const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
+    store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
+        acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum);
+  }
 }
 
 template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI>
@@ -202,6 +292,7 @@ int launch_pp(const GemmArgs& a, hipStream_t s) {
   p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  p.partial = a.partial; p.npartial = a.npartial; p.s_out = a.s_out; p.packed_out = static_cast<uint8_t*>(a.packed_out);
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
   auto kern = k_gemm_pp<BITS, BM, BN, WM, WN, S, EPI>;
   static bool attr_done = false;
@@ -236,6 +327,38 @@ int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
 }
 
 }  // namespace
+
+namespace {
+// Tile configuration of the fused 8-bit passes: the large tile when it fills the chip, else the small one.
+int fused_variant(const GemmArgs& a) {
+  int v = forced_variant();
+  if (v <= 0) v = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200 ? 1 : 3;
+  return v;
+}
+size_t tiles_of(int variant, size_t M, size_t N) {
+  const size_t bm = (variant == 3) ? 128 : 256, bn = (variant == 3 || variant == 4) ? 128 : 256;
+  return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+}
+}  // namespace
+
+// Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
+size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 127) / 128); }
+
+int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s) {
+  GemmArgs b = a;
+  b.partial = partials;
+  return launch_pp_variant<8, kPAmax>(b, fused_variant(a), s);
+}
+
+int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, void* packed_out, hipStream_t s) {
+  GemmArgs b = a;
+  const int v = fused_variant(a);
+  b.partial = const_cast<float*>(partials);
+  b.npartial = (unsigned)tiles_of(v, a.M, a.N);     // what the amax pass wrote with the same variant
+  b.s_out = s_out;
+  b.packed_out = packed_out;
+  return launch_pp_variant<8, kPRequant>(b, v, s);
+}
 
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   int v = forced_variant();

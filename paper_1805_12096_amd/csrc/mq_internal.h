@@ -73,6 +73,11 @@ struct GemmArgs {
   float* out_amax;
   // argmax
   unsigned long long* keys;  // [M] packed (sum, ~index) maxima
+  // fused FFN passes
+  float* partial;
+  unsigned npartial;
+  float* s_out;
+  void* packed_out;
 };
 int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
 void set_forced_variant(int v);
@@ -84,6 +89,15 @@ int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, con
 int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
 int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* sA, const float* sW,
                          int32_t* tok, float* maxlogit, hipStream_t s);
+
+constexpr unsigned kAbsmaxPartials = 1024;   // floats of scratch launch_absmax_quantize_pack needs
+int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
+                                float* scale_out, void* packed, hipStream_t s);
+// Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same
+// product re-quantized with the multiplier formed from those partials, written as packed activations.
+size_t gemm_amax_partials(size_t M, size_t N);
+int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s);
+int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, void* packed_out, hipStream_t s);
 
 // Streaming arg-max product for decode-sized batches (both operands packed, 8 bit).
 size_t argmax_stream_ws_bytes(size_t M);

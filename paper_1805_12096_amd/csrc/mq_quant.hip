@@ -224,12 +224,70 @@ int launch_quantize(const float* x, size_t rows, size_t cols, int bits, const fl
 namespace mq {
 namespace {
 
-template <int BITS, bool VEC>
+// Abs-max without atomics or initialisation: block b writes its maximum to partial[b];
+// the consumer reduces the few hundred values itself (block_max_of_partials).
+__global__ __launch_bounds__(kThreads) void k_absmax_partial(const float* __restrict__ x, size_t n,
+                                                             float* __restrict__ partial) {
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t nthreads = (size_t)gridDim.x * kThreads;
+  const size_t nvec = n / 4;
+  const float4* xv = reinterpret_cast<const float4*>(x);
+  float m0 = 0.f, m1 = 0.f;
+  size_t i = tid;
+  for (; i + nthreads < nvec; i += 2 * nthreads) {
+    const float4 a = xv[i], b = xv[i + nthreads];
+    m0 = fmaxf(m0, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    m1 = fmaxf(m1, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+  }
+  for (; i < nvec; i += nthreads) {
+    const float4 a = xv[i];
+    m0 = fmaxf(m0, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+  }
+  for (size_t j = nvec * 4 + tid; j < n; j += nthreads) m1 = fmaxf(m1, fabsf(x[j]));
+  const float m = wave_max(fmaxf(m0, m1));
+  __shared__ float part[kThreads / kWave];
+  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
+  if (lane == 0) part[w] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float r = part[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / kWave; ++k) r = fmaxf(r, part[k]);
+    partial[blockIdx.x] = r;
+  }
+}
+
+// Maximum of `count` partial maxima, computed redundantly by every block that needs it.
+__device__ __forceinline__ float block_max_of_partials(const float* __restrict__ partial, unsigned count) {
+  float m = 0.f;
+  for (unsigned i = threadIdx.x; i < count; i += kThreads) m = fmaxf(m, partial[i]);
+  m = wave_max(m);
+  __shared__ float red[kThreads / kWave];
+  if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = m;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int k = 1; k < kThreads / kWave; ++k) r = fmaxf(r, red[k]);
+  return r;
+}
+
+// FROM_PARTIALS: `scale` holds `npartial` partial abs-maxima instead of the multiplier; the
+// multiplier Qmax / max is formed here (one correctly rounded division) and block 0 also
+// publishes it in scale_out[0] for the product kernels that follow.
+template <int BITS, bool VEC, bool FROM_PARTIALS>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restrict__ x, size_t rows,
                                                             size_t cols, const float* __restrict__ scale,
-                                                            uint8_t* __restrict__ packed, unsigned ksplit) {
+                                                            uint8_t* __restrict__ packed, unsigned ksplit,
+                                                            unsigned npartial, float* __restrict__ scale_out) {
   const PackedDims d(BITS, rows, cols);
-  const float s = *scale;
+  float s;
+  if (FROM_PARTIALS) {
+    const float amax = block_max_of_partials(scale, npartial);
+    s = (amax > 0.0f) ? __fdiv_rn(BITS == 8 ? 127.0f : 32767.0f, amax) : 1.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = s;
+  } else {
+    s = *scale;
+  }
   const float lim = BITS == 8 ? 127.0f : 32767.0f;
   const int lane = threadIdx.x % kWave;
   const int sub = lane % 8;                       // which 4 floats of a 32-element fragment row
@@ -293,12 +351,40 @@ int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, con
   const unsigned grid = grid_for(row_groups * ksplit, kThreads / kWave, 8192);
   uint8_t* p = static_cast<uint8_t*>(packed);
   const bool vec = cols % 4 == 0;
+  float* none = nullptr;
   if (bits == 8) {
-    if (vec) hipLaunchKernelGGL((k_quantize_pack<8, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
-    else hipLaunchKernelGGL((k_quantize_pack<8, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<8, true, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
+    else hipLaunchKernelGGL((k_quantize_pack<8, false, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
   } else {
-    if (vec) hipLaunchKernelGGL((k_quantize_pack<16, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
-    else hipLaunchKernelGGL((k_quantize_pack<16, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit);
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<16, true, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
+    else hipLaunchKernelGGL((k_quantize_pack<16, false, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
+  }
+  return check_hip(hipGetLastError());
+}
+
+// abs-max + quant_int into the packed layout in two launches, no atomics, no fill:
+// partial maxima to `partials` (kAbsmaxPartials floats), then quantization with the multiplier
+// formed from them; scale_out[0] receives the multiplier.
+int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
+                                float* scale_out, void* packed, hipStream_t s) {
+  const size_t n = rows * cols;
+  const unsigned g1 = grid_for(n, (size_t)kThreads * 8, kAbsmaxPartials);
+  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials);
+  const PackedDims d(bits, rows, cols);
+  const size_t row_groups = d.Np / 8;
+  unsigned ksplit = 1;
+  if (bits == 8) {
+    while (row_groups * ksplit < 2048 && ksplit * 4 <= d.kfrags) ksplit *= 2;
+  }
+  const unsigned grid = grid_for(row_groups * ksplit, kThreads / kWave, 8192);
+  uint8_t* p = static_cast<uint8_t*>(packed);
+  const bool vec = cols % 4 == 0;
+  if (bits == 8) {
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<8, true, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
+    else hipLaunchKernelGGL((k_quantize_pack<8, false, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
+  } else {
+    if (vec) hipLaunchKernelGGL((k_quantize_pack<16, true, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
+    else hipLaunchKernelGGL((k_quantize_pack<16, false, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
   }
   return check_hip(hipGetLastError());
 }

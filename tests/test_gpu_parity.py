@@ -546,3 +546,85 @@ def test_config3_output_layer_full_packed():
     tok, val = gpu_greedy_packed(c["Hd"], c["E"])
     assert np.array_equal(tok, o["tok"])
     assert np.array_equal(val, o["maxlogit"])
+
+
+# ----------------------------------------------------------- fused FFN (8 bit)
+
+def gpu_ffn_fused(c):
+    A = dev(c["A"])
+    M, d = A.shape
+    f = c["W1t"].shape[0]
+    p1 = mq.prepare_weight(dev(c["W1t"]), 8)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 8)
+    nbytes = mq.mq_ffn_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device=DEV)     # contents must not matter
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+    mq.mq_ffn_i8_f32(A, M, d, f, p1.packed, p1.scale, dev(c["b1"]), p2.packed, p2.scale, dev(c["b2"]), Y, ws, nbytes)
+    return host(Y)
+
+
+@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (320, 512, 2048), (130, 96, 100), (513, 256, 384)])
+def test_ffn_fused_matches_oracle_chain(M, d, f):
+    c = workloads.ffn(2, M, d, f, 0.04, 8, seed_extra=M + d + f)
+    o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
+    for v in (0, 1, 3, 4):
+        try:
+            mq.mq_set_gemm_variant(v)
+            assert np.array_equal(gpu_ffn_fused(c), o2["Y"]), f"variant {v}"
+        finally:
+            mq.mq_set_gemm_variant(0)
+
+
+def test_ffn_fused_full_size_equals_unfused_and_sampled_oracle():
+    c = workloads.config2()
+    Yf = gpu_ffn_fused(c)
+    g = gpu_ffn(c, 8)
+    assert np.array_equal(Yf, host(g["Y"]))          # same bits as the call-by-call chain at M = 8192
+    sA = oracle.scale_from_amax(oracle.absmax(c["A"]), 8)
+    s2 = host(g["s2"])[0]
+    rows = np.r_[0:24, 5000:5024, 8168:8192]
+    _, o2 = oracle_ffn_rows(c, 8, rows, sA, s2)
+    assert np.array_equal(Yf[rows], o2["Y"])
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+@pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (2000, 1024)])
+def test_quantize_absmax_pack_two_launch(bits, shape):
+    rng = np.random.default_rng(shape[0] + shape[1] * 3 + bits)
+    x = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.3)
+    oq, os_ = oracle.quant_int_absmax(x, bits)
+    nb = mq.mq_quantize_absmax_ws_bytes()
+    ws = torch.full((nb,), 0x7F, dtype=torch.uint8, device=DEV)
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    packed = torch.empty(mq.mq_packed_bytes(bits, *shape), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_absmax_pack_f32(dev(x), shape[0], shape[1], bits, packed, s, ws, nb)
+    q = torch.empty(shape, dtype=QT[bits], device=DEV)
+    mq.mq_unpack_weight(packed, bits, shape[0], shape[1], q)
+    assert host(s)[0] == os_ and np.array_equal(host(q), oq)
+
+
+def test_two_pass_requantizing_product():
+    p = workloads.random_problem(404, 300, 520, 256)
+    o = oracle.linear(p["A"], p["Wt"], 8, p["bias"], True)
+    os2 = oracle.scale_from_amax(oracle.absmax(o["Y"]), 8)
+    oq = oracle.quant_int(o["Y"], 8, os2)
+    M, K = p["A"].shape
+    N = p["Wt"].shape[0]
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    pa, s = gpu_quantize_pack(p["A"], 8)
+    nb = mq.mq_gemm_amax_ws_bytes(M, N)
+    ws = torch.full((nb,), 0x11, dtype=torch.uint8, device=DEV)
+    bias = dev(p["bias"])
+    s2 = torch.empty(1, dtype=torch.float32, device=DEV)
+    out = torch.full((mq.mq_packed_bytes(8, M, N),), 0x22, dtype=torch.uint8, device=DEV)
+    mq.mq_gemm_amax_packed(pa, pw.packed, M, N, K, s, pw.scale, bias, True, ws, nb)
+    mq.mq_gemm_requant_packed(pa, pw.packed, M, N, K, s, pw.scale, bias, True, ws, nb, s2, out)
+    q = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    mq.mq_unpack_weight(out, 8, M, N, q)
+    assert host(s2)[0] == os2
+    assert np.array_equal(host(q), oq)
+    # padding of the packed output is zero: a prepared copy of the same integers has identical bytes
+    ref = mq.prepare_weight(dev(oq.astype(np.float32)), 8, scale=torch.ones(1, dtype=torch.float32, device=DEV))
+    assert torch.equal(out, ref.packed)
