@@ -70,37 +70,60 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
   const int lj = lane % 32, lh = lane / 32;
   float u = 0.f, local_amax = 0.f;
   if (EPI == kEpiDequant) u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+  // Addresses split into a wave-uniform part (tile origin, register's row) and a per-lane constant
+  // (4 (l / 32) rows down, l % 32 columns right), so that a store needs no per-element arithmetic.
+  const size_t lane_off = (size_t)(4 * lh) * p.N + lj;
+  // Whole wave tile inside the matrix (the common case): no per-element bounds checks.
+  const bool interior = wave_m0 + TM * 32 <= p.M && wave_n0 + TN * 32 <= p.N;
+  auto element = [&](int mt, int nt, int r, float bias, unsigned corr_n, unsigned m) -> void {
+    int v;
+    if constexpr (BITS == 8) {
+      v = acc[mt][nt][0][r];
+    } else {
+      const unsigned t = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
+                         (unsigned)acc[mt][nt][NACC - 1][r] + 128u * (unsigned)rowsum[m] + corr_n;
+      v = (int)t;
+    }
+    const size_t uni = (size_t)(wave_m0 + mt * 32 + 8 * (r / 4) + r % 4) * p.N + wave_n0 + nt * 32;
+    if (EPI == kEpiRaw) {
+      p.C[uni + lane_off] = v;
+    } else {
+      float y = fmaf((float)v, u, bias);
+      if (p.relu) y = (y > 0.0f) ? y : 0.0f;
+      p.Y[uni + lane_off] = y;
+      local_amax = fmaxf(local_amax, fabsf(y));
+    }
+  };
+  if (interior) {
 #pragma unroll
-  for (int nt = 0; nt < TN; ++nt) {
-    const unsigned n = wave_n0 + nt * 32 + lj;
-    const bool n_ok = n < p.N;
-    float bias = 0.f;
-    unsigned corr_n = 0;
-    if (EPI == kEpiDequant && p.bias != nullptr && n_ok) bias = p.bias[n];
-    if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
+    for (int nt = 0; nt < TN; ++nt) {
+      const unsigned n = wave_n0 + nt * 32 + lj;
+      float bias = 0.f;
+      unsigned corr_n = 0;
+      if (EPI == kEpiDequant && p.bias != nullptr) bias = p.bias[n];
+      if (BITS == 16) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
 #pragma unroll
-    for (int mt = 0; mt < TM; ++mt)
+      for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const unsigned m = wave_m0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
-        if (!n_ok || m >= p.M) continue;
-        int v;
-        if constexpr (BITS == 8) {
-          v = acc[mt][nt][0][r];
-        } else {
-          const unsigned t = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
-                             (unsigned)acc[mt][nt][NACC - 1][r] + 128u * (unsigned)rowsum[m] + corr_n;
-          v = (int)t;
+        for (int r = 0; r < 16; ++r) element(mt, nt, r, bias, corr_n, wave_m0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4);
+    }
+  } else {
+#pragma unroll
+    for (int nt = 0; nt < TN; ++nt) {
+      const unsigned n = wave_n0 + nt * 32 + lj;
+      const bool n_ok = n < p.N;
+      float bias = 0.f;
+      unsigned corr_n = 0;
+      if (EPI == kEpiDequant && p.bias != nullptr && n_ok) bias = p.bias[n];
+      if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned m = wave_m0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
+          if (n_ok && m < p.M) element(mt, nt, r, bias, corr_n, m);
         }
-        if (EPI == kEpiRaw) {
-          p.C[(size_t)m * p.N + n] = v;
-        } else {
-          float y = fmaf((float)v, u, bias);
-          if (p.relu) y = (y > 0.0f) ? y : 0.0f;
-          p.Y[(size_t)m * p.N + n] = y;
-          local_amax = fmaxf(local_amax, fabsf(y));
-        }
-      }
+    }
   }
   if (EPI == kEpiDequant && p.out_amax != nullptr) {
     // block-wide maximum, then at most one atomic per block; the running

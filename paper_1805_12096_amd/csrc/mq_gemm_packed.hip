@@ -120,7 +120,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   constexpr int PR = BITS == 16 ? 4 : 1;          // 8-bit products per result tile and K slice
   constexpr int R = (TM + TN) * NPL;              // fragment reads per K slice
   constexpr int NM = TM * TN * PR;                // MFMAs per K slice
-  static_assert(R <= NM, "one fragment read is paired with each of the first R MFMAs");
 
   // r-th fragment read of slice ks of a stage, in the order the MFMAs need them:
   // A block 0, every parameter block, then the other A blocks.
@@ -160,8 +159,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   // the matrix pipeline instead of stalling it.
   auto slice = [&](const Frags& cur, Frags& nxt, const uint8_t* next_stage, int next_ks) {
 #pragma unroll
-    for (int i = 0; i < NM; ++i) {
-      mfma_one(cur, i);
+    for (int i = 0; i < (NM > R ? NM : R); ++i) {
+      if (i < NM) mfma_one(cur, i);
       if (i < R) read_one(nxt, next_stage, next_ks, i);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -242,33 +241,46 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       const float s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
       if (blockIdx.x == 0 && tid == 0) *p.s_out = s2;
       // operands were swapped: register r of lane l is (n, m) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32),
-      // so r = 4 q .. 4 q + 3 are four consecutive n of one row m: one dword of the packed output
+      // so r = 4 q .. 4 q + 3 are four consecutive n of one row m: one dword of the packed output.
+      // Each 32 x 32 sub-tile is exactly one 1 KB fragment of the output; it is assembled in LDS (the
+      // pipeline stages are free now) and leaves as one 16-byte store per lane, 1 KB contiguous.
       const PackedDims dO(8, p.M, p.N);
+      __syncthreads();                             // every wave is done reading the last stage
+      uint8_t* scratch = smem + wave * kFragBytes;
 #pragma unroll
-      for (int mt = 0; mt < TM; ++mt) {
-        const unsigned m = wm0 + mt * 32 + lj;
+      for (int nt = 0; nt < TN; ++nt) {
+        float bias[16];
 #pragma unroll
-        for (int nt = 0; nt < TN; ++nt)
+        for (int j = 0; j < 16; ++j) {
+          const unsigned n = wn0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4;
+          bias[j] = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
+        }
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt) {
+          const unsigned m = wm0 + mt * 32 + lj;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const unsigned n4 = wn0 + nt * 32 + 8 * q + 4 * lh;
             int qv[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-              const unsigned n = n4 + t;
-              const float bias = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
-              float y = fmaf((float)acc[mt][nt][0][4 * q + t], u, bias);
+              const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
+              float y = fmaf((float)acc[mt][nt][0][4 * q + t], u, bias[4 * q + t]);
               if (p.relu) y = (y > 0.0f) ? y : 0.0f;
               qv[t] = (n < p.N && m < p.M) ? quant8(y, s2) : 0;     // padding stays zero
             }
-            if (m < dO.Np && n4 < dO.Kp) {
-              const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
-                                    ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
-              uint8_t* dst = p.packed_out + dO.frag_offset(m / 32, n4 / 32) +
-                             (size_t)((m % 32) + 32 * ((n4 % 32) / 16)) * 16 + n4 % 16;
-              *reinterpret_cast<uint32_t*>(dst) = word;
-            }
+            const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
+                                  ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
+            // slot of row m in the fragment: lj + 32 (K half); the 4 bytes sit at 8 (q % 2) + 4 lh
+            *reinterpret_cast<uint32_t*>(scratch + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
           }
+          // the wave reads back what it wrote itself: only its own LDS operations need to be complete
+          __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+          const u4 v = *reinterpret_cast<const u4*>(scratch + lane * 16);
+          const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
+          if (mrow < dO.Np && ncol < dO.Kp)
+            *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
+          __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
+        }
       }
     }
   } else {
@@ -314,6 +326,9 @@ int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
       case 2: return launch_pp<8, 256, 256, 2, 2, 4, EPI>(a, s);   // 4 waves, 128x128 per wave
       case 3: return launch_pp<8, 128, 128, 2, 2, 4, EPI>(a, s);   // small tile, 64x64 per wave
       case 4: return launch_pp<8, 256, 128, 4, 2, 4, EPI>(a, s);   // 8 waves, 64x64 per wave
+      case 5: return launch_pp<8, 128, 128, 2, 2, 8, EPI>(a, s);   // small tile, deep pipeline (6 stages in flight)
+      case 6: return launch_pp<8, 256, 128, 4, 2, 6, EPI>(a, s);   // 8 waves, 64x64 per wave, deep pipeline
+      case 7: return launch_pp<8, 128, 64, 2, 2, 8, EPI>(a, s);    // very small tile for narrow results
       default: return MQ_ERR_UNSUPPORTED;
     }
   } else {
@@ -336,13 +351,19 @@ int fused_variant(const GemmArgs& a) {
   return v;
 }
 size_t tiles_of(int variant, size_t M, size_t N) {
-  const size_t bm = (variant == 3) ? 128 : 256, bn = (variant == 3 || variant == 4) ? 128 : 256;
+  size_t bm = 256, bn = 256;
+  switch (variant) {
+    case 3: case 5: bm = 128; bn = 128; break;
+    case 4: case 6: bm = 256; bn = 128; break;
+    case 7: bm = 128; bn = 64; break;
+    default: break;
+  }
   return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
 }
 }  // namespace
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
-size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 127) / 128); }
+size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
 
 int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s) {
   GemmArgs b = a;

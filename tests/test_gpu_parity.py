@@ -435,7 +435,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4], 16: [0, 1, 2, 3]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7], 16: [0, 1, 2, 3]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
@@ -569,7 +569,7 @@ def test_ffn_fused_matches_oracle_chain(M, d, f):
     o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
     s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
     o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
-    for v in (0, 1, 3, 4):
+    for v in (0, 1, 3, 4, 5, 7):
         try:
             mq.mq_set_gemm_variant(v)
             assert np.array_equal(gpu_ffn_fused(c), o2["Y"]), f"variant {v}"
