@@ -47,7 +47,7 @@ __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
 }
 
-template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI>
+template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI, bool PF = true>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   constexpr int NW = WM * WN;
   constexpr int NPL = BITS == 16 ? 2 : 1;
@@ -166,31 +166,52 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     }
   };
 
-  Frags f0, f1;
 #pragma unroll
   for (int st = 0; st < S - 1; ++st)
     if ((unsigned)st < KT) issue(st);
-  if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
-  else wait_vmcnt(0);
-  block_barrier();
-#pragma unroll
-  for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
-
-  for (unsigned kt = 0; kt < KT; ++kt) {
-    const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
-    const uint8_t* nxt = smem + ((kt + 1) % S) * STAGE + lane * 16;
-    // slice 0 of stage kt; slice 1's fragments stream in behind it
-    slice(f0, f1, cur, 1);
-    // stage kt + 1 must have landed for everybody before its first fragments are
-    // read; stages kt + 2 .. kt + S - 2 may stay in flight (none in the tail)
-    if (kt + S - 2 < KT) wait_vmcnt((S - 3) * L);
+  if constexpr (PF) {
+    Frags f0, f1;
+    if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
     else wait_vmcnt(0);
     block_barrier();
-    // every wave is past slice 0 of stage kt, so stage kt - 1's slot is free
-    if (kt + S - 1 < KT) issue(kt + S - 1);
-    // slice 1 of stage kt; slice 0 of stage kt + 1 streams in behind it (after
-    // the last stage this reads a finished slot again and the result is unused)
-    slice(f1, f0, nxt, 0);
+#pragma unroll
+    for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
+
+    for (unsigned kt = 0; kt < KT; ++kt) {
+      const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
+      const uint8_t* nxt = smem + ((kt + 1) % S) * STAGE + lane * 16;
+      // slice 0 of stage kt; slice 1's fragments stream in behind it
+      slice(f0, f1, cur, 1);
+      // stage kt + 1 must have landed for everybody before its first fragments are
+      // read; stages kt + 2 .. kt + S - 2 may stay in flight (none in the tail)
+      if (kt + S - 2 < KT) wait_vmcnt((S - 3) * L);
+      else wait_vmcnt(0);
+      block_barrier();
+      // every wave is past slice 0 of stage kt, so stage kt - 1's slot is free
+      if (kt + S - 1 < KT) issue(kt + S - 1);
+      // slice 1 of stage kt; slice 0 of stage kt + 1 streams in behind it (after
+      // the last stage this reads a finished slot again and the result is unused)
+      slice(f1, f0, nxt, 0);
+    }
+  } else {
+    // Register-lean variant for tiles whose accumulators leave no room for a second fragment
+    // set: fragments are read right before use; with two waves per SIMD the other wave's MFMAs
+    // cover the LDS latency.  One barrier per K step, as in the simple pipeline.
+    Frags f;
+    for (unsigned kt = 0; kt < KT; ++kt) {
+      if (kt + S - 2 < KT) wait_vmcnt((S - 2) * L);
+      else wait_vmcnt(0);
+      block_barrier();
+      if (kt + S - 1 < KT) issue(kt + S - 1);
+      const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) read_one(f, cur, ks, r);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) mfma_one(f, i);
+      }
+    }
   }
 
   if constexpr (EPI == kPAmax || EPI == kPRequant) {
@@ -291,7 +312,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   }
 }
 
-template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI>
+template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI, bool PF = true>
 int launch_pp(const GemmArgs& a, hipStream_t s) {
   constexpr int NPL = BITS == 16 ? 2 : 1;
   constexpr size_t smem = (size_t)S * ((BM / 32) + (BN / 32)) * 2 * NPL * kFragBytes;
@@ -306,7 +327,7 @@ int launch_pp(const GemmArgs& a, hipStream_t s) {
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
   p.partial = a.partial; p.npartial = a.npartial; p.s_out = a.s_out; p.packed_out = static_cast<uint8_t*>(a.packed_out);
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
-  auto kern = k_gemm_pp<BITS, BM, BN, WM, WN, S, EPI>;
+  auto kern = k_gemm_pp<BITS, BM, BN, WM, WN, S, EPI, PF>;
   static bool attr_done = false;
   if (!attr_done) {
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -336,6 +357,8 @@ int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
       case 1: return launch_pp<16, 128, 128, 4, 2, 4, EPI>(a, s);  // 8 waves, 32x64 per wave
       case 2: return launch_pp<16, 128, 128, 2, 2, 4, EPI>(a, s);  // 4 waves, 64x64 per wave
       case 3: return launch_pp<16, 64, 128, 2, 2, 4, EPI>(a, s);   // small tile, 32x64 per wave
+      case 4: return launch_pp<16, 256, 128, 4, 2, 3, EPI, false>(a, s);   // 8 waves, 64x64 per wave, lean registers
+      case 5: return launch_pp<16, 128, 128, 4, 2, 4, EPI, false>(a, s);   // as 1 without fragment prefetch
       default: return MQ_ERR_UNSUPPORTED;
     }
   }
@@ -384,8 +407,11 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   int v = forced_variant();
   if (v <= 0) {
+    // Shape heuristic standing in for a per-shape timing run: the largest tile that still gives
+    // every compute unit work, smaller tiles for small problems.
     if (a.bits == 16) {
-      v = 1;
+      const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
+      v = t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3);
     } else {
       const size_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
       v = t256 >= 200 ? 1 : 3;

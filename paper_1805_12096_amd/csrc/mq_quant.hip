@@ -302,30 +302,40 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restr
     const size_t nb = row / kFragRows;
     const int slot = (int)(row % kFragRows) + 32 * (sub / 4);
     int sum = 0;
-    for (size_t kb = part * per; kb < kb_end; ++kb) {
-      const size_t k = kb * kFragK + 4 * sub;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < rows) {
-        if (VEC) {
-          if (k < cols) v = *reinterpret_cast<const float4*>(x + row * cols + k);
-        } else {
-          const float* xr = x + row * cols;
-          if (k + 0 < cols) v.x = xr[k + 0];
-          if (k + 1 < cols) v.y = xr[k + 1];
-          if (k + 2 < cols) v.z = xr[k + 2];
-          if (k + 3 < cols) v.w = xr[k + 3];
+    // four fragments per trip: all four loads are issued before the first conversion, so several
+    // 128-byte lines per row are in flight instead of one
+    for (size_t kb0 = part * per; kb0 < kb_end; kb0 += 4) {
+      float4 v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t k = (kb0 + j) * kFragK + 4 * sub;
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (kb0 + j < kb_end && row < rows) {
+          if (VEC) {
+            if (k < cols) v[j] = *reinterpret_cast<const float4*>(x + row * cols + k);
+          } else {
+            const float* xr = x + row * cols;
+            if (k + 0 < cols) v[j].x = xr[k + 0];
+            if (k + 1 < cols) v[j].y = xr[k + 1];
+            if (k + 2 < cols) v[j].z = xr[k + 2];
+            if (k + 3 < cols) v[j].w = xr[k + 3];
+          }
         }
       }
-      const int q0 = quant1(v.x, s, lim), q1 = quant1(v.y, s, lim), q2 = quant1(v.z, s, lim),
-                q3 = quant1(v.w, s, lim);
-      uint8_t* dst = packed + d.frag_offset(nb, kb) + (size_t)slot * 16 + 4 * (sub % 4);
-      if (BITS == 8) {
-        *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0, q1, q2, q3);
-      } else {
-        sum += q0 + q1 + q2 + q3;
-        // q = 256 h + l + 128: high bytes, and low bytes with the top bit flipped
-        *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0 >> 8, q1 >> 8, q2 >> 8, q3 >> 8);
-        *reinterpret_cast<uint32_t*>(dst + kFragBytes) = pack4_i8(q0, q1, q2, q3) ^ 0x80808080u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (kb0 + j >= kb_end) break;
+        const int q0 = quant1(v[j].x, s, lim), q1 = quant1(v[j].y, s, lim), q2 = quant1(v[j].z, s, lim),
+                  q3 = quant1(v[j].w, s, lim);
+        uint8_t* dst = packed + d.frag_offset(nb, kb0 + j) + (size_t)slot * 16 + 4 * (sub % 4);
+        if (BITS == 8) {
+          *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0, q1, q2, q3);
+        } else {
+          sum += q0 + q1 + q2 + q3;
+          // q = 256 h + l + 128: high bytes, and low bytes with the top bit flipped
+          *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0 >> 8, q1 >> 8, q2 >> 8, q3 >> 8);
+          *reinterpret_cast<uint32_t*>(dst + kFragBytes) = pack4_i8(q0, q1, q2, q3) ^ 0x80808080u;
+        }
       }
     }
     if (BITS == 16) {  // ksplit is 1 for 16 bit: one wave owns whole rows
