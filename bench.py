@@ -32,9 +32,14 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
-# None until measured for the kernel/workload in question.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file on the default workload
+# (profiles/ffn_int8_hbm_counters.txt: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after calibration on a known copy).
+MEASURED_TRAFFIC = {
+    "gemm1 pass 1: bias+relu -> max|H|": 12.9e6,
+    "gemm1 pass 2: bias+relu -> quant_int(H)": 29.8e6,
+    "gemm2+bias": 42.1e6,
+    "absmax+quant_int(A) [2 launches]": 2 * 16.8e6 * 1.0 + 4.2e6,
+}
 
 
 def parse_args():
@@ -45,6 +50,8 @@ def parse_args():
     ap.add_argument("--no-extras", action="store_true", help="skip the output-layer and int16 side workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy, the known-size reference for scaling HBM counters")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the workload the oracle is timed on")
     return ap.parse_args()
 
@@ -253,6 +260,14 @@ def main():
         "roofline": roofline,
         "kernels": pk2,
     }
+
+    if args.copy_calibration:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------- extras
     if not args.no_extras:
