@@ -313,6 +313,14 @@ def main():
             "us_per_step_cold": round(us3c, 2), "tokens_per_s_cold": round(M / us3c * 1e6, 0),
             "GBps_alg_cold": round(alg3 / us3c / 1e3, 1), "pct_hbm_peak_cold": round(100 * alg3 / us3c / 1e3 / PEAK_HBM_GBS, 1),
             "TOPS_warm": round(2 * M * V * d / us3 / 1e6, 1), "argmax_product_only_us": round(us3k, 2)}
+        # short-listed output layer: 100 most frequent ids + 100 candidates per source word of a 384-word batch
+        rng = np.random.default_rng(workloads.BASE_SEED + 33)
+        sl_host = np.unique(np.concatenate([np.arange(100), rng.integers(0, V, size=384 * 100 // 8)])).astype(np.int32)
+        sl = to_dev(sl_host)
+        us3s = time_kernel(lambda: mq.mq_gemm_argmax_shortlist(qp, pe.packed, sl, sl.numel(), M, V, d, s, pe.scale,
+                                                                tok, val, ws, nws))
+        extras["output_layer_shortlist"] = {"shortlist_rows": int(sl.numel()), "argmax_product_only_us": round(us3s, 2)}
+
         # int16 Transformer-big FFN
         c4 = workloads.config4()
         w4, us4, pk4 = run_ffn(c4, 16, max(10, args.steps // 10), max(3, args.warmup // 5), fused=False)
@@ -322,6 +330,53 @@ def main():
             "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / us4 / 1e6 / PEAK_INT8_TOPS, 2),
             "kernels": pk4}
         del w4
+
+        # single int16 product of the 384-word CPU batch (latency case: reported in microseconds)
+        c1 = workloads.config1()
+        A1 = to_dev(c1["A"])
+        p1_ = mq.prepare_weight(to_dev(c1["Wt"]), 16)
+        b1_ = to_dev(c1["bias"])
+        q1_ = torch.empty(mq.mq_packed_bytes(16, 384, 512), dtype=torch.uint8, device=dev)
+        s1_ = torch.empty(1, dtype=torch.float32, device=dev)
+        Y1_ = torch.empty((384, 512), dtype=torch.float32, device=dev)
+
+        def c1_step():
+            mq.mq_quantize_absmax_pack_f32(A1, 384, 512, 16, q1_, s1_, qws, 4096)
+            mq.mq_gemm_dequant_packed(q1_, p1_.packed, 16, 384, 512, 512, s1_, p1_.scale, b1_, False, Y1_, None)
+
+        c1_step()
+        us1 = time_events(graphed(c1_step), args.steps, args.warmup)
+        extras["single_int16_product_384x512x512"] = {"us_per_call": round(us1, 2), "launches": 3,
+                                                      "TOPS_useful": round(2 * 384 * 512 * 512 / us1 / 1e6, 2)}
+
+        # all parameter products of one greedy decode step of the 6-layer base AAN decoder + output layer
+        c5 = workloads.config5()
+        g5 = []
+        for g in c5["gemms"]:
+            Ad = to_dev(g["A"])
+            N5, K5 = g["Wt"].shape
+            g5.append((Ad, mq.prepare_weight(to_dev(g["Wt"]), 8), to_dev(g["bias"]), bool(g["relu"]), N5, K5,
+                       torch.empty(mq.mq_packed_bytes(8, 300, K5), dtype=torch.uint8, device=dev),
+                       torch.empty(1, dtype=torch.float32, device=dev),
+                       torch.empty((300, N5), dtype=torch.float32, device=dev)))
+        Hd5 = to_dev(c5["output"]["Hd"])
+        pe5 = mq.prepare_weight(to_dev(c5["output"]["E"]), 8)
+
+        def c5_step():
+            for Ad, pw_, b_, relu_, N5, K5, qbuf, sbuf, Ybuf in g5:
+                mq.mq_quantize_absmax_pack_f32(Ad, 300, K5, 8, qbuf, sbuf, qws, 4096)
+                mq.mq_gemm_dequant_packed(qbuf, pw_.packed, 8, 300, N5, K5, sbuf, pw_.scale, b_, relu_, Ybuf, None)
+            mq.mq_quantize_absmax_pack_f32(Hd5, M, d, 8, qp, s, qws, 4096)
+            mq.mq_gemm_argmax_packed(qp, pe5.packed, M, V, d, s, pe5.scale, tok, val, ws, nws)
+
+        c5_step()
+        us5 = time_events(graphed(c5_step), max(10, args.steps // 4), 3)
+        ops5 = sum(2 * 300 * n_ * k_ for _, _, _, _, n_, k_, _, _, _ in g5) + 2 * M * V * d
+        extras["aan_decode_step_products"] = {
+            "workload": "42 int8 parameter products of a 6-layer base AAN decoder step (300 sentences) + greedy output layer",
+            "us_per_step": round(us5, 1), "launches": 3 * len(g5) + 4, "tokens_per_s": round(300 / us5 * 1e6, 0),
+            "TOPS_useful": round(ops5 / us5 / 1e6, 1)}
+        del g5
         result["extras"] = extras
 
     # ------------------------------------------------------------- CPU baseline

@@ -219,6 +219,20 @@ int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, si
                           const float* sA, const float* sW, int32_t* tok, float* maxlogit,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* Short-listed output layer (Section 4.1 "Shortlist": the output product is
+ * restricted to a subset of translation candidates).  shortlist: device int32
+ * [shortlist_len], vocabulary row ids in [0, N), strictly ascending.  Only these
+ * rows of the packed [N x K] embedding are read (gathered by the loads
+ * themselves, no compacted copy is made):
+ *   tok[m] = the listed row with the largest sum (the smallest id on ties),
+ *   maxlogit[m] as in mq_gemm_argmax.
+ * Ids outside [0, N) are undefined behaviour.  Same limits and workspace as
+ * mq_gemm_argmax_packed. */
+int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int32_t* shortlist,
+                             size_t shortlist_len, size_t M, size_t N, size_t K,
+                             const float* sA, const float* sW, int32_t* tok, float* maxlogit,
+                             void* ws, size_t ws_bytes, void* stream);
+
 /* ---- composition -------------------------------------------------------- */
 
 /* Workspace bytes mq_linear_f32 needs. */

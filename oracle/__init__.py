@@ -187,16 +187,30 @@ def linear(A, Wt, bits: int, bias=None, relu: bool = False, sA=None, sW=None):
             "overflow_count": over, "Y": Y}
 
 
-def greedy_output_layer(Hd, E, bits: int = 8, sA=None, sW=None):
-    """Output layer with tied embedding E [V x d] and beam-1 arg-max, no softmax."""
+def greedy_output_layer(Hd, E, bits: int = 8, sA=None, sW=None, shortlist=None):
+    """Output layer with tied embedding E [V x d] and beam-1 arg-max, no softmax.
+
+    shortlist (Section 4.1): ascending vocabulary ids; the product is restricted to those rows
+    of the quantized embedding (the whole embedding is quantized once, with its own multiplier)
+    and the winning position is mapped back to its vocabulary id.
+    """
     if sA is None:
         sA = scale_from_amax(absmax(Hd), bits)
     if sW is None:
         sW = scale_from_amax(absmax(E), bits)
     qA = quant_int(Hd, bits, sA)
     qW = quant_int(E, bits, sW)
-    acc = dot_int(qA, qW)
-    tok, val = argmax_i32(acc, sA, sW)
+    if shortlist is not None:
+        shortlist = np.asarray(shortlist, dtype=np.int64)
+        if shortlist.ndim != 1 or shortlist.size == 0 or np.any(np.diff(shortlist) <= 0) \
+                or shortlist[0] < 0 or shortlist[-1] >= qW.shape[0]:
+            raise ValueError("shortlist must be strictly ascending ids inside the vocabulary")
+        rows = np.ascontiguousarray(qW[shortlist])          # gather only, no arithmetic
+    else:
+        rows = qW
+    acc = dot_int(qA, rows)
+    pos, val = argmax_i32(acc, sA, sW)
+    tok = pos if shortlist is None else shortlist[pos].astype(np.int32)
     return {"sA": np.float32(sA), "sW": np.float32(sW), "qA": qA, "qW": qW, "acc": acc,
             "tok": tok, "maxlogit": val}
 

@@ -272,7 +272,23 @@ int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, si
     return MQ_ERR_ALIGN;
   if (ws_bytes < mq_argmax_ws_bytes(M, N)) return MQ_ERR_WORKSPACE;
   if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
-  return launch_argmax_stream(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, as_stream(stream));
+  return launch_argmax_stream(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, nullptr, 0, as_stream(stream));
+}
+
+int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int32_t* shortlist,
+                             size_t shortlist_len, size_t M, size_t N, size_t K, const float* sA, const float* sW,
+                             int32_t* tok, float* maxlogit, void* ws, size_t ws_bytes, void* stream) {
+  if (packedA == nullptr || packedW == nullptr || shortlist == nullptr || sA == nullptr || sW == nullptr ||
+      tok == nullptr || maxlogit == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K) || shortlist_len == 0 || shortlist_len > N) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(shortlist, 4) || !aligned(sA, 4) ||
+      !aligned(sW, 4) || !aligned(tok, 4) || !aligned(maxlogit, 4) || !aligned(ws, 16))
+    return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_argmax_ws_bytes(M, N)) return MQ_ERR_WORKSPACE;
+  if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
+  return launch_argmax_stream(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, shortlist, shortlist_len,
+                              as_stream(stream));
 }
 
 int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,

@@ -52,6 +52,8 @@ struct ArgmaxParams {
   const uint8_t* packedW;   // embedding, packed 8 bit [N x K]
   unsigned M, N, K;
   unsigned long long* partial;   // [M][gridDim.x]
+  const int32_t* shortlist;      // optional: vocabulary rows to score, ascending; NULL = all N rows
+  unsigned L;                    // candidates: shortlist length, or N
 };
 
 // What lane l feeds to the 16x16x64 MFMA for rows 16 u .. 16 u + 15 of a packed
@@ -66,7 +68,11 @@ __device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, 
 }
 
 // TPW: 16-sentence tiles per wave (8 * TPW * 16 >= M).
-template <int TPW>
+// GATHER: candidates are the rows listed in p.shortlist (the lexical shortlist of Section 4.1: the
+// output product restricted to a subset of the vocabulary).  A unit is then 16 consecutive shortlist
+// positions; since every lane of a direct-to-LDS load supplies its own address, gathering the 16
+// rows costs nothing extra.  Indices are candidate positions; the reduce kernel maps them back.
+template <int TPW, bool GATHER>
 __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p) {
   constexpr int KG = kKG, S = kStages;
   constexpr int STAGE = KG * kFragBytes;
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
   const unsigned kgroups = (unsigned)(dW.kfrags / 2);          // real K groups (<= KG)
-  const unsigned nunits = (unsigned)(dW.nblocks * 2);          // 16-row units of the (padded) embedding
+  const unsigned nunits = GATHER ? (p.L + 15) / 16 : (unsigned)(dW.nblocks * 2);   // 16-candidate units
   const unsigned first = blockIdx.x, stride = gridDim.x;
   const unsigned nlocal = first < nunits ? (nunits - first + stride - 1) / stride : 0;
   const unsigned lane_off = operand16_lane_offset(lane);
@@ -86,10 +92,27 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   // (K shorter than 512: a real group is copied again and its products are zeroed through `hid`)
   const unsigned my_group = (unsigned)wave < kgroups ? (unsigned)wave : kgroups - 1;
   const uint8_t* src_lane = p.packedW + lane_off;
+  // GATHER: this workgroup's candidate rows, 16 per stage, are fetched into LDS once, before any
+  // direct-to-LDS load is in flight (later ordinary loads would have to drain the pipeline)
+  int32_t* rows_lds = reinterpret_cast<int32_t*>(smem + S * STAGE);
+  if (GATHER) {
+    for (unsigned i = threadIdx.x; i < nlocal * 16; i += kWaves * 64) {
+      const unsigned pos = (first + (i / 16) * stride) * 16 + i % 16;
+      rows_lds[i] = pos < p.L ? p.shortlist[pos] : p.shortlist[0];   // positions past the end are masked later
+    }
+    __syncthreads();
+  }
   auto issue = [&](unsigned s) {
-    const size_t unit = (size_t)first + (size_t)s * stride;
+    const uint8_t* src;
+    if (GATHER) {
+      const unsigned r = (unsigned)rows_lds[s * 16 + lane % 16];
+      src = p.packedW + dW.frag_offset(r / 32, 2 * my_group + lane / 32) +
+            (size_t)((r % 32) + 32 * ((lane / 16) % 2)) * 16;
+    } else {
+      src = src_lane + operand16_uniform_offset(dW, (size_t)first + (size_t)s * stride, my_group);
+    }
     __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(src_lane + operand16_uniform_offset(dW, unit, my_group)),
+        (const __attribute__((address_space(1))) void*)src,
         (__attribute__((address_space(3))) void*)(smem + (s % S) * STAGE + wave * kFragBytes), 16, 0, 0);
   };
 #pragma unroll
@@ -179,7 +202,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int v = (sl % 2 == 0) ? acc0[i][r] : acc1[i][r];
-        if (unit0 + r < p.N) best[i][r] = max(best[i][r], (v << 8) | tag);
+        if (unit0 + r < p.L) best[i][r] = max(best[i][r], (v << 8) | tag);
       }
   }
 
@@ -212,7 +235,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 __global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long* __restrict__ partial, unsigned cols,
                                                        unsigned M, const float* __restrict__ sA,
                                                        const float* __restrict__ sW, int32_t* __restrict__ tok,
-                                                       float* __restrict__ maxlogit) {
+                                                       float* __restrict__ maxlogit,
+                                                       const int32_t* __restrict__ shortlist) {
   const int lane = threadIdx.x % 64;
   const unsigned m = blockIdx.x * 4 + threadIdx.x / 64;
   if (m >= M) return;
@@ -230,15 +254,16 @@ __global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long*
   if (lane == 0) {
     const float u = __fdiv_rn(1.0f, __fmul_rn(*sA, *sW));
     const int best = (int)((unsigned)(key >> 32) ^ 0x80000000u);
-    tok[m] = (int32_t)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+    const unsigned pos = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
+    tok[m] = shortlist != nullptr ? shortlist[pos] : (int32_t)pos;
     maxlogit[m] = __fmul_rn((float)best, u);
   }
 }
 
-template <int TPW>
+template <int TPW, bool GATHER>
 int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
-  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes;
-  auto kern = k_argmax_stream<TPW>;
+  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0);
+  auto kern = k_argmax_stream<TPW, GATHER>;
   static bool attr_done = false;
   if (!attr_done) {
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -260,13 +285,16 @@ bool argmax_stream_supported(size_t M, size_t N, size_t K) {
 }
 
 int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
-                         const float* sW, int32_t* tok, float* maxlogit, void* ws, hipStream_t s) {
+                         const float* sW, int32_t* tok, float* maxlogit, void* ws, const int32_t* shortlist,
+                         size_t shortlist_len, hipStream_t s) {
   if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
   ArgmaxParams p;
   p.packedA = static_cast<const uint8_t*>(packedA);
   p.packedW = static_cast<const uint8_t*>(packedW);
   p.M = (unsigned)M; p.N = (unsigned)N; p.K = (unsigned)K;
   p.partial = static_cast<unsigned long long*>(ws);
+  p.shortlist = shortlist;
+  p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
   const PackedDims dW(8, N, K);
   static int cus = 0;               // compute units of the device, asked once
   if (cus == 0) {
@@ -276,21 +304,29 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
       cus = v;
   }
-  const size_t units = dW.nblocks * 2;
+  const size_t units = shortlist != nullptr ? (shortlist_len + 15) / 16 : dW.nblocks * 2;
   unsigned grid = (unsigned)(units < (size_t)cus ? units : (size_t)cus);
   if (grid > (unsigned)kMaxBlocks) grid = kMaxBlocks;
   if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
   const size_t tiles = (M + 15) / 16;
   const int tpw = (int)((tiles + kWaves - 1) / kWaves);
   int rc;
-  switch (tpw) {
-    case 1: rc = launch_stream<1>(p, grid, s); break;
-    case 2: rc = launch_stream<2>(p, grid, s); break;
-    default: rc = launch_stream<3>(p, grid, s); break;
+  if (shortlist != nullptr) {
+    switch (tpw) {
+      case 1: rc = launch_stream<1, true>(p, grid, s); break;
+      case 2: rc = launch_stream<2, true>(p, grid, s); break;
+      default: rc = launch_stream<3, true>(p, grid, s); break;
+    }
+  } else {
+    switch (tpw) {
+      case 1: rc = launch_stream<1, false>(p, grid, s); break;
+      case 2: rc = launch_stream<2, false>(p, grid, s); break;
+      default: rc = launch_stream<3, false>(p, grid, s); break;
+    }
   }
   if (rc != MQ_OK) return rc;
   hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, p.partial, grid, (unsigned)M,
-                     sA, sW, tok, maxlogit);
+                     sA, sW, tok, maxlogit, shortlist);
   return check_hip(hipGetLastError());
 }
 

@@ -103,6 +103,7 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
 size_t argmax_stream_ws_bytes(size_t M);
 bool argmax_stream_supported(size_t M, size_t N, size_t K);
 int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
-                         const float* sW, int32_t* tok, float* maxlogit, void* ws, hipStream_t s);
+                         const float* sW, int32_t* tok, float* maxlogit, void* ws, const int32_t* shortlist,
+                         size_t shortlist_len, hipStream_t s);
 
 }  // namespace mq

@@ -628,3 +628,46 @@ def test_two_pass_requantizing_product():
     # padding of the packed output is zero: a prepared copy of the same integers has identical bytes
     ref = mq.prepare_weight(dev(oq.astype(np.float32)), 8, scale=torch.ones(1, dtype=torch.float32, device=DEV))
     assert torch.equal(out, ref.packed)
+
+
+# ------------------------------------------------ short-listed output layer
+
+def gpu_greedy_shortlist(Hd, E, shortlist):
+    pw = mq.prepare_weight(dev(E), 8)
+    pa, s = gpu_quantize_pack(Hd, 8)
+    M, K = Hd.shape
+    N = E.shape[0]
+    sl = dev(np.asarray(shortlist, dtype=np.int32))
+    nbytes = mq.mq_argmax_ws_bytes(M, N)
+    ws = torch.full((nbytes,), 0xEE, dtype=torch.uint8, device=DEV)
+    tok = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+    val = torch.empty(M, dtype=torch.float32, device=DEV)
+    mq.mq_gemm_argmax_shortlist(pa, pw.packed, sl, sl.numel(), M, N, K, s, pw.scale, tok, val, ws, nbytes)
+    return host(tok), host(val)
+
+
+@pytest.mark.parametrize("M,V,d,L", [(1, 1, 1, 1), (12, 777, 64, 1), (12, 777, 64, 15), (33, 4100, 96, 1000),
+                                     (300, 36000, 512, 4321), (300, 36000, 512, 36000), (130, 9000, 192, 8999)])
+def test_greedy_shortlist(M, V, d, L):
+    c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + L)
+    rng = np.random.default_rng(L + V)
+    sl = np.sort(rng.choice(V, size=L, replace=False))
+    o = oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=sl)
+    tok, val = gpu_greedy_shortlist(c["Hd"], c["E"], sl)
+    assert np.array_equal(tok, o["tok"])
+    assert np.array_equal(val, o["maxlogit"])
+
+
+def test_greedy_shortlist_ties_and_frequent_plus_translations_shape():
+    # list shaped like the paper's: the 100 most frequent ids plus 100 candidates per source word
+    V, d, M = 36000, 512, 15
+    c = workloads.config3(M=M, V=V, d=d, seed_extra=77)
+    rng = np.random.default_rng(5)
+    sl = np.unique(np.concatenate([np.arange(100), rng.integers(0, V, size=384 * 100 // 8)]))
+    E = c["E"].copy()
+    E[sl[40]] = E[sl[3000]]          # duplicate rows inside the list: the smaller id has to win
+    E[sl[-1]] = E[sl[3000]]
+    o = oracle.greedy_output_layer(c["Hd"], E, shortlist=sl)
+    tok, val = gpu_greedy_shortlist(c["Hd"], E, sl)
+    assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
+    assert np.all(np.isin(tok, sl))

@@ -353,3 +353,25 @@ def test_memoized_weight_equals_requantizing_every_call():
     # transposing before or after quantizing commutes for a per-tensor scale
     B = np.ascontiguousarray(c["W1t"].T)
     assert np.array_equal(oracle.quant_int(B, 8, sW).T, qW)
+
+
+def test_shortlisted_output_layer_is_argmax_over_the_listed_rows():
+    # Section 4.1: the output product restricted to a candidate subset.  Pinned against numpy on the
+    # full logits: the winner among the listed ids is the masked arg-max of the full product.
+    c = workloads.config3(M=9, V=500, d=32, seed_extra=4)
+    full = oracle.greedy_output_layer(c["Hd"], c["E"])
+    rng = np.random.default_rng(12)
+    sl = np.sort(rng.choice(500, size=77, replace=False))
+    r = oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=sl)
+    masked = np.full(full["acc"].shape, np.iinfo(np.int64).min, dtype=np.int64)
+    masked[:, sl] = full["acc"][:, sl]
+    assert np.array_equal(r["tok"], np.argmax(masked, axis=1))
+    assert np.array_equal(r["maxlogit"], (masked.max(1).astype(np.float32) * (np.float32(1) / (r["sA"] * r["sW"]))))
+    # the full vocabulary as a shortlist changes nothing; a one-entry list always returns that entry
+    assert np.array_equal(oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=np.arange(500))["tok"], full["tok"])
+    assert np.all(oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=[123])["tok"] == 123)
+    # if the unrestricted winner is listed it stays the winner
+    keep = np.unique(np.concatenate([sl, full["tok"]]))
+    assert np.array_equal(oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=keep)["tok"], full["tok"])
+    with pytest.raises(ValueError):
+        oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=[5, 5, 7])
