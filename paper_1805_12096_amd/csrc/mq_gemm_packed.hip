@@ -100,6 +100,18 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
           (const __attribute__((address_space(1))) void*)(src[j] + (size_t)kt * (FPB * kFragBytes)),
           (__attribute__((address_space(3))) void*)(dst + j * kFragBytes), 16, 0, 0);
   };
+  // One load of a stage, without a branch: past the last stage the same instruction re-reads stage 0
+  // into a per-wave dummy slot behind the stages, so that every K step issues exactly L loads and the
+  // loads can sit between MFMAs (a burst of them right after the barrier stalls in the address queue
+  // and holds up the wave's MFMAs with it).
+  auto issue_one = [&](unsigned kt, int j) {
+    const bool real = kt < KT;
+    const unsigned k2 = real ? kt : 0;
+    uint8_t* dst = real ? smem + (kt % S) * STAGE + (wave * L + j) * kFragBytes : smem + S * STAGE + wave * kFragBytes;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src[j] + (size_t)k2 * (FPB * kFragBytes)),
+        (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+  };
 
   v16i acc[TM][TN][NACC];
 #pragma unroll
@@ -166,9 +178,16 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     }
   };
 
+  if constexpr (PF) {
 #pragma unroll
-  for (int st = 0; st < S - 1; ++st)
-    if ((unsigned)st < KT) issue(st);
+    for (int st = 0; st < S - 1; ++st)
+      if ((unsigned)st < KT) issue(st);
+  } else {
+#pragma unroll
+    for (int st = 0; st < S - 1; ++st)
+#pragma unroll
+      for (int j = 0; j < L; ++j) issue_one(st, j);
+  }
   if constexpr (PF) {
     Frags f0, f1;
     if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
@@ -198,20 +217,30 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     // set: fragments are read right before use; with two waves per SIMD the other wave's MFMAs
     // cover the LDS latency.  One barrier per K step, as in the simple pipeline.
     Frags f;
+    constexpr int EVERY = (2 * NM) / L > 0 ? (2 * NM) / L : 1;     // MFMAs between two loads
     for (unsigned kt = 0; kt < KT; ++kt) {
-      if (kt + S - 2 < KT) wait_vmcnt((S - 2) * L);
-      else wait_vmcnt(0);
+      // every step issues L loads (real or dummy), so S - 2 steps' worth may always stay in flight
+      wait_vmcnt((S - 2) * L);
       block_barrier();
-      if (kt + S - 1 < KT) issue(kt + S - 1);
       const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
+      int issued = 0;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
         for (int r = 0; r < R; ++r) read_one(f, cur, ks, r);
 #pragma unroll
-        for (int i = 0; i < NM; ++i) mfma_one(f, i);
+        for (int i = 0; i < NM; ++i) {
+          mfma_one(f, i);
+          if ((ks * NM + i) % EVERY == EVERY - 1 && issued < L) {
+            issue_one(kt + S - 1, issued);
+            ++issued;
+          }
+        }
       }
+#pragma unroll
+      for (; issued < L; ++issued) issue_one(kt + S - 1, issued);
     }
+    wait_vmcnt(0);     // dummy loads of the tail must not outlive the stages' reuse in the epilogue
   }
 
   if constexpr (EPI == kPAmax || EPI == kPRequant) {
@@ -315,7 +344,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 template <int BITS, int BM, int BN, int WM, int WN, int S, int EPI, bool PF = true>
 int launch_pp(const GemmArgs& a, hipStream_t s) {
   constexpr int NPL = BITS == 16 ? 2 : 1;
-  constexpr size_t smem = (size_t)S * ((BM / 32) + (BN / 32)) * 2 * NPL * kFragBytes;
+  constexpr size_t smem = (size_t)S * ((BM / 32) + (BN / 32)) * 2 * NPL * kFragBytes + (PF ? 0 : WM * WN * kFragBytes);
   static_assert(smem <= 160 * 1024, "LDS budget");
   Params p{};
   p.qA = static_cast<const uint8_t*>(a.qA);
