@@ -192,6 +192,34 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
                            const float* sA, const float* sW, const float* bias, int relu,
                            const void* ws, size_t ws_bytes, float* scale_out, void* packed_out, void* stream);
 
+/* Single-pass variant for multipliers fixed in advance, the paper's own scheme
+ * (Section 4.2: 2^10 for 16 bit, 127/2 after clipping to [-2, 2] for 8 bit):
+ * quant_int of the next product's input is done in the epilogue of the product
+ * that creates it, with the given multiplier s_out[0] (device float[1], read
+ * only); values beyond +-127 / s_out saturate, which is the clipping of Section
+ * 4.2.  No abs-max pass, no workspace. */
+int mq_gemm_requant_fixed_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                 const float* sA, const float* sW, const float* bias, int relu,
+                                 const float* s_out, void* packed_out, void* stream);
+
+/* ---- auto-tuning (Section 4.4) ------------------------------------------
+ * The paper times alternative implementations per tensor shape over a fixed
+ * number of runs and then uses the fastest for all following calls.  Here the
+ * alternatives are the tile configurations of the packed product kernels.
+ * mq_autotune_gemm times every configuration valid for `bits` on an [M x K] x
+ * [N x K] problem (`runs` launches each, on dummy operands inside ws), records
+ * the fastest in a process-wide table keyed by (bits, M, N, K) -- which all
+ * packed products of that shape consult from then on, unless
+ * mq_set_gemm_variant forces a configuration -- and reports it.  Results of the
+ * products never depend on the configuration.  UNLIKE every other call this one
+ * synchronizes with the stream (it reads timers) and is meant for set-up time.
+ * ws: device, 256-byte aligned, mq_autotune_ws_bytes(bits, M, N, K) bytes.
+ * best_variant / best_us (host pointers, may be NULL) receive the choice and its
+ * average microseconds.  Not thread safe; the table holds 256 shapes. */
+size_t mq_autotune_ws_bytes(int bits, size_t M, size_t N, size_t K);
+int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws, size_t ws_bytes,
+                     void* stream, int* best_variant, float* best_us);
+
 /* ---- greedy output layer (Section 2.3) ---------------------------------- */
 
 /* Workspace bytes mq_gemm_argmax needs for an M-row problem. */

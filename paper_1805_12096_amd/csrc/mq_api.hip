@@ -11,6 +11,30 @@ int check_hip(hipError_t e) {
   return MQ_ERR_HIP;
 }
 
+// ---- auto-tuner table (arxiv 1805.12096, Section 4.4: hash shapes and algorithm ids, time the
+// alternatives, keep the fastest for all following calls) ---------------------------------------
+namespace {
+struct TunedEntry { int bits; size_t M, N, K; int variant; };
+constexpr int kTunedSlots = 256;
+TunedEntry g_tuned[kTunedSlots];
+int g_tuned_count = 0;
+}  // namespace
+
+int tuned_variant(int bits, size_t M, size_t N, size_t K) {
+  for (int i = 0; i < g_tuned_count; ++i)
+    if (g_tuned[i].bits == bits && g_tuned[i].M == M && g_tuned[i].N == N && g_tuned[i].K == K) return g_tuned[i].variant;
+  return 0;
+}
+
+void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant) {
+  for (int i = 0; i < g_tuned_count; ++i)
+    if (g_tuned[i].bits == bits && g_tuned[i].M == M && g_tuned[i].N == N && g_tuned[i].K == K) {
+      g_tuned[i].variant = variant;
+      return;
+    }
+  if (g_tuned_count < kTunedSlots) g_tuned[g_tuned_count++] = TunedEntry{bits, M, N, K, variant};
+}
+
 namespace {
 
 constexpr size_t kMaxElems = (size_t)1 << 40;
@@ -251,6 +275,83 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
   a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
   a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
   return launch_gemm_requant(a, static_cast<const float*>(ws), scale_out, packed_out, as_stream(stream));
+}
+
+int mq_gemm_requant_fixed_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                 const float* sA, const float* sW, const float* bias, int relu,
+                                 const float* s_out, void* packed_out, void* stream) {
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || s_out == nullptr ||
+      packed_out == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(s_out, 4) ||
+      !aligned(packed_out, 16))
+    return MQ_ERR_ALIGN;
+  if (bias != nullptr && !aligned(bias, 4)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
+  return launch_gemm_requant_fixed(a, s_out, packed_out, as_stream(stream));
+}
+
+size_t mq_autotune_ws_bytes(int bits, size_t M, size_t N, size_t K) {
+  if (!bits_ok(bits) || !dims_ok(M, N, K)) return 0;
+  return round_up(PackedDims(bits, M, K).total_bytes(), 256) + round_up(PackedDims(bits, N, K).total_bytes(), 256) +
+         round_up(M * N * sizeof(float), 256) + 256;
+}
+
+int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws, size_t ws_bytes, void* stream,
+                     int* best_variant, float* best_us) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K) || runs <= 0) return MQ_ERR_SHAPE;
+  if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_autotune_ws_bytes(bits, M, N, K)) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  const size_t a_bytes = round_up(PackedDims(bits, M, K).total_bytes(), 256);
+  const size_t w_bytes = round_up(PackedDims(bits, N, K).total_bytes(), 256);
+  void* pa = base;
+  void* pw = base + a_bytes;
+  float* Y = reinterpret_cast<float*>(base + a_bytes + w_bytes);
+  float* scal = reinterpret_cast<float*>(base + a_bytes + w_bytes + round_up(M * N * sizeof(float), 256));
+  // operand bytes only need to be valid memory; give them a fixed non-trivial pattern and unit multipliers
+  int rc = check_hip(hipMemsetAsync(pa, 0x35, a_bytes, s));
+  if (rc == MQ_OK) rc = check_hip(hipMemsetAsync(pw, 0xC7, w_bytes, s));
+  const float ones[2] = {1.0f, 1.0f};
+  if (rc == MQ_OK) rc = check_hip(hipMemcpyAsync(scal, ones, sizeof ones, hipMemcpyHostToDevice, s));
+  if (rc != MQ_OK) return rc;
+  hipEvent_t e0, e1;
+  if (check_hip(hipEventCreate(&e0)) != MQ_OK || check_hip(hipEventCreate(&e1)) != MQ_OK) return MQ_ERR_HIP;
+  GemmArgs a{};
+  a.qA = pa; a.packedW = pw; a.bits = bits; a.M = M; a.N = N; a.K = K;
+  a.sA = scal; a.sW = scal + 1; a.relu = 0; a.Y = Y;
+  const int saved = forced_variant();
+  int best = 0;
+  float best_ms = 0.f;
+  for (int v = 1; v <= packed_variant_count(bits); ++v) {
+    set_forced_variant(v);
+    rc = launch_gemm_packed(a, kEpiDequant, s);          // untimed first call: code upload, attribute set-up
+    if (rc == MQ_ERR_UNSUPPORTED) continue;
+    if (rc != MQ_OK) break;
+    hipEventRecord(e0, s);
+    for (int i = 0; i < runs && rc == MQ_OK; ++i) rc = launch_gemm_packed(a, kEpiDequant, s);
+    hipEventRecord(e1, s);
+    if (rc != MQ_OK) break;
+    if (check_hip(hipEventSynchronize(e1)) != MQ_OK) { rc = MQ_ERR_HIP; break; }
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, e0, e1);
+    if (best == 0 || ms < best_ms) { best = v; best_ms = ms; }
+  }
+  set_forced_variant(saved);
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (rc != MQ_OK && rc != MQ_ERR_UNSUPPORTED) return rc;
+  if (best == 0) return MQ_ERR_UNSUPPORTED;
+  set_tuned_variant(bits, M, N, K, best);
+  if (best_variant != nullptr) *best_variant = best;
+  if (best_us != nullptr) *best_us = best_ms * 1000.0f / (float)runs;
+  return MQ_OK;
 }
 
 size_t mq_argmax_ws_bytes(size_t M, size_t N) {

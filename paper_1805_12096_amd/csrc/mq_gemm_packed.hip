@@ -278,18 +278,23 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
         p.partial[blockIdx.x] = m;
       }
     } else {
-      // multiplier of the output from the partial maxima of the first pass (every block forms it)
-      float amax = 0.f;
-      for (unsigned i = tid; i < p.npartial; i += NW * 64) amax = fmaxf(amax, p.partial[i]);
+      float s2;
+      if (p.partial != nullptr) {
+        // multiplier of the output from the partial maxima of the first pass (every block forms it)
+        float amax = 0.f;
+        for (unsigned i = tid; i < p.npartial; i += NW * 64) amax = fmaxf(amax, p.partial[i]);
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-      if (lane == 0) red[wave] = amax;
-      __syncthreads();
-      amax = red[0];
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        if (lane == 0) red[wave] = amax;
+        __syncthreads();
+        amax = red[0];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) amax = fmaxf(amax, red[w]);
-      const float s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
-      if (blockIdx.x == 0 && tid == 0) *p.s_out = s2;
+        for (int w = 1; w < NW; ++w) amax = fmaxf(amax, red[w]);
+        s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
+        if (blockIdx.x == 0 && tid == 0) *p.s_out = s2;
+      } else {
+        s2 = *p.s_out;      // fixed multiplier supplied by the caller (the paper's scheme): single pass
+      }
       // operands were swapped: register r of lane l is (n, m) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32),
       // so r = 4 q .. 4 q + 3 are four consecutive n of one row m: one dword of the packed output.
       // Each 32 x 32 sub-tile is exactly one 1 KB fragment of the output; it is assembled in LDS (the
@@ -399,7 +404,8 @@ namespace {
 // Tile configuration of the fused 8-bit passes: the large tile when it fills the chip, else the small one.
 int fused_variant(const GemmArgs& a) {
   int v = forced_variant();
-  if (v <= 0) v = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200 ? 1 : 3;
+  if (v <= 0) v = tuned_variant(8, a.M, a.N, a.K);
+  if (v <= 0 || v == 2) v = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200 ? 1 : 3;
   return v;
 }
 size_t tiles_of(int variant, size_t M, size_t N) {
@@ -413,6 +419,8 @@ size_t tiles_of(int variant, size_t M, size_t N) {
   return ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
 }
 }  // namespace
+
+int packed_variant_count(int bits) { return bits == 8 ? 7 : 5; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
@@ -433,8 +441,20 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
   return launch_pp_variant<8, kPRequant>(b, v, s);
 }
 
+// Single-pass re-quantizing product with a multiplier known in advance (fixed multipliers as in the
+// paper): quant_int of the next layer's input happens in the producing epilogue.
+int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s) {
+  GemmArgs b = a;
+  b.partial = nullptr;
+  b.npartial = 0;
+  b.s_out = const_cast<float*>(s_fixed);
+  b.packed_out = packed_out;
+  return launch_pp_variant<8, kPRequant>(b, fused_variant(a), s);
+}
+
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   int v = forced_variant();
+  if (v <= 0) v = tuned_variant(a.bits, a.M, a.N, a.K);     // frozen by mq_autotune_gemm for this shape, or 0
   if (v <= 0) {
     // Shape heuristic standing in for a per-shape timing run: the largest tile that still gives
     // every compute unit work, smaller tiles for small problems.

@@ -98,6 +98,11 @@ int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bi
 size_t gemm_amax_partials(size_t M, size_t N);
 int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s);
 int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, void* packed_out, hipStream_t s);
+int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
+// Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
+int tuned_variant(int bits, size_t M, size_t N, size_t K);
+void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant);
+int packed_variant_count(int bits);
 
 // Streaming arg-max product for decode-sized batches (both operands packed, 8 bit).
 size_t argmax_stream_ws_bytes(size_t M);

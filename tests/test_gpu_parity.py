@@ -671,3 +671,52 @@ def test_greedy_shortlist_ties_and_frequent_plus_translations_shape():
     tok, val = gpu_greedy_shortlist(c["Hd"], E, sl)
     assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
     assert np.all(np.isin(tok, sl))
+
+
+# ---------------------------------- fixed multipliers (the paper's scheme) and auto-tuning
+
+def test_ffn_with_fixed_multipliers_single_pass():
+    # Section 4.2: 8-bit inputs clipped to [-2, 2] and scaled by 127/2; no abs-max anywhere.  The
+    # intermediate is quantized in the epilogue of the product that creates it.
+    c = workloads.ffn(2, 200, 128, 384, 0.04, 8, seed_extra=5)
+    A = c["A"] * np.float32(1.5)                  # some values beyond +-2: they saturate at +-127
+    W1, W2 = c["W1t"] * np.float32(8), c["W2t"] * np.float32(8)
+    fixed = np.float32(63.5)
+    o1 = oracle.linear(A, W1, 8, c["b1"], True, sA=fixed, sW=fixed)
+    assert np.abs(o1["qA"]).max() == 127 and (np.abs(A) > 2).any()
+    oqH = oracle.quant_int(o1["Y"], 8, fixed)
+    o2 = oracle.dequant_bias(oracle.dot_int(oqH, oracle.quant_int(W2, 8, fixed)), fixed, fixed, c["b2"], False)
+    M, d = A.shape
+    f = W1.shape[0]
+    sc = torch.full((1,), 63.5, dtype=torch.float32, device=DEV)
+    p1 = mq.prepare_weight(dev(W1), 8, scale=sc)
+    p2 = mq.prepare_weight(dev(W2), 8, scale=sc)
+    qA = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_pack_f32(dev(A), M, d, 8, sc, qA)
+    qH = torch.full((mq.mq_packed_bytes(8, M, f),), 0x44, dtype=torch.uint8, device=DEV)
+    mq.mq_gemm_requant_fixed_packed(qA, p1.packed, M, f, d, sc, p1.scale, dev(c["b1"]), True, sc, qH)
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+    mq.mq_gemm_dequant_packed(qH, p2.packed, 8, M, d, f, sc, p2.scale, dev(c["b2"]), False, Y, None)
+    q = torch.empty((M, f), dtype=torch.int8, device=DEV)
+    mq.mq_unpack_weight(qH, 8, M, f, q)
+    assert np.array_equal(host(q), oqH)
+    assert np.array_equal(host(Y), o2)
+
+
+def test_autotune_freezes_a_variant_and_results_stay_identical():
+    M, N, K = 300, 512, 256
+    p = workloads.random_problem(909, M, N, K)
+    o = oracle.linear(p["A"], p["Wt"], 8, p["bias"], False)
+    nbytes = mq.mq_autotune_ws_bytes(8, M, N, K)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    best, us = mq.mq_autotune_gemm(8, M, N, K, 20, ws, nbytes)
+    assert 1 <= best <= 7 and us > 0
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    pa, s = gpu_quantize_pack(p["A"], 8)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    mq.mq_gemm_dequant_packed(pa, pw.packed, 8, M, N, K, s, pw.scale, dev(p["bias"]), False, Y, None)
+    assert np.array_equal(host(Y), o["Y"])
+    best16, _ = mq.mq_autotune_gemm(16, 64, 96, 128, 5, torch.empty(mq.mq_autotune_ws_bytes(16, 64, 96, 128),
+                                                                      dtype=torch.uint8, device=DEV),
+                                    mq.mq_autotune_ws_bytes(16, 64, 96, 128))
+    assert 1 <= best16 <= 5
