@@ -192,6 +192,24 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
                            const float* sA, const float* sW, const float* bias, int relu,
                            const void* ws, size_t ws_bytes, float* scale_out, void* packed_out, void* stream);
 
+/* The same result in ONE pass over the operands, for results small enough that
+ * every 256 x 256 tile is resident on the chip at once (at most one tile per
+ * compute unit; MQ_ERR_UNSUPPORTED beyond that, nothing computed): each tile
+ * keeps its sums in registers while all workgroups agree on max|y| through
+ * two words of ws, then quantizes and stores.  Two launches (clearing the two
+ * words, the product).  The wait for the other workgroups is bounded (0.5 s);
+ * should it ever expire, scale_out[0] is set to NaN so that nothing computed
+ * from it can pass for a result.  Arguments and results as
+ * mq_gemm_requant_packed; ws is written here.
+ * mq_set_barrier_timeout_us changes the bound on the wait (default 500000, at
+ * most 10^7; 0 makes every waiter give up at once, which is how the tests
+ * reach the failure path without a kernel that hangs). */
+int mq_set_barrier_timeout_us(unsigned us);
+int mq_gemm_requant_single_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                  const float* sA, const float* sW, const float* bias, int relu,
+                                  void* ws, size_t ws_bytes, float* scale_out, void* packed_out,
+                                  void* stream);
+
 /* Single-pass variant for multipliers fixed in advance, the paper's own scheme
  * (Section 4.2: 2^10 for 16 bit, 127/2 after clipping to [-2, 2] for 8 bit):
  * quant_int of the next product's input is done in the epilogue of the product
@@ -288,12 +306,18 @@ size_t mq_ffn_ws_bytes(size_t M, size_t d, size_t f);
  * intermediate H never goes to memory: the first product runs twice, once
  * reduced to max|H| and once re-quantized with the multiplier that maximum
  * gives, which is cheaper on this machine than writing and re-reading 4 M f bytes.
- * Five launches, no atomics, no host synchronisation.
+ * Five launches, no atomics, no host synchronisation.  When the intermediate
+ * result is small enough for one tile per resident workgroup (M f <= 256 x 256 x
+ * the number of compute units), the two passes become ONE launch:
+ * the sums wait in registers while the grid agrees on max|H| (four launches).
+ * mq_set_ffn_single_pass(0) switches that off (two passes always); results are
+ * identical either way.
  *   A: device float [M x d], 16-byte aligned.  packedW1: 8-bit packed [f x d];
  *   packedW2: 8-bit packed [d x f]; sW1, sW2: their multipliers (device float[1]);
  *   b1: device float [f] or NULL; b2: device float [d] or NULL; Y: device float [M x d];
  *   ws: device, 256-byte aligned, mq_ffn_ws_bytes(M, d, f) bytes, contents
  *   irrelevant on entry, undefined on return. */
+int mq_set_ffn_single_pass(int enable);
 int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
                   const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                   void* ws, size_t ws_bytes, void* stream);

@@ -19,7 +19,7 @@ __all__ = [
     "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_autotune_ws_bytes", "mq_autotune_gemm",
     "PreparedWeight", "prepare_weight",
@@ -52,7 +52,7 @@ def exported_symbols():
             "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
-            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32",
+            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
             "mq_autotune_ws_bytes", "mq_autotune_gemm"]
@@ -97,10 +97,13 @@ def load_library():
     lib.mq_gemm_amax_ws_bytes.argtypes = [sz, sz]
     lib.mq_gemm_amax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp]
     lib.mq_gemm_requant_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp, vp, vp]
+    lib.mq_gemm_requant_single_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp, vp, vp]
     lib.mq_gemm_requant_fixed_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, vp, vp]
     lib.mq_autotune_ws_bytes.restype = sz
     lib.mq_autotune_ws_bytes.argtypes = [ci, sz, sz, sz]
     lib.mq_autotune_gemm.argtypes = [ci, sz, sz, sz, ci, vp, sz, vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
+    lib.mq_set_ffn_single_pass.argtypes = [ci]
+    lib.mq_set_barrier_timeout_us.argtypes = [ctypes.c_uint]
     lib.mq_ffn_ws_bytes.restype = sz
     lib.mq_ffn_ws_bytes.argtypes = [sz, sz, sz]
     lib.mq_ffn_i8_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -263,6 +266,14 @@ def mq_gemm_requant_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, ws, ws
                                                  _stream(stream)), "mq_gemm_requant_packed")
 
 
+def mq_gemm_requant_single_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, ws, ws_bytes, scale_out,
+                                  packed_out, stream=None):
+    _check(load_library().mq_gemm_requant_single_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW),
+                                                        _p(bias), int(relu), _p(ws), ws_bytes, _p(scale_out),
+                                                        _p(packed_out), _stream(stream)),
+           "mq_gemm_requant_single_packed")
+
+
 def mq_gemm_requant_fixed_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, s_out, packed_out, stream=None):
     _check(load_library().mq_gemm_requant_fixed_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(bias),
                                                        int(relu), _p(s_out), _p(packed_out), _stream(stream)),
@@ -280,6 +291,14 @@ def mq_autotune_gemm(bits, M, N, K, runs, ws, ws_bytes, stream=None):
     _check(load_library().mq_autotune_gemm(bits, M, N, K, runs, _p(ws), ws_bytes, _stream(stream),
                                            ctypes.byref(best), ctypes.byref(us)), "mq_autotune_gemm")
     return int(best.value), float(us.value)
+
+
+def mq_set_ffn_single_pass(enable) -> None:
+    _check(load_library().mq_set_ffn_single_pass(int(bool(enable))), "mq_set_ffn_single_pass")
+
+
+def mq_set_barrier_timeout_us(us) -> None:
+    _check(load_library().mq_set_barrier_timeout_us(int(us)), "mq_set_barrier_timeout_us")
 
 
 def mq_ffn_ws_bytes(M, d, f) -> int:

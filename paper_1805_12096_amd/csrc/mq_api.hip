@@ -238,7 +238,10 @@ int mq_gemm_dequant_packed(const void* packedA, const void* packedW, int bits, s
 
 size_t mq_gemm_amax_ws_bytes(size_t M, size_t N) {
   if (M == 0 || N == 0 || M >= kMaxDim || N >= kMaxDim) return 0;
-  return round_up(gemm_amax_partials(M, N) * sizeof(float), 256);
+  // room for the two-pass partial maxima or for the single-pass barrier words, whichever is larger
+  const size_t partials = round_up(gemm_amax_partials(M, N) * sizeof(float), 256);
+  const size_t barrier = round_up(kBarrierWords * sizeof(unsigned), 256);
+  return partials > barrier ? partials : barrier;
 }
 
 namespace {
@@ -275,6 +278,22 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
   a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
   a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
   return launch_gemm_requant(a, static_cast<const float*>(ws), scale_out, packed_out, as_stream(stream));
+}
+
+int mq_gemm_requant_single_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                  const float* sA, const float* sW, const float* bias, int relu, void* ws,
+                                  size_t ws_bytes, float* scale_out, void* packed_out, void* stream) {
+  int rc = fused_pass_checks(packedA, packedW, M, N, K, sA, sW, bias, ws, ws_bytes);
+  if (rc != MQ_OK) return rc;
+  if (scale_out == nullptr || packed_out == nullptr) return MQ_ERR_NULL;
+  if (!aligned(scale_out, 4) || !aligned(packed_out, 16)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
+  unsigned* barrier = static_cast<unsigned*>(ws);
+  rc = launch_clear_words(barrier, kBarrierWords, as_stream(stream));
+  if (rc != MQ_OK) return rc;
+  return launch_gemm_requant_coop(a, scale_out, packed_out, barrier, as_stream(stream));
 }
 
 int mq_gemm_requant_fixed_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
@@ -417,18 +436,32 @@ namespace mq {
 namespace {
 // Scratch layout of mq_ffn_i8_f32.
 struct FfnWs {
-  size_t off_part1, off_part2, off_scal, off_qA, off_qH, total;
+  size_t off_part1, off_part2, off_scal, off_bar, off_qA, off_qH, total;
   FfnWs(size_t M, size_t d, size_t f) {
     off_part1 = 0;
     off_part2 = round_up(off_part1 + kAbsmaxPartials * sizeof(float), 256);
     off_scal = round_up(off_part2 + gemm_amax_partials(M, f) * sizeof(float), 256);
-    off_qA = off_scal + 256;
+    off_bar = off_scal + 256;
+    off_qA = off_bar + round_up(kBarrierWords * sizeof(unsigned), 256);
     off_qH = round_up(off_qA + PackedDims(8, M, d).total_bytes(), 256);
     total = round_up(off_qH + PackedDims(8, M, f).total_bytes(), 256);
   }
 };
 }  // namespace
 }  // namespace mq
+
+static int g_ffn_single_pass = 1;
+
+int mq_set_barrier_timeout_us(unsigned us) {
+  if (us > 10u * 1000 * 1000) return MQ_ERR_SHAPE;
+  set_barrier_timeout_ticks(100ull * us);       // the wall clock runs at 100 MHz
+  return MQ_OK;
+}
+
+int mq_set_ffn_single_pass(int enable) {
+  g_ffn_single_pass = enable != 0;
+  return MQ_OK;
+}
 
 size_t mq_ffn_ws_bytes(size_t M, size_t d, size_t f) {
   if (!dims_ok(M, f, d)) return 0;
@@ -457,16 +490,22 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   void* qA = base + L.off_qA;
   void* qH = base + L.off_qH;
   // a1 + a2: abs-max and quant_int of the input (two launches, no atomics)
-  int rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s);
+  unsigned* barrier = reinterpret_cast<unsigned*>(base + L.off_bar);     // cleared by the first kernel below
+  int rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s, barrier);
   if (rc != MQ_OK) return rc;
   // a4 + a5, first pass: only the abs-max of relu(A W1 + b1) leaves the chip
   GemmArgs g1{};
   g1.qA = qA; g1.packedW = packedW1; g1.bits = 8; g1.M = M; g1.N = f; g1.K = d;
   g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1;
-  rc = launch_gemm_amax_partial(g1, part2, s);
-  if (rc != MQ_OK) return rc;
-  // second pass: the same sums again, quantized with the multiplier now known, stored as packed int8
-  rc = launch_gemm_requant(g1, part2, sH, qH, s);
+  // when the first product's result is at most one tile per resident workgroup, one launch does both
+  // passes with the sums held in registers across a grid-wide barrier
+  rc = g_ffn_single_pass ? launch_gemm_requant_coop(g1, sH, qH, barrier, s) : MQ_ERR_UNSUPPORTED;
+  if (rc == MQ_ERR_UNSUPPORTED) {
+    rc = launch_gemm_amax_partial(g1, part2, s);
+    if (rc != MQ_OK) return rc;
+    // second pass: the same sums again, quantized with the multiplier now known, stored as packed int8
+    rc = launch_gemm_requant(g1, part2, sH, qH, s);
+  }
   if (rc != MQ_OK) return rc;
   // second product with the float epilogue
   GemmArgs g2{};

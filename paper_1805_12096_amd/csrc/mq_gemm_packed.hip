@@ -14,19 +14,40 @@
 //   stage kt - 1's slot, multiply stage kt.
 // The compiler does not track LDS written by these loads, so the waits are
 // explicit and the barrier is fenced against compile-time motion by hand.
+#include <type_traits>
+
 #include "mq_gemm_common.h"
 
 namespace mq {
 
 namespace {
 
-enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3 };
+// Slots of the grid-wide barrier of the single-pass epilogue: one per workgroup, read 64 at a time.
+constexpr unsigned kBarrierSlots = 256;
+static_assert(kBarrierSlots % 64 == 0 && kBarrierSlots + 1 <= kBarrierWords, "barrier layout");
+
+enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3, kPCoop = 4 };
 
 // One element of quant_int (8 bit): binary32 multiply, round half to even, clamp, NaN -> 0.
 __device__ __forceinline__ int quant8(float x, float s) {
   const float r = rintf(__fmul_rn(x, s));
-  const float c = fminf(fmaxf(r, -127.0f), 127.0f);
-  return (r != r) ? 0 : (int)c;
+  // the hardware conversion saturates and maps NaN to 0, which a C cast does not promise
+  int i;
+  asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(r));
+  return min(max(i, -127), 127);
+}
+
+// Maximum of an unsigned value over the 64 lanes, the same in every lane: inside rows of 16 lanes by
+// data-parallel-primitive moves (swap neighbours, swap pairs, mirror the half rows, mirror the rows),
+// across the four rows through scalar registers.
+__device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
+  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, true));   // row_mirror
+  const unsigned a = __builtin_amdgcn_readlane((int)x, 0), b = __builtin_amdgcn_readlane((int)x, 16);
+  const unsigned c = __builtin_amdgcn_readlane((int)x, 32), d = __builtin_amdgcn_readlane((int)x, 48);
+  return max(max(a, b), max(c, d));
 }
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -69,6 +90,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   const int lane = tid % 64;
   const int wave = tid / 64;
   const int wm = wave / WN, wn = wave % WN;
+#ifdef MQ_TS
+  if (EPI == kPCoop && tid == 0) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8] = wall_clock64();
+#endif
   unsigned tile_m, tile_n;
   tile_coords(p.tiles_m, p.tiles_n, BM >= 1024 ? 1u : 1024u / BM, tile_m, tile_n);
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
@@ -155,7 +179,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     if constexpr (BITS == 8) {
       // the re-quantizing epilogue wants consecutive n in one lane (4 bytes = one store), i.e. the
       // parameter as operand `a`; everything else wants consecutive n across lanes
-      acc[mt][nt][0] = EPI == kPRequant
+      acc[mt][nt][0] = (EPI == kPRequant || EPI == kPCoop)
                            ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[nt][0], F.a[mt][0], acc[mt][nt][0], 0, 0, 0)
                            : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][0], F.b[nt][0], acc[mt][nt][0], 0, 0, 0);
     } else {
@@ -243,43 +267,195 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     wait_vmcnt(0);     // dummy loads of the tail must not outlive the stages' reuse in the epilogue
   }
 
-  if constexpr (EPI == kPAmax || EPI == kPRequant) {
-    static_assert(BITS == 8 || (EPI != kPAmax && EPI != kPRequant), "fused epilogues are 8 bit");
+#ifdef MQ_TS
+#define MQ_STAMP(i) do { if (EPI == kPCoop && tid == 0) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define MQ_STAMP(i) do { } while (0)
+#endif
+  MQ_STAMP(1);
+  if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop) {
+    static_assert(BITS == 8, "fused epilogues are 8 bit");
     __shared__ float red[NW];
     const int lj = lane % 32, lh = lane / 32;
     const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
     const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
-    if constexpr (EPI == kPAmax) {
-      // y = relu?(fma(acc, u, bias)) as in the storing epilogue, reduced to this block's abs-max
+    // a tile with no row or column past the end needs no masking anywhere below
+    const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
+    constexpr bool SWAPPED = EPI != kPAmax;
+    // bias[n] without a branch (a branch per element makes every load wait for the one before): the
+    // index is clamped into the vector, and without a bias some readable address stands in
+    const bool has_bias = p.bias != nullptr;
+    auto bias_at = [&](unsigned n) -> float {
+      const float* src = has_bias ? p.bias + (n < p.N ? n : p.N - 1) : p.sA;
+      const float b = *src;
+      return has_bias ? b : 0.f;
+    };
+    // swapped layout: the 16 registers of a sub-tile are 16 columns n; their biases are fetched once
+    float biasv[SWAPPED ? TN : 1][16];
+    if constexpr (SWAPPED) {
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) biasv[nt][j] = bias_at(wn0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4);
+    }
+#ifdef MQ_TS
+    if (u == 12345.f) return;
+    MQ_STAMP(6);
+#endif
+
+    // ---- max|y| of this block, y = relu?(fma((float)acc, u, bias[n])) as in the storing epilogue.
+    // For one column n the value y is a monotonic function of the integer sum (both
+    // the conversion and the fused multiply-add round monotonically), so max|y| over the rows of a
+    // column is reached at the largest or the smallest sum (whatever the sign of u): the rows are reduced as integers and the
+    // float expression is evaluated once (with ReLU) or twice per column instead of once per element.
+    if constexpr (EPI == kPAmax || EPI == kPCoop) {
       float local = 0.f;
+      // with ReLU and u > 0 only the largest sum of a column matters
+      const bool max_only = p.relu != 0 && u > 0.0f;
+      auto column = [&](int imax, int imin, unsigned n, float bias) {
+        if (n < p.N && imax >= imin) {                       // imax < imin: no valid row in this lane
+          const float hi = fmaf((float)imax, u, bias), lo = fmaf((float)imin, u, bias);
+          if (p.relu) local = fmaxf(local, fmaxf(hi, lo));   // max(relu(y)) = max(0, y at an extreme sum)
+          else local = fmaxf(local, fmaxf(fabsf(hi), fabsf(lo)));
+        }
+      };
+      auto reduce_rows = [&](auto interior_tag, auto max_only_tag) {
+        constexpr bool INTERIOR = decltype(interior_tag)::value;
+        constexpr bool MAX_ONLY = decltype(max_only_tag)::value;
+        if constexpr (!SWAPPED) {
+          // register r of lane l is (m, n) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32): a lane holds one column
 #pragma unroll
-      for (int nt = 0; nt < TN; ++nt) {
-        const unsigned n = wn0 + nt * 32 + lj;
-        const bool n_ok = n < p.N;
-        const float bias = (p.bias != nullptr && n_ok) ? p.bias[n] : 0.f;
+          for (int nt = 0; nt < TN; ++nt) {
+            int imax = INT_MIN, imin = INT_MAX;
 #pragma unroll
-        for (int mt = 0; mt < TM; ++mt)
+            for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const unsigned m = wm0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
-            float y = fmaf((float)acc[mt][nt][0][r], u, bias);
-            if (p.relu) y = (y > 0.0f) ? y : 0.0f;
-            if (n_ok && m < p.M) local = fmaxf(local, fabsf(y));
+              for (int r = 0; r < 16; ++r) {
+                const unsigned m = wm0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4;
+                const int v = acc[mt][nt][0][r];
+                if (INTERIOR || m < p.M) {
+                  imax = max(imax, v);
+                  if (!MAX_ONLY) imin = min(imin, v);
+                }
+              }
+            if (MAX_ONLY && (INTERIOR || imax != INT_MIN)) imin = imax;
+            column(imax, imin, wn0 + nt * 32 + lj, bias_at(wn0 + nt * 32 + lj));
           }
-      }
+        } else {
+          // operands swapped: register j of lane l is (n, m) = (8 (j / 4) + 4 (l / 32) + j % 4, l % 32)
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) local = fmaxf(local, __shfl_xor(local, off, 64));
+          for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              int imax = INT_MIN, imin = INT_MAX;
+#pragma unroll
+              for (int mt = 0; mt < TM; ++mt) {
+                const unsigned m = wm0 + mt * 32 + lj;
+                const int v = acc[mt][nt][0][j];
+                if (INTERIOR || m < p.M) {
+                  imax = max(imax, v);
+                  if (!MAX_ONLY) imin = min(imin, v);
+                }
+              }
+              if (MAX_ONLY && (INTERIOR || imax != INT_MIN)) imin = imax;
+              column(imax, imin, wn0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4, biasv[nt][j]);
+            }
+        }
+      };
+      if (interior && max_only) reduce_rows(std::true_type{}, std::true_type{});
+      else if (interior) reduce_rows(std::true_type{}, std::false_type{});
+      else reduce_rows(std::false_type{}, std::false_type{});
+#ifdef MQ_TS
+      if (local == 12345.f) return;
+      MQ_STAMP(7);
+#endif
+      local = __uint_as_float(wave_max_u32(__float_as_uint(local)));   // local >= 0: bit patterns order like floats
       if (lane == 0) red[wave] = local;
       __syncthreads();
-      if (tid == 0) {
-        float m = red[0];
+      if constexpr (EPI == kPAmax) {
+        if (tid == 0) {
+          float m = red[0];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
-        p.partial[blockIdx.x] = m;
+          for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
+          p.partial[blockIdx.x] = m;
+        }
+      } else {
+        // ---- grid-wide agreement on max|y| (every workgroup of the launch is resident; the launcher
+        // checked, and the grid has at most kBarrierSlots workgroups).  Each workgroup stores the bit
+        // pattern of its maximum, plus one, in a slot of its own (zero before; patterns of non-negative
+        // floats order like unsigned integers) and then reads all slots until none is zero: the read
+        // that ends the wait also delivers every maximum.  No counter, no atomic read-modify-write on a
+        // shared address, and no cache write-back or invalidation: slots are written and read with
+        // device-scope accesses only.  The wait is bounded in wall-clock time.  A workgroup that gives
+        // up first raises the sticky word behind the slots, then reads once more; if slots are still
+        // missing it goes on with a meaningless multiplier.  Workgroup 0 looks at the sticky word after
+        // its last store, which is later than any complete read, and publishes NaN instead of the
+        // multiplier if it is raised, so that nothing computed from this launch can pass for a result.
+        // While the maxima travel, every wave turns its sums into y in place (the float's bits in the
+        // accumulator registers): that part of the epilogue does not need the multiplier.
+        auto sums_to_y = [&]() {
+#pragma unroll
+          for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+              for (int j = 0; j < 16; ++j) {
+                float y = fmaf((float)acc[mt][nt][0][j], u, biasv[SWAPPED ? nt : 0][j]);
+                if (p.relu) y = fmaxf(y, 0.0f);
+                acc[mt][nt][0][j] = __float_as_int(y);
+              }
+        };
+        if (tid == 0) {
+          float m = red[0];
+#pragma unroll
+          for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
+          MQ_STAMP(2);
+          __hip_atomic_store(p.barrier + blockIdx.x, __float_as_uint(m) + 1u, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
+        sums_to_y();
+        if (wave == 0) {
+          MQ_STAMP(3);
+          const unsigned total = gridDim.x;
+          const unsigned long long t0 = wall_clock64();       // 100 MHz, the same value in every lane
+          unsigned best;
+          bool gave_up = false;
+          for (;;) {
+            best = 1u;
+            bool all = true;
+#pragma unroll
+            for (unsigned k = 0; k < kBarrierSlots / 64; ++k) {
+              const unsigned i = lane + 64 * k;
+              const unsigned v = i < total ? __hip_atomic_load(p.barrier + i, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT) : 1u;
+              all = all && v != 0u;
+              best = max(best, v);
+            }
+            if (__all(all)) break;
+            if (gave_up) break;                                // that was the one read after giving up
+            if (wall_clock64() - t0 >= p.barrier_ticks) {
+              if (lane == 0) (void)atomicOr(p.barrier + kBarrierSlots, 1u);
+              // the value returned by the atomic is waited for before the next read is issued
+              gave_up = true;
+              __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+              continue;
+            }
+            __builtin_amdgcn_s_sleep(2);
+          }
+          best = wave_max_u32(best);
+          MQ_STAMP(4);
+          if (lane == 0) red[0] = __uint_as_float(best - 1u);
+        }
+        __syncthreads();
       }
-    } else {
+    }
+
+    if constexpr (EPI != kPAmax) {
       float s2;
-      if (p.partial != nullptr) {
+      if constexpr (EPI == kPCoop) {
+        const float amax = red[0];
+        s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
+      } else if (p.partial != nullptr) {
         // multiplier of the output from the partial maxima of the first pass (every block forms it)
         float amax = 0.f;
         for (unsigned i = tid; i < p.npartial; i += NW * 64) amax = fmaxf(amax, p.partial[i]);
@@ -302,39 +478,53 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       const PackedDims dO(8, p.M, p.N);
       __syncthreads();                             // every wave is done reading the last stage
       uint8_t* scratch = smem + wave * kFragBytes;
+      const bool relu = p.relu != 0;
+      auto store_tiles = [&](auto interior_tag) {
+        constexpr bool INTERIOR = decltype(interior_tag)::value;
 #pragma unroll
-      for (int nt = 0; nt < TN; ++nt) {
-        float bias[16];
+        for (int nt = 0; nt < TN; ++nt) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const unsigned n = wn0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4;
-          bias[j] = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
-        }
+          for (int mt = 0; mt < TM; ++mt) {
+            const unsigned m = wm0 + mt * 32 + lj;
 #pragma unroll
-        for (int mt = 0; mt < TM; ++mt) {
-          const unsigned m = wm0 + mt * 32 + lj;
+            for (int q = 0; q < 4; ++q) {
+              int qv[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            int qv[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
-              float y = fmaf((float)acc[mt][nt][0][4 * q + t], u, bias[4 * q + t]);
-              if (p.relu) y = (y > 0.0f) ? y : 0.0f;
-              qv[t] = (n < p.N && m < p.M) ? quant8(y, s2) : 0;     // padding stays zero
+              for (int t = 0; t < 4; ++t) {
+                const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
+                float y;
+                if constexpr (EPI == kPCoop) {
+                  y = __int_as_float(acc[mt][nt][0][4 * q + t]);    // converted while waiting for the maximum
+                } else {
+                  y = fmaf((float)acc[mt][nt][0][4 * q + t], u, biasv[SWAPPED ? nt : 0][4 * q + t]);
+                  if (relu) y = fmaxf(y, 0.0f);                     // NaN -> 0 like (y > 0) ? y : 0
+                }
+                const int v = quant8(y, s2);
+                qv[t] = (INTERIOR || (n < p.N && m < p.M)) ? v : 0;   // padding stays zero
+              }
+              const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
+                                    ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
+              // slot of row m in the fragment: lj + 32 (K half); the 4 bytes sit at 8 (q % 2) + 4 lh
+              *reinterpret_cast<uint32_t*>(scratch + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
             }
-            const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
-                                  ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
-            // slot of row m in the fragment: lj + 32 (K half); the 4 bytes sit at 8 (q % 2) + 4 lh
-            *reinterpret_cast<uint32_t*>(scratch + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
+            // the wave reads back what it wrote itself: only its own LDS operations need to be complete
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+            const u4 v = *reinterpret_cast<const u4*>(scratch + lane * 16);
+            const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
+            if (INTERIOR || (mrow < dO.Np && ncol < dO.Kp))
+              *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
           }
-          // the wave reads back what it wrote itself: only its own LDS operations need to be complete
-          __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
-          const u4 v = *reinterpret_cast<const u4*>(scratch + lane * 16);
-          const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
-          if (mrow < dO.Np && ncol < dO.Kp)
-            *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
-          __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
+        }
+      };
+      if (interior) store_tiles(std::true_type{});
+      else store_tiles(std::false_type{});
+      MQ_STAMP(5);
+      if constexpr (EPI == kPCoop) {
+        if (blockIdx.x == 0 && tid == 0) {
+          const unsigned sticky = __hip_atomic_load(p.barrier + kBarrierSlots, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+          *p.s_out = sticky != 0u ? __builtin_nanf("") : s2;
         }
       }
     }
@@ -439,6 +629,58 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
   b.s_out = s_out;
   b.packed_out = packed_out;
   return launch_pp_variant<8, kPRequant>(b, v, s);
+}
+
+static unsigned long long g_barrier_ticks = 50ull * 1000 * 1000;     // 0.5 s of the 100 MHz wall clock
+unsigned long long barrier_timeout_ticks() { return g_barrier_ticks; }
+void set_barrier_timeout_ticks(unsigned long long ticks) { g_barrier_ticks = ticks; }
+
+template <int BM, int BN, int WM, int WN, int S>
+int launch_coop(const GemmArgs& a, hipStream_t s) {
+  constexpr size_t smem = (size_t)S * ((BM / 32) + (BN / 32)) * 2 * kFragBytes;
+  Params p{};
+  p.qA = static_cast<const uint8_t*>(a.qA);
+  p.packedW = static_cast<const uint8_t*>(a.packedW);
+  p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
+  const size_t tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  p.tiles_m = (unsigned)tiles_m;
+  p.tiles_n = (unsigned)tiles_n;
+  p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu;
+  p.s_out = a.s_out;
+  p.packed_out = static_cast<uint8_t*>(a.packed_out);
+  p.barrier = a.barrier;
+  p.barrier_ticks = barrier_timeout_ticks();
+  if (a.barrier == nullptr) return MQ_ERR_NULL;
+  auto kern = k_gemm_pp<8, BM, BN, WM, WN, S, kPCoop>;
+  static int max_blocks = -1;       // workgroups the device can hold at once, asked once
+  if (max_blocks < 0) {
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    if (rc != MQ_OK) return rc;
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), WM * WN * 64, smem) != hipSuccess)
+      return MQ_ERR_HIP;
+    max_blocks = per_cu * cus;
+  }
+  // the grid-wide barrier needs every workgroup resident at the same time (and has a slot)
+  if (tiles_m * tiles_n > (size_t)max_blocks || tiles_m * tiles_n > kBarrierSlots) return MQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), smem, s, p);
+  return check_hip(hipGetLastError());
+}
+
+// Product + bias (+ReLU) -> max|y| -> quant_int(y) in ONE launch, for results of at most one tile per
+// resident workgroup.  MQ_ERR_UNSUPPORTED otherwise (the caller then runs the two-pass version).
+// The kBarrierWords words at barrier must be zero when the kernel starts (an earlier kernel on the stream
+// clears them); should the barrier ever time out, *s_out becomes NaN and so does everything computed from it.
+int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
+                             hipStream_t s) {
+  GemmArgs b = a;
+  b.barrier = barrier;
+  b.s_out = s_out;
+  b.packed_out = packed_out;
+  return launch_coop<256, 256, 2, 4, 4>(b, s);
 }
 
 // Single-pass re-quantizing product with a multiplier known in advance (fixed multipliers as in the

@@ -78,6 +78,7 @@ struct GemmArgs {
   unsigned npartial;
   float* s_out;
   void* packed_out;
+  unsigned* barrier;
 };
 int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
 void set_forced_variant(int v);
@@ -92,12 +93,20 @@ int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* 
 
 constexpr unsigned kAbsmaxPartials = 1024;   // floats of scratch launch_absmax_quantize_pack needs
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
-                                float* scale_out, void* packed, hipStream_t s);
+                                float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr);
 // Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same
 // product re-quantized with the multiplier formed from those partials, written as packed activations.
 size_t gemm_amax_partials(size_t M, size_t N);
 int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s);
 int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, void* packed_out, hipStream_t s);
+// Words of the grid-wide barrier of the single-pass re-quantizing product: one slot per workgroup
+// (at most 256) and a sticky failure word, rounded up.
+constexpr unsigned kBarrierWords = 320;
+unsigned long long barrier_timeout_ticks();
+void set_barrier_timeout_ticks(unsigned long long ticks);
+int launch_clear_words(unsigned* p, unsigned n, hipStream_t s);
+int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
+                             hipStream_t s);
 int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
 int tuned_variant(int bits, size_t M, size_t N, size_t K);

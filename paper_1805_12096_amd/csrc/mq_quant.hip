@@ -22,6 +22,9 @@ __device__ __forceinline__ int wave_sum(int v) {
 }
 
 __global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
+__global__ void k_clear_words(uint32_t* p, unsigned n) {
+  for (unsigned i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
 
 // |x| of a non-NaN float orders like its bit pattern, so the grid-wide maximum
 // is an integer atomicMax.  fmaxf drops NaN operands.
@@ -227,7 +230,9 @@ namespace {
 // Abs-max without atomics or initialisation: block b writes its maximum to partial[b];
 // the consumer reduces the few hundred values itself (block_max_of_partials).
 __global__ __launch_bounds__(kThreads) void k_absmax_partial(const float* __restrict__ x, size_t n,
-                                                             float* __restrict__ partial) {
+                                                             float* __restrict__ partial, unsigned* clear, unsigned nclear) {
+  if (clear != nullptr && blockIdx.x == 0)                 // a later kernel's counters
+    for (unsigned i = threadIdx.x; i < nclear; i += kThreads) clear[i] = 0u;
   const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
   const size_t nthreads = (size_t)gridDim.x * kThreads;
   const size_t nvec = n / 4;
@@ -372,14 +377,19 @@ int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, con
   return check_hip(hipGetLastError());
 }
 
+int launch_clear_words(unsigned* p, unsigned n, hipStream_t s) {
+  hipLaunchKernelGGL(k_clear_words, dim3(1), dim3(256), 0, s, reinterpret_cast<uint32_t*>(p), n);
+  return check_hip(hipGetLastError());
+}
+
 // abs-max + quant_int into the packed layout in two launches, no atomics, no fill:
 // partial maxima to `partials` (kAbsmaxPartials floats), then quantization with the multiplier
 // formed from them; scale_out[0] receives the multiplier.
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
-                                float* scale_out, void* packed, hipStream_t s) {
+                                float* scale_out, void* packed, hipStream_t s, unsigned* clear) {
   const size_t n = rows * cols;
   const unsigned g1 = grid_for(n, (size_t)kThreads * 8, kAbsmaxPartials);
-  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials);
+  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials, clear, kBarrierWords);
   const PackedDims d(bits, rows, cols);
   const size_t row_groups = d.Np / 8;
   unsigned ksplit = 1;

@@ -577,6 +577,23 @@ def test_ffn_fused_matches_oracle_chain(M, d, f):
             mq.mq_set_gemm_variant(0)
 
 
+@pytest.mark.parametrize("M,d,f", [(37, 64, 200), (700, 128, 600), (4352, 64, 4096)])
+def test_ffn_single_pass_and_two_pass_agree_with_oracle(M, d, f):
+    # The intermediate's multiplier needs max|H| over the whole tensor: one launch with a grid-wide
+    # barrier when every tile is resident at once, two passes otherwise (the last shape has 272
+    # tiles of 256 x 256, more than the chip holds).  Repeated calls reuse the workspace's counter.
+    c = workloads.ffn(2, M, d, f, 0.04, 8, seed_extra=M + 2 * d + f)
+    o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
+    try:
+        for single in (1, 0, 1, 1):
+            mq.mq_set_ffn_single_pass(single)
+            assert np.array_equal(gpu_ffn_fused(c), o2["Y"]), f"single_pass={single}"
+    finally:
+        mq.mq_set_ffn_single_pass(1)
+
+
 def test_ffn_fused_full_size_equals_unfused_and_sampled_oracle():
     c = workloads.config2()
     Yf = gpu_ffn_fused(c)
@@ -628,6 +645,57 @@ def test_two_pass_requantizing_product():
     # padding of the packed output is zero: a prepared copy of the same integers has identical bytes
     ref = mq.prepare_weight(dev(oq.astype(np.float32)), 8, scale=torch.ones(1, dtype=torch.float32, device=DEV))
     assert torch.equal(out, ref.packed)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (300, 520, 256), (1000, 1100, 128)])
+def test_single_pass_requantizing_product(shape):
+    # one pass over the operands, the sums waiting in registers while the grid agrees on max|y|;
+    # called twice on one workspace (it clears its two words itself)
+    M, N, K = shape
+    p = workloads.random_problem(405 + M, M, N, K)
+    o = oracle.linear(p["A"], p["Wt"], 8, p["bias"], True)
+    os2 = oracle.scale_from_amax(oracle.absmax(o["Y"]), 8)
+    oq = oracle.quant_int(o["Y"], 8, os2)
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    pa, s = gpu_quantize_pack(p["A"], 8)
+    nb = mq.mq_gemm_amax_ws_bytes(M, N)
+    ws = torch.full((nb,), 0xA5, dtype=torch.uint8, device=DEV)
+    bias = dev(p["bias"])
+    ref = mq.prepare_weight(dev(oq.astype(np.float32)), 8, scale=torch.ones(1, dtype=torch.float32, device=DEV))
+    for _ in range(2):
+        s2 = torch.empty(1, dtype=torch.float32, device=DEV)
+        out = torch.full((mq.mq_packed_bytes(8, M, N),), 0x22, dtype=torch.uint8, device=DEV)
+        mq.mq_gemm_requant_single_packed(pa, pw.packed, M, N, K, s, pw.scale, bias, True, ws, nb, s2, out)
+        assert host(s2)[0] == os2
+        assert torch.equal(out, ref.packed)
+
+
+def test_single_pass_barrier_timeout_is_loud_and_recoverable():
+    # With a zero time limit every workgroup that has to wait gives up at once: all kernels still end,
+    # the output's multiplier is NaN (and so is everything a caller computes from it), and the next
+    # call with the normal limit is correct again on the same workspace.
+    c = workloads.ffn(2, 1000, 128, 1100, 0.04, 8, seed_extra=77)
+    o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
+    try:
+        mq.mq_set_barrier_timeout_us(0)
+        assert np.all(np.isnan(gpu_ffn_fused(c)))
+    finally:
+        mq.mq_set_barrier_timeout_us(500000)
+    assert np.array_equal(gpu_ffn_fused(c), o2["Y"])
+
+
+def test_single_pass_requantizing_product_refuses_what_does_not_fit():
+    M, N, K = 4352, 4096, 64           # 272 tiles of 256 x 256
+    pa = torch.zeros(mq.mq_packed_bytes(8, M, K), dtype=torch.uint8, device=DEV)
+    pw = torch.zeros(mq.mq_packed_bytes(8, N, K), dtype=torch.uint8, device=DEV)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    nb = mq.mq_gemm_amax_ws_bytes(M, N)
+    ws = torch.zeros(nb, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(mq.mq_packed_bytes(8, M, N), dtype=torch.uint8, device=DEV)
+    with pytest.raises(mq.MqError):
+        mq.mq_gemm_requant_single_packed(pa, pw, M, N, K, one, one, None, False, ws, nb, one.clone(), out)
 
 
 # ------------------------------------------------ short-listed output layer
