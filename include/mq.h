@@ -322,6 +322,18 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
                   const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* The same block in 16 bit (Transformer-big style): quant_int(A), product +
+ * b1 + ReLU into a binary32 H kept in ws with max|H| as a by-product of the
+ * epilogue, quant_int(H) straight into the packed layout with the multiplier
+ * formed in that kernel, second product + b2.  Five launches, no host
+ * synchronisation; packedW1 / packedW2 from mq_prepare_weight(bits = 16).
+ * Results are identical to the call-by-call chain.  Arguments as
+ * mq_ffn_i8_f32; ws: mq_ffn_i16_ws_bytes(M, d, f) bytes (it holds H). */
+size_t mq_ffn_i16_ws_bytes(size_t M, size_t d, size_t f);
+int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                   const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                   void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

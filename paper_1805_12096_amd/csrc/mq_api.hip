@@ -491,7 +491,7 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   void* qH = base + L.off_qH;
   // a1 + a2: abs-max and quant_int of the input (two launches, no atomics)
   unsigned* barrier = reinterpret_cast<unsigned*>(base + L.off_bar);     // cleared by the first kernel below
-  int rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s, barrier);
+  int rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s, barrier, kBarrierWords);
   if (rc != MQ_OK) return rc;
   // a4 + a5, first pass: only the abs-max of relu(A W1 + b1) leaves the chip
   GemmArgs g1{};
@@ -510,6 +510,70 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   // second product with the float epilogue
   GemmArgs g2{};
   g2.qA = qH; g2.packedW = packedW2; g2.bits = 8; g2.M = M; g2.N = d; g2.K = f;
+  g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
+  return launch_gemm_packed(g2, kEpiDequant, s);
+}
+
+namespace mq {
+namespace {
+// Scratch layout of mq_ffn_i16_f32.
+struct Ffn16Ws {
+  size_t off_part, off_scal, off_qA, off_H, off_qH, total;
+  Ffn16Ws(size_t M, size_t d, size_t f) {
+    off_part = 0;
+    off_scal = round_up(kAbsmaxPartials * sizeof(float), 256);
+    off_qA = off_scal + 256;
+    off_H = round_up(off_qA + PackedDims(16, M, d).total_bytes(), 256);
+    off_qH = round_up(off_H + M * f * sizeof(float), 256);
+    total = round_up(off_qH + PackedDims(16, M, f).total_bytes(), 256);
+  }
+};
+}  // namespace
+}  // namespace mq
+
+size_t mq_ffn_i16_ws_bytes(size_t M, size_t d, size_t f) {
+  if (!dims_ok(M, f, d)) return 0;
+  return Ffn16Ws(M, d, f).total;
+}
+
+int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                   const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                   void* ws, size_t ws_bytes, void* stream) {
+  if (A == nullptr || packedW1 == nullptr || sW1 == nullptr || packedW2 == nullptr || sW2 == nullptr ||
+      Y == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, f, d)) return MQ_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(packedW1, 16) || !aligned(packedW2, 16) || !aligned(ws, 256) ||
+      !aligned(sW1, 4) || !aligned(sW2, 4) || !aligned(Y, 4))
+    return MQ_ERR_ALIGN;
+  if ((b1 != nullptr && !aligned(b1, 4)) || (b2 != nullptr && !aligned(b2, 4))) return MQ_ERR_ALIGN;
+  const Ffn16Ws L(M, d, f);
+  if (ws_bytes < L.total) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  float* part = reinterpret_cast<float*>(base + L.off_part);
+  float* sA = reinterpret_cast<float*>(base + L.off_scal);
+  float* sH = sA + 1;
+  float* hmax = sA + 2;                       // max|H|, raised by the first product's epilogue
+  uint8_t* qA = base + L.off_qA;
+  float* H = reinterpret_cast<float*>(base + L.off_H);
+  uint8_t* qH = base + L.off_qH;
+  // a1 + a2 on the input; the same first kernel zeroes max|H|
+  int rc = launch_absmax_quantize_pack(A, M, d, 16, part, sA, qA, s, reinterpret_cast<unsigned*>(hmax), 1);
+  if (rc != MQ_OK) return rc;
+  // a4 + a5: H = relu(A W1 + b1) in binary32, max|H| as a by-product of the epilogue
+  GemmArgs g1{};
+  g1.qA = qA;
+  g1.packedW = packedW1; g1.bits = 16; g1.M = M; g1.N = f; g1.K = d;
+  g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1; g1.Y = H; g1.out_amax = hmax;
+  rc = launch_gemm_packed(g1, kEpiDequant, s);
+  if (rc != MQ_OK) return rc;
+  // a1 + a2 on H: the multiplier comes from the one maximum already there
+  rc = launch_quantize_pack_partials(H, M, f, 16, hmax, 1, sH, qH, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs g2{};
+  g2.qA = qH;
+  g2.packedW = packedW2; g2.bits = 16; g2.M = M; g2.N = d; g2.K = f;
   g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
   return launch_gemm_packed(g2, kEpiDequant, s);
 }

@@ -93,7 +93,10 @@ int launch_argmax_finish(const unsigned long long* keys, size_t M, const float* 
 
 constexpr unsigned kAbsmaxPartials = 1024;   // floats of scratch launch_absmax_quantize_pack needs
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
-                                float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr);
+                                float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr,
+                                unsigned nclear = 0);
+int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,
+                                  unsigned npartials, float* scale_out, void* packed, hipStream_t s);
 // Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same
 // product re-quantized with the multiplier formed from those partials, written as packed activations.
 size_t gemm_amax_partials(size_t M, size_t N);

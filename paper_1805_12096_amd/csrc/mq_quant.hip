@@ -382,14 +382,11 @@ int launch_clear_words(unsigned* p, unsigned n, hipStream_t s) {
   return check_hip(hipGetLastError());
 }
 
-// abs-max + quant_int into the packed layout in two launches, no atomics, no fill:
-// partial maxima to `partials` (kAbsmaxPartials floats), then quantization with the multiplier
-// formed from them; scale_out[0] receives the multiplier.
-int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
-                                float* scale_out, void* packed, hipStream_t s, unsigned* clear) {
-  const size_t n = rows * cols;
-  const unsigned g1 = grid_for(n, (size_t)kThreads * 8, kAbsmaxPartials);
-  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials, clear, kBarrierWords);
+// quant_int into the packed layout with the multiplier formed in the kernel from `npartials` partial
+// maxima (one is enough: a single max|x| in device memory); scale_out[0] receives the multiplier.
+int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,
+                                  unsigned npartials, float* scale_out, void* packed, hipStream_t s) {
+  const unsigned g1 = npartials;
   const PackedDims d(bits, rows, cols);
   const size_t row_groups = d.Np / 8;
   unsigned ksplit = 1;
@@ -407,6 +404,17 @@ int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bi
     else hipLaunchKernelGGL((k_quantize_pack<16, false, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
   }
   return check_hip(hipGetLastError());
+}
+
+// abs-max + quant_int into the packed layout in two launches, no atomics, no fill:
+// partial maxima to `partials` (kAbsmaxPartials floats), then quantization with the multiplier
+// formed from them; scale_out[0] receives the multiplier.
+int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
+                                float* scale_out, void* packed, hipStream_t s, unsigned* clear, unsigned nclear) {
+  const size_t n = rows * cols;
+  const unsigned g1 = grid_for(n, (size_t)kThreads * 8, kAbsmaxPartials);
+  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials, clear, nclear);
+  return launch_quantize_pack_partials(x, rows, cols, bits, partials, g1, scale_out, packed, s);
 }
 
 }  // namespace mq

@@ -594,6 +594,24 @@ def test_ffn_single_pass_and_two_pass_agree_with_oracle(M, d, f):
         mq.mq_set_ffn_single_pass(1)
 
 
+@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (300, 256, 520)])
+def test_ffn_int16_one_call_matches_oracle_chain(M, d, f):
+    c = workloads.ffn(4, M, d, f, 0.03, 16, seed_extra=M + d + 3 * f)
+    o1 = oracle.linear(c["A"], c["W1t"], 16, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 16)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 16, c["b2"], False, sA=s2)
+    A = dev(c["A"])
+    p1 = mq.prepare_weight(dev(c["W1t"]), 16)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 16)
+    nbytes = mq.mq_ffn_i16_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device=DEV)     # contents must not matter
+    for _ in range(2):
+        Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+        mq.mq_ffn_i16_f32(A, M, d, f, p1.packed, p1.scale, dev(c["b1"]), p2.packed, p2.scale, dev(c["b2"]), Y, ws,
+                          nbytes)
+        assert np.array_equal(host(Y), o2["Y"])
+
+
 def test_ffn_fused_full_size_equals_unfused_and_sampled_oracle():
     c = workloads.config2()
     Yf = gpu_ffn_fused(c)
