@@ -108,11 +108,22 @@ int mq_quantize_f32(const float* x, size_t rows, size_t cols, int bits, const fl
 int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                          void* packed, void* stream);
 
-/* Abs-max and quant_int into the packed layout in two launches with no atomics
- * and no initialisation pass: per-block partial maxima go to ws, the quantizing
- * kernel forms Qmax / max from them (one correctly rounded division) and stores
- * it in scale_out[0].  Same results as mq_absmax_f32 + mq_scale_from_amax +
- * mq_quantize_pack_f32.  ws: device, 16-byte aligned, mq_quantize_absmax_ws_bytes(). */
+/* Abs-max and quant_int into the packed layout in two launches with no
+ * shared-address atomics.  Same results as mq_absmax_f32 + mq_scale_from_amax +
+ * mq_quantize_pack_f32; Qmax / max (one correctly rounded division) is stored in
+ * scale_out[0].  Tensors of at most 2048 groups of 8 rows x 1024 columns
+ * (16 bit: at most 16384 rows of at most 1024 columns) are read ONCE: after a
+ * tiny launch that clears a few words of ws, one kernel holds the whole tensor
+ * in registers while its workgroups agree on the maximum (bounded wait, NaN
+ * multiplier on failure, as described at mq_gemm_requant_single_packed).  Larger
+ * tensors take two passes: per-block partial maxima to ws, then the quantizing
+ * kernel; so do tensors below 2^20 elements, for which two tiny kernels are
+ * quicker than one with a grid-wide wait.  mq_set_quantize_single_pass(0) forces
+ * the two-pass form, (2) the single-pass form whenever the tensor fits, (1) is
+ * the default choice by size.
+ * ws: device, 16-byte aligned, mq_quantize_absmax_ws_bytes(), contents
+ * irrelevant on entry. */
+int mq_set_quantize_single_pass(int enable);
 size_t mq_quantize_absmax_ws_bytes(void);
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
                                 float* scale_out, void* ws, size_t ws_bytes, void* stream);

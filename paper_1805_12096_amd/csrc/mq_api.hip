@@ -137,7 +137,17 @@ int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, con
   return launch_quantize_pack(x, rows, cols, bits, scale, packed, as_stream(stream));
 }
 
-size_t mq_quantize_absmax_ws_bytes(void) { return kAbsmaxPartials * sizeof(float); }
+static int g_quantize_single_pass = 1;
+
+int mq_set_quantize_single_pass(int enable) {
+  g_quantize_single_pass = enable < 0 ? 0 : (enable > 2 ? 2 : enable);
+  return MQ_OK;
+}
+
+size_t mq_quantize_absmax_ws_bytes(void) {
+  static_assert(kAbsmaxPartials * sizeof(float) >= kBarrierWords * sizeof(unsigned), "one workspace serves both forms");
+  return kAbsmaxPartials * sizeof(float);
+}
 
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
                                 float* scale_out, void* ws, size_t ws_bytes, void* stream) {
@@ -146,8 +156,17 @@ int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bi
   if (!dims_ok(1, rows, cols)) return MQ_ERR_SHAPE;
   if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(scale_out, 4) || !aligned(ws, 16)) return MQ_ERR_ALIGN;
   if (ws_bytes < mq_quantize_absmax_ws_bytes()) return MQ_ERR_WORKSPACE;
-  return launch_absmax_quantize_pack(x, rows, cols, bits, static_cast<float*>(ws), scale_out, packed,
-                                     as_stream(stream));
+  hipStream_t s = as_stream(stream);
+  // (below a million elements two tiny kernels are quicker than one with a grid-wide wait)
+  if (g_quantize_single_pass != 0 && (g_quantize_single_pass > 1 || rows * cols >= ((size_t)1 << 20))) {
+    // small enough for the registers of one resident grid: clear the agreement words, then one kernel
+    // that reads x once; larger tensors take the two-pass form below
+    int rc = launch_clear_words(static_cast<unsigned*>(ws), kBarrierWords, s);
+    if (rc != MQ_OK) return rc;
+    rc = launch_absmax_quantize_pack_fused(x, rows, cols, bits, static_cast<unsigned*>(ws), scale_out, packed, s);
+    if (rc != MQ_ERR_UNSUPPORTED) return rc;
+  }
+  return launch_absmax_quantize_pack(x, rows, cols, bits, static_cast<float*>(ws), scale_out, packed, s);
 }
 
 size_t mq_packed_bytes(int bits, size_t N, size_t K) {

@@ -26,6 +26,8 @@
 //     small kernel reduces them and decodes.  No atomics, no initialisation.
 // 64-bit keys order by sum first and by smaller index second:
 //   key = (sum ^ 0x80000000) << 32 | (0xFFFFFFFF - n);  0 means "no candidate".
+#include <type_traits>
+
 #include "mq_gemm_common.h"
 
 namespace mq {
@@ -41,7 +43,7 @@ __device__ __forceinline__ void wait_vmcnt_n(int n) {
   switch (n) {
 #define MQ_CASE(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | 0x0F70); break;
     MQ_CASE(0) MQ_CASE(1) MQ_CASE(2) MQ_CASE(3) MQ_CASE(4) MQ_CASE(5) MQ_CASE(6) MQ_CASE(7) MQ_CASE(8) MQ_CASE(9)
-    MQ_CASE(10) MQ_CASE(12) MQ_CASE(13) MQ_CASE(14) MQ_CASE(15) MQ_CASE(16)
+    MQ_CASE(10) MQ_CASE(11) MQ_CASE(12) MQ_CASE(13) MQ_CASE(14) MQ_CASE(15) MQ_CASE(16)
 #undef MQ_CASE
     default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
   }
@@ -72,6 +74,15 @@ __device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, 
 // output product restricted to a subset of the vocabulary).  A unit is then 16 consecutive shortlist
 // positions; since every lane of a direct-to-LDS load supplies its own address, gathering the 16
 // rows costs nothing extra.  Indices are candidate positions; the reduce kernel maps them back.
+#ifdef MQ_TS
+#ifndef MQ_TS_TID
+#define MQ_TS_TID 0
+#endif
+#define MQ_ASTAMP(i) do { if (threadIdx.x == MQ_TS_TID) (p.partial + (1u << 20) / 8 * 2)[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define MQ_ASTAMP(i) do { } while (0)
+#endif
+
 template <int TPW, bool GATHER>
 __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p) {
   constexpr int KG = kKG, S = kStages;
@@ -81,6 +92,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 
   const int lane = threadIdx.x % 64;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  MQ_ASTAMP(0);
   const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
   const unsigned kgroups = (unsigned)(dW.kfrags / 2);          // real K groups (<= KG)
   const unsigned nunits = GATHER ? (p.L + 15) / 16 : (unsigned)(dW.nblocks * 2);   // 16-candidate units
@@ -115,26 +127,34 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
         (const __attribute__((address_space(1))) void*)src,
         (__attribute__((address_space(3))) void*)(smem + (s % S) * STAGE + wave * kFragBytes), 16, 0, 0);
   };
+  // The first two stages go out first (their memory latency is the longest wait of the kernel), then the
+  // hidden-state operands of this wave's sentence tiles (tile t = wave + 8 i covers sentences 16 t ..
+  // 16 t + 15; they come from L2, every workgroup reads the same ones), then the remaining stages.  The
+  // memory counter retires loads in order, so waiting for "all but the newest n" later covers stages 0
+  // and 1 and the operands while the newer stages are still on their way.  The operand loads are written
+  // as instructions so that the waiting is ours: the compiler would wait for ALL outstanding loads, the
+  // whole pipeline included, at the first use.
+  constexpr int kEarly = 2;
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s)
+  for (int s = 0; s < kEarly; ++s)
     if ((unsigned)s < nlocal) issue(s);
-
-  // hidden-state operands of this wave's sentence tiles: tile t = wave + 8 i covers sentences 16 t .. 16 t + 15
   v4i hid[TPW][KG];
   const size_t tiles_avail = dA.nblocks * 2;
+  // 16-sentence tiles this wave really owns (a slot beyond them would only repeat a tile): TPW or TPW - 1
+  const int ntl = (size_t)wave < tiles_avail ? (int)((tiles_avail - 1 - wave) / kWaves) + 1 : 0;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
     size_t t = (size_t)wave + kWaves * i;
-    if (t >= tiles_avail) t = tiles_avail - 1;   // tile past the end: computed on a copy, never written out
+    if (t >= tiles_avail) t = tiles_avail - 1;   // slot past the end: a copy, never multiplied, never written out
 #pragma unroll
     for (int g = 0; g < KG; ++g) {
-      const bool real = (unsigned)g < kgroups;
-      const u4 v = *reinterpret_cast<const u4*>(p.packedA + lane_off + operand16_uniform_offset(dA, t, real ? g : 0));
-      hid[i][g] = real ? as_v4i(v) : v4i{0, 0, 0, 0};
+      const uint8_t* src = p.packedA + lane_off + operand16_uniform_offset(dA, t, (unsigned)g < kgroups ? g : 0);
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(hid[i][g]) : "v"(src) : "memory");
     }
   }
-  // vmcnt counts ordinary and direct-to-LDS loads alike: drain everything once (stages 0 .. S-2 included)
-  __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+  for (int s = kEarly; s < S - 1; ++s)
+    if ((unsigned)s < nlocal) issue(s);
 
   // running maxima, one per accumulator register: (sum << 8) | (255 - stage).  Real sums exceed
   // -2^23, so a key whose sum field is -2^23 means "no candidate yet".
@@ -145,35 +165,51 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 #pragma unroll
     for (int r = 0; r < 4; ++r) best[i][r] = kNone;
 
-  // One stage: the unit's K groups against this wave's sentence tiles into `cur`, while the
-  // maxima are updated from `prev` (the sums of the stage before).  The update's VALU work is
-  // cut into slices that sit between the MFMA groups, so it runs while the matrix pipeline is
-  // busy instead of after it; the scheduling fences keep that order.
-  auto stage = [&](unsigned s, v4i (&cur)[TPW], const v4i (&prev)[TPW]) {
-    if (s == 0) {
-      // drained above
-    } else if (s + S - 2 < nlocal) {
-      wait_vmcnt_n(S - 2);                      // stages s+1 .. s+S-2 may stay in flight (one load each)
-    } else {
-      wait_vmcnt_n(0);
-    }
+  // Before stage s is multiplied, stages s and s + 1 must have landed (s + 1 is read from LDS into
+  // registers while s is multiplied).  Loads issued so far: stages 0 .. min(nlocal, s + S - 1) - 1.
+  auto land = [&](unsigned s) {
+    const unsigned issued = nlocal < s + S - 1 ? nlocal : s + S - 1;
+    const unsigned need = s + 2 < nlocal ? s + 2 : nlocal;
+    wait_vmcnt_n((int)(issued - need));
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // everybody is past stage s - 1, so its slot can be refilled
-    if (s + S - 1 < nlocal) issue(s + S - 1);
-
+  };
+  auto read_stage = [&](unsigned s, v4i (&e)[KG]) {
     const uint8_t* st = smem + (s % S) * STAGE + lane * 16;
-    v4i e[KG];
 #pragma unroll
     for (int g = 0; g < KG; ++g) e[g] = as_v4i(*reinterpret_cast<const u4*>(st + g * kFragBytes));
+  };
+
+  // One stage: the unit's K groups (in `e`) against this wave's NT sentence tiles into `cur`, while the
+  // maxima are updated from `prev` (the sums of the stage before) and the next unit is read from LDS
+  // into `enext`.  The update's VALU work is cut into slices that sit between the MFMA groups, so it
+  // runs while the matrix pipeline is busy instead of after it; the scheduling fences keep that order.
+  auto stage = [&](auto nt_tag, unsigned s, v4i (&cur)[TPW], const v4i (&prev)[TPW], const v4i (&e)[KG],
+                   v4i (&enext)[KG]) {
+    constexpr int NT = decltype(nt_tag)::value;
+    land(s);
+#ifdef MQ_TS
+    if (threadIdx.x == MQ_TS_TID && s < 12)
+      reinterpret_cast<unsigned long long*>(smem + S * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s] = wall_clock64();
+#endif
+    // everybody is past stage s - 1 (and has its copy of stage s in registers), so slot s - 1 can be refilled
+    if (s + S - 1 < nlocal) issue(s + S - 1);
+#ifdef MQ_DBG_NOCOMPUTE
+    return;
+#endif
+    // the next unit's LDS reads are spread between the MFMA groups: eight reads in a row would fill the
+    // LDS queue (all eight waves read at the same time) and hold this wave's MFMAs back behind them
+    const bool more = s + 1 < nlocal;
+    const uint8_t* nx = smem + ((s + 1) % S) * STAGE + lane * 16;
     const int prev_tag = 256 - (int)s;          // 255 - (s - 1); unused garbage for s == 0 (prev holds "none")
-    constexpr int ITEMS = TPW * 4, PER = (ITEMS + KG - 1) / KG;
+    constexpr int ITEMS = NT * 4, PER = (ITEMS + KG - 1) / KG;
     const v4i zero = {0, 0, 0, 0};
 #pragma unroll
     for (int g = 0; g < KG; ++g) {
+      if (more) enext[g] = as_v4i(*reinterpret_cast<const u4*>(nx + g * kFragBytes));
 #pragma unroll
-      for (int i = 0; i < TPW; ++i)
+      for (int i = 0; i < NT; ++i)
         cur[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(e[g], hid[i][g], g == 0 ? zero : cur[i], 0, 0, 0);
 #pragma unroll
       for (int j = g * PER; j < (g + 1) * PER && j < ITEMS; ++j)
@@ -182,14 +218,45 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     }
   };
 
-  // two stages per trip so the two accumulator sets swap roles without copies
-  v4i acc0[TPW], acc1[TPW];
+  // two stages per trip so the two accumulator sets and the two unit buffers swap roles without copies
+  v4i acc0[TPW], acc1[TPW], e0[KG], e1[KG];
 #pragma unroll
-  for (int i = 0; i < TPW; ++i) acc1[i] = v4i{-8388608, -8388608, -8388608, -8388608};   // "none" for stage 0's update
-  for (unsigned s = 0; s < nlocal; s += 2) {
-    stage(s, acc0, acc1);
-    if (s + 1 < nlocal) stage(s + 1, acc1, acc0);
+  for (int i = 0; i < TPW; ++i) {
+    acc0[i] = v4i{-8388608, -8388608, -8388608, -8388608};
+    acc1[i] = v4i{-8388608, -8388608, -8388608, -8388608};   // "none" for stage 0's update
   }
+  if (nlocal > 0) {
+    // stage 0 has to be in registers before the loop, and so have the operands: everything but the
+    // stages issued after the operands may still be outstanding
+    const unsigned issued = nlocal < (unsigned)(S - 1) ? nlocal : (unsigned)(S - 1);
+    wait_vmcnt_n(issued > (unsigned)kEarly ? (int)(issued - kEarly) : 0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    read_stage(0, e0);
+  } else {
+    wait_vmcnt_n(0);
+  }
+  // the operands are older than every stage, so they are there now; K groups past the end of K are zeroed
+#pragma unroll
+  for (int i = 0; i < TPW; ++i)
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+      asm volatile("" : "+v"(hid[i][g]));
+      if ((unsigned)g >= kgroups) hid[i][g] = v4i{0, 0, 0, 0};
+    }
+  if (ntl == TPW) {
+    for (unsigned s = 0; s < nlocal; s += 2) {
+      stage(std::integral_constant<int, TPW>{}, s, acc0, acc1, e0, e1);
+      if (s + 1 < nlocal) stage(std::integral_constant<int, TPW>{}, s + 1, acc1, acc0, e1, e0);
+    }
+  } else {
+    for (unsigned s = 0; s < nlocal; s += 2) {
+      stage(std::integral_constant<int, TPW - 1>{}, s, acc0, acc1, e0, e1);
+      if (s + 1 < nlocal) stage(std::integral_constant<int, TPW - 1>{}, s + 1, acc1, acc0, e1, e0);
+    }
+  }
+  MQ_ASTAMP(14);
   // the last stage's sums are still pending; only a workgroup's last unit can reach past N, where
   // the rows are padding and must not compete (needs at least two workgroups, which the launcher
   // guarantees whenever there is more than one unit)
@@ -229,6 +296,13 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     const unsigned m = (wave + kWaves * i) * 16 + lane % 16;
     if (lane < 16 && m < p.M) p.partial[(size_t)m * gridDim.x + blockIdx.x] = key;
   }
+#ifdef MQ_TS
+  if (threadIdx.x == MQ_TS_TID)
+    for (unsigned s = 0; s < nlocal && s < 12; ++s)
+      (p.partial + (1u << 20) / 8 * 2)[blockIdx.x * 16 + 2 + s] =
+          reinterpret_cast<unsigned long long*>(smem + S * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s];
+#endif
+  MQ_ASTAMP(15);
 }
 
 // One wave per sentence: maximum over the per-workgroup keys, then decode.
@@ -262,7 +336,11 @@ __global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long*
 
 template <int TPW, bool GATHER>
 int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
-  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0);
+  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0)
+#ifdef MQ_TS
+                          + 256
+#endif
+      ;
   auto kern = k_argmax_stream<TPW, GATHER>;
   static bool attr_done = false;
   if (!attr_done) {

@@ -17,14 +17,11 @@
 #include <type_traits>
 
 #include "mq_gemm_common.h"
+#include "mq_grid_max.h"
 
 namespace mq {
 
 namespace {
-
-// Slots of the grid-wide barrier of the single-pass epilogue: one per workgroup, read 64 at a time.
-constexpr unsigned kBarrierSlots = 256;
-static_assert(kBarrierSlots % 64 == 0 && kBarrierSlots + 1 <= kBarrierWords, "barrier layout");
 
 enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3, kPCoop = 4 };
 
@@ -35,19 +32,6 @@ __device__ __forceinline__ int quant8(float x, float s) {
   int i;
   asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(r));
   return min(max(i, -127), 127);
-}
-
-// Maximum of an unsigned value over the 64 lanes, the same in every lane: inside rows of 16 lanes by
-// data-parallel-primitive moves (swap neighbours, swap pairs, mirror the half rows, mirror the rows),
-// across the four rows through scalar registers.
-__device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
-  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
-  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
-  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true));   // row_half_mirror
-  x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, true));   // row_mirror
-  const unsigned a = __builtin_amdgcn_readlane((int)x, 0), b = __builtin_amdgcn_readlane((int)x, 16);
-  const unsigned c = __builtin_amdgcn_readlane((int)x, 32), d = __builtin_amdgcn_readlane((int)x, 48);
-  return max(max(a, b), max(c, d));
 }
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -380,17 +364,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
           p.partial[blockIdx.x] = m;
         }
       } else {
-        // ---- grid-wide agreement on max|y| (every workgroup of the launch is resident; the launcher
-        // checked, and the grid has at most kBarrierSlots workgroups).  Each workgroup stores the bit
-        // pattern of its maximum, plus one, in a slot of its own (zero before; patterns of non-negative
-        // floats order like unsigned integers) and then reads all slots until none is zero: the read
-        // that ends the wait also delivers every maximum.  No counter, no atomic read-modify-write on a
-        // shared address, and no cache write-back or invalidation: slots are written and read with
-        // device-scope accesses only.  The wait is bounded in wall-clock time.  A workgroup that gives
-        // up first raises the sticky word behind the slots, then reads once more; if slots are still
-        // missing it goes on with a meaningless multiplier.  Workgroup 0 looks at the sticky word after
-        // its last store, which is later than any complete read, and publishes NaN instead of the
-        // multiplier if it is raised, so that nothing computed from this launch can pass for a result.
+        // ---- grid-wide agreement on max|y|: every workgroup of the launch is resident (the launcher
+        // checked), each publishes its maximum and collects everybody's.
         // While the maxima travel, every wave turns its sums into y in place (the float's bits in the
         // accumulator registers): that part of the epilogue does not need the multiplier.
         auto sums_to_y = [&]() {
@@ -410,41 +385,14 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 #pragma unroll
           for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
           MQ_STAMP(2);
-          __hip_atomic_store(p.barrier + blockIdx.x, __float_as_uint(m) + 1u, __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
+          grid_max_publish(p.barrier, m);
         }
         sums_to_y();
         if (wave == 0) {
           MQ_STAMP(3);
-          const unsigned total = gridDim.x;
-          const unsigned long long t0 = wall_clock64();       // 100 MHz, the same value in every lane
-          unsigned best;
-          bool gave_up = false;
-          for (;;) {
-            best = 1u;
-            bool all = true;
-#pragma unroll
-            for (unsigned k = 0; k < kBarrierSlots / 64; ++k) {
-              const unsigned i = lane + 64 * k;
-              const unsigned v = i < total ? __hip_atomic_load(p.barrier + i, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT) : 1u;
-              all = all && v != 0u;
-              best = max(best, v);
-            }
-            if (__all(all)) break;
-            if (gave_up) break;                                // that was the one read after giving up
-            if (wall_clock64() - t0 >= p.barrier_ticks) {
-              if (lane == 0) (void)atomicOr(p.barrier + kBarrierSlots, 1u);
-              // the value returned by the atomic is waited for before the next read is issued
-              gave_up = true;
-              __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
-              continue;
-            }
-            __builtin_amdgcn_s_sleep(2);
-          }
-          best = wave_max_u32(best);
+          const float amax = grid_max_collect(p.barrier, p.barrier_ticks);
           MQ_STAMP(4);
-          if (lane == 0) red[0] = __uint_as_float(best - 1u);
+          if (lane == 0) red[0] = amax;
         }
         __syncthreads();
       }
@@ -522,9 +470,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       MQ_STAMP(5);
       if constexpr (EPI == kPCoop) {
         if (blockIdx.x == 0 && tid == 0) {
-          const unsigned sticky = __hip_atomic_load(p.barrier + kBarrierSlots, __ATOMIC_RELAXED,
-                                                    __HIP_MEMORY_SCOPE_AGENT);
-          *p.s_out = sticky != 0u ? __builtin_nanf("") : s2;
+          *p.s_out = grid_max_failed(p.barrier) ? __builtin_nanf("") : s2;
         }
       }
     }
@@ -704,8 +650,11 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
       const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
       v = t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3);
     } else {
+      // small problems (a decode step's 300 sentences) are latency bound: the 128 x 64 tile with its deep
+      // pipeline gives more workgroups and the shortest prologue
       const size_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-      v = t256 >= 200 ? 1 : 3;
+      const size_t t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+      v = t256 >= 200 ? 1 : (t128 >= 128 ? 3 : 7);
     }
   }
   if (a.bits == 8)

@@ -95,6 +95,8 @@ constexpr unsigned kAbsmaxPartials = 1024;   // floats of scratch launch_absmax_
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
                                 float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr,
                                 unsigned nclear = 0);
+int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
+                                      float* scale_out, void* packed, hipStream_t s);
 int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,
                                   unsigned npartials, float* scale_out, void* packed, hipStream_t s);
 // Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same

@@ -1,6 +1,7 @@
 // quant_int on gfx950: per-tensor abs-max, multiplier, and the float -> int8 /
 // int16 conversion (arxiv 1805.12096, Section 4.2).  All three are bound by HBM
 // traffic: wide coalesced loads, one pass each.
+#include "mq_grid_max.h"
 #include "mq_internal.h"
 
 namespace mq {
@@ -352,6 +353,103 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restr
   }
 }
 
+
+// abs-max + quant_int in ONE launch for tensors whose elements all fit the registers of one resident
+// grid: every wave loads its share (8 rows x 4 NI fragments), the workgroups agree on max|x| (see
+// mq_grid_max.h), and the share is converted from registers.  Same work split, rounding and layout as
+// k_quantize_pack; x is read once instead of twice and one kernel boundary disappears.
+template <int BITS, bool VEC, int NI>
+__global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __restrict__ x, size_t rows, size_t cols,
+                                                              uint8_t* __restrict__ packed, unsigned ksplit,
+                                                              unsigned* barrier, unsigned long long ticks,
+                                                              float* __restrict__ scale_out) {
+  constexpr int kW = 512 / kWave;
+  const PackedDims d(BITS, rows, cols);
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int sub = lane % 8;                       // which 4 floats of a 32-element fragment row
+  const size_t row_groups = d.Np / 8;
+  const size_t per = (d.kfrags + ksplit - 1) / ksplit;   // fragments along K per wave, at most 4 NI
+  const size_t item = (size_t)blockIdx.x * kW + wave;
+  const bool active = item < row_groups * ksplit;
+  const size_t rg = item / ksplit, part = item % ksplit;
+  const size_t row = rg * 8 + lane / 8;
+  const size_t kb_begin = part * per;
+  const size_t kb_end = (part + 1) * per < d.kfrags ? (part + 1) * per : d.kfrags;
+  float4 v[NI][4];
+  float m = 0.f;
+#pragma unroll
+  for (int t = 0; t < NI; ++t)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const size_t kb = kb_begin + 4 * t + j;
+      const size_t k = kb * kFragK + 4 * sub;
+      v[t][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (active && kb < kb_end && row < rows) {
+        if (VEC) {
+          if (k < cols) v[t][j] = *reinterpret_cast<const float4*>(x + row * cols + k);
+        } else {
+          const float* xr = x + row * cols;
+          if (k + 0 < cols) v[t][j].x = xr[k + 0];
+          if (k + 1 < cols) v[t][j].y = xr[k + 1];
+          if (k + 2 < cols) v[t][j].z = xr[k + 2];
+          if (k + 3 < cols) v[t][j].w = xr[k + 3];
+        }
+      }
+    }
+#pragma unroll
+  for (int t = 0; t < NI; ++t)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      m = fmaxf(m, fmaxf(fmaxf(fabsf(v[t][j].x), fabsf(v[t][j].y)), fmaxf(fabsf(v[t][j].z), fabsf(v[t][j].w))));
+  m = __uint_as_float(wave_max_u32(__float_as_uint(m)));      // m >= 0 and never NaN (fmaxf drops NaN operands)
+  __shared__ float red[kW];
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  if (wave == 0) {
+    float b = red[0];
+#pragma unroll
+    for (int w = 1; w < kW; ++w) b = fmaxf(b, red[w]);
+    if (lane == 0) grid_max_publish(barrier, b);
+    const float amax = grid_max_collect(barrier, ticks);
+    if (lane == 0) red[0] = amax;
+  }
+  __syncthreads();
+  const float amax = red[0];
+  const float lim = BITS == 8 ? 127.0f : 32767.0f;
+  const float s = (amax > 0.0f) ? __fdiv_rn(lim, amax) : 1.0f;
+  if (active) {
+    const size_t nb = row / kFragRows;
+    const int slot = (int)(row % kFragRows) + 32 * (sub / 4);
+    int sum = 0;
+#pragma unroll
+    for (int t = 0; t < NI; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t kb = kb_begin + 4 * t + j;
+        if (kb < kb_end) {
+          const int q0 = quant1(v[t][j].x, s, lim), q1 = quant1(v[t][j].y, s, lim), q2 = quant1(v[t][j].z, s, lim),
+                    q3 = quant1(v[t][j].w, s, lim);
+          uint8_t* dst = packed + d.frag_offset(nb, kb) + (size_t)slot * 16 + 4 * (sub % 4);
+          if (BITS == 8) {
+            *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0, q1, q2, q3);
+          } else {
+            sum += q0 + q1 + q2 + q3;
+            // q = 256 h + l + 128: high bytes, and low bytes with the top bit flipped
+            *reinterpret_cast<uint32_t*>(dst) = pack4_i8(q0 >> 8, q1 >> 8, q2 >> 8, q3 >> 8);
+            *reinterpret_cast<uint32_t*>(dst + kFragBytes) = pack4_i8(q0, q1, q2, q3) ^ 0x80808080u;
+          }
+        }
+      }
+    if (BITS == 16) {  // ksplit is 1 for 16 bit: one wave owns whole rows
+      sum += __shfl_xor(sum, 1, kWave);
+      sum += __shfl_xor(sum, 2, kWave);
+      sum += __shfl_xor(sum, 4, kWave);
+      if (sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = grid_max_failed(barrier) ? __builtin_nanf("") : s;
+}
+
 }  // namespace
 
 int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
@@ -404,6 +502,68 @@ int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int 
     else hipLaunchKernelGGL((k_quantize_pack<16, false, true>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, partials, p, ksplit, g1, scale_out);
   }
   return check_hip(hipGetLastError());
+}
+
+namespace {
+template <int BITS, bool VEC, int NI>
+int launch_fused_one(const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
+                     unsigned* barrier, float* scale_out, hipStream_t s) {
+  auto kern = k_absmax_quantize_pack<BITS, VEC, NI>;
+  static int max_blocks = -1;       // workgroups the device can hold at once, asked once
+  if (max_blocks < 0) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), 512, 0) != hipSuccess)
+      return MQ_ERR_HIP;
+    max_blocks = per_cu * cus;
+  }
+  if (grid > (unsigned)max_blocks) return MQ_ERR_UNSUPPORTED;     // the grid-wide wait needs every workgroup resident
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, s, x, rows, cols, packed, ksplit, barrier, barrier_timeout_ticks(),
+                     scale_out);
+  return check_hip(hipGetLastError());
+}
+
+template <int BITS, bool VEC>
+int launch_fused_ni(int ni, const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
+                    unsigned* barrier, float* scale_out, hipStream_t s) {
+  switch (ni) {
+    case 1: return launch_fused_one<BITS, VEC, 1>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
+    case 2: return launch_fused_one<BITS, VEC, 2>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
+    case 4: return launch_fused_one<BITS, VEC, 4>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
+    default: return launch_fused_one<BITS, VEC, 8>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
+  }
+}
+}  // namespace
+
+// abs-max + quant_int into the packed layout in ONE launch, for tensors small enough to sit in the
+// registers of one resident grid (at most 256 workgroups of 8 waves, at most 32 fragments along K per
+// wave): MQ_ERR_UNSUPPORTED otherwise, nothing launched.  The kBarrierWords words at `barrier` must be
+// zero when the kernel starts.  scale_out[0] receives the multiplier (NaN if the grid-wide wait failed).
+int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
+                                      float* scale_out, void* packed, hipStream_t s) {
+  const PackedDims d(bits, rows, cols);
+  const size_t row_groups = d.Np / 8;
+  const size_t max_waves = (size_t)kBarrierSlots * (512 / kWave);
+  if (row_groups > max_waves) return MQ_ERR_UNSUPPORTED;
+  // split K as far as one trip of four fragments per wave allows while the waves still fit (8 bit; 16 bit
+  // keeps rows whole for the row sums)
+  unsigned ksplit = 1;
+  if (bits == 8) {
+    while (row_groups * ksplit * 2 <= max_waves && (d.kfrags + 2 * ksplit - 1) / (2 * ksplit) >= 4) ksplit *= 2;
+  }
+  const size_t per = (d.kfrags + ksplit - 1) / ksplit;
+  if (per > 32) return MQ_ERR_UNSUPPORTED;
+  const int ni = per <= 4 ? 1 : per <= 8 ? 2 : per <= 16 ? 4 : 8;
+  const unsigned grid = (unsigned)((row_groups * ksplit + 512 / kWave - 1) / (512 / kWave));
+  uint8_t* p = static_cast<uint8_t*>(packed);
+  const bool vec = cols % 4 == 0;
+  if (bits == 8) {
+    return vec ? launch_fused_ni<8, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s)
+               : launch_fused_ni<8, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s);
+  }
+  return vec ? launch_fused_ni<16, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s)
+             : launch_fused_ni<16, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s);
 }
 
 // abs-max + quant_int into the packed layout in two launches, no atomics, no fill:

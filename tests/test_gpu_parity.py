@@ -625,18 +625,49 @@ def test_ffn_fused_full_size_equals_unfused_and_sampled_oracle():
 
 
 @pytest.mark.parametrize("bits", [8, 16])
-@pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (2000, 1024)])
-def test_quantize_absmax_pack_two_launch(bits, shape):
+@pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (300, 2048), (2000, 1024), (8192, 512), (70, 1030),
+                                   (17000, 96)])
+def test_quantize_absmax_pack(bits, shape):
+    # Tensors that fit the registers of one resident grid are read once (the last shapes do not fit and take
+    # the two-pass form anyway); with the switch off it is always two passes.  Both forms must give the
+    # oracle's integers and multiplier and the same bytes, padding and appended row sums included.  Each
+    # form is called twice on one workspace whose contents do not matter.
     rng = np.random.default_rng(shape[0] + shape[1] * 3 + bits)
     x = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.3)
     oq, os_ = oracle.quant_int_absmax(x, bits)
     nb = mq.mq_quantize_absmax_ws_bytes()
     ws = torch.full((nb,), 0x7F, dtype=torch.uint8, device=DEV)
+    outs = []
+    try:
+        for single in (2, 0, 2, 1):
+            mq.mq_set_quantize_single_pass(single)
+            s = torch.empty(1, dtype=torch.float32, device=DEV)
+            packed = torch.full((mq.mq_packed_bytes(bits, *shape),), 0x5A, dtype=torch.uint8, device=DEV)
+            mq.mq_quantize_absmax_pack_f32(dev(x), shape[0], shape[1], bits, packed, s, ws, nb)
+            q = torch.empty(shape, dtype=QT[bits], device=DEV)
+            mq.mq_unpack_weight(packed, bits, shape[0], shape[1], q)
+            assert host(s)[0] == os_ and np.array_equal(host(q), oq)
+            outs.append(packed)
+    finally:
+        mq.mq_set_quantize_single_pass(1)
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+
+
+def test_quantize_absmax_pack_skips_nan_and_handles_zero_tensor():
+    x = np.zeros((40, 70), dtype=np.float32)
+    nb = mq.mq_quantize_absmax_ws_bytes()
+    ws = torch.empty(nb, dtype=torch.uint8, device=DEV)
     s = torch.empty(1, dtype=torch.float32, device=DEV)
-    packed = torch.empty(mq.mq_packed_bytes(bits, *shape), dtype=torch.uint8, device=DEV)
-    mq.mq_quantize_absmax_pack_f32(dev(x), shape[0], shape[1], bits, packed, s, ws, nb)
-    q = torch.empty(shape, dtype=QT[bits], device=DEV)
-    mq.mq_unpack_weight(packed, bits, shape[0], shape[1], q)
+    packed = torch.empty(mq.mq_packed_bytes(8, 40, 70), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_absmax_pack_f32(dev(x), 40, 70, 8, packed, s, ws, nb)
+    assert host(s)[0] == 1.0
+    x[3, 5] = np.nan
+    x[7, 9] = -2.5
+    oq, os_ = oracle.quant_int_absmax(x, 8)
+    mq.mq_quantize_absmax_pack_f32(dev(x), 40, 70, 8, packed, s, ws, nb)
+    q = torch.empty((40, 70), dtype=torch.int8, device=DEV)
+    mq.mq_unpack_weight(packed, 8, 40, 70, q)
     assert host(s)[0] == os_ and np.array_equal(host(q), oq)
 
 
