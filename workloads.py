@@ -93,6 +93,32 @@ def config5(M: int = 300, layers: int = 6, V: int = 36000, seed_extra: int = 0):
     return {"bits": 8, "gemms": gemms, "output": out}
 
 
+def config5_chained(M: int = 300, layers: int = 6, d: int = 512, ffn: int = 2048, aan_ffn: int = 2048,
+                    S: int = 25, V: int = 36000, t: int = 20, seed_extra: int = 0):
+    """The same decode step with its real data dependencies: per layer the parameters of the seven
+    products and the three layer normalisations, the running average up to position t - 1, and
+    the precomputed source keys / values [M x S x d]; plus the layer-0 input and the tied embedding."""
+    r = rng_for(5, 1000 + seed_extra)
+
+    def product(N, K):
+        return {"Wt": _normal(r, (N, K), 0.04), "bias": _normal(r, (N,), 0.1)}
+
+    def norm():
+        return {"gamma": (np.float32(1) + _normal(r, (d,), 0.1)).astype(np.float32), "beta": _normal(r, (d,), 0.1)}
+
+    L = []
+    KV = []
+    g_prev = []
+    for _ in range(layers):
+        L.append({"aan_ffn1": product(aan_ffn, d), "aan_ffn2": product(d, aan_ffn), "aan_gate": product(2 * d, 2 * d),
+                  "ln1": norm(), "ctx_q": product(d, d), "ctx_o": product(d, d), "ln2": norm(),
+                  "ffn1": product(ffn, d), "ffn2": product(d, ffn), "ln3": norm()})
+        KV.append((_normal(r, (M, S, d), 1.0), _normal(r, (M, S, d), 1.0)))
+        g_prev.append(_normal(r, (M, d), 1.0 / np.sqrt(max(t - 1, 1))))
+    return {"bits": 8, "t": t, "heads": 8, "x0": _normal(r, (M, d), 1.0), "layers": L, "KV": KV, "g_prev": g_prev,
+            "E": _normal(r, (V, d), 0.05)}
+
+
 def random_problem(seed: int, M: int, N: int, K: int, a_sigma: float = 1.0, w_sigma: float = 0.05):
     """Free-shape problem for parity tests (odd sizes, tails)."""
     r = np.random.default_rng(BASE_SEED * 7 + seed)
