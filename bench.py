@@ -434,6 +434,40 @@ def main():
             "us_per_step": round(us5, 1), "launches": 3 * len(g5) + 4, "tokens_per_s": round(300 / us5 * 1e6, 0),
             "TOPS_useful": round(ops5 / us5 / 1e6, 1)}
         del g5
+
+        # the same decode step with its real dependencies: six chained decoder layers (running average, averaging
+        # block's network and gate, source attention over 25 positions, feed-forward block, layer normalisations)
+        # and the greedy output layer, as one HIP graph
+        cc = workloads.config5_chained()
+        Lc = []
+        for Pl in cc["layers"]:
+            prods = {n_: (mq.prepare_weight(to_dev(Pl[n_]["Wt"]), 8), to_dev(Pl[n_]["bias"]))
+                     for n_ in ("aan_ffn1", "aan_ffn2", "aan_gate", "ctx_q", "ctx_o", "ffn1", "ffn2")}
+            norms = {n_: (to_dev(Pl[n_]["gamma"]), to_dev(Pl[n_]["beta"])) for n_ in ("ln1", "ln2", "ln3")}
+            Lc.append(mq.aan_layer(prods, norms, 512, 2048, 2048))
+        KVc = [(to_dev(k_), to_dev(v_)) for k_, v_ in cc["KV"]]
+        gpc = [to_dev(g_) for g_ in cc["g_prev"]]
+        gnc = [torch.empty_like(g_) for g_ in gpc]
+        xs = [to_dev(cc["x0"])] + [torch.empty((300, 512), dtype=torch.float32, device=dev) for _ in Lc]
+        nwl = mq.mq_aan_layer_ws_bytes(300, 512, 2048, 2048)
+        wsl = torch.empty(nwl, dtype=torch.uint8, device=dev)
+        pec = mq.prepare_weight(to_dev(cc["E"]), 8)
+
+        def chained_step():
+            for l_, layer_ in enumerate(Lc):
+                mq.mq_aan_layer_f32(layer_, xs[l_], gpc[l_], cc["t"], KVc[l_][0], KVc[l_][1], 300, 25, cc["heads"], True,
+                                    True, 1e-6, xs[l_ + 1], gnc[l_], wsl, nwl)
+            mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, 4096)
+            mq.mq_gemm_argmax_packed(qp, pec.packed, M, V, d, s, pec.scale, tok, val, ws, nws)
+
+        chained_step()
+        usc = time_events(graphed(chained_step), max(10, args.steps // 4), 3)
+        extras["aan_decode_step_chained"] = {
+            "workload": "one greedy decode step of the 6-layer base AAN decoder for 300 sentences at position 20: "
+                        "42 int8 products with their float glue (running average, gate, source attention over 25 "
+                        "positions x 8 heads, layer normalisations) and the greedy output layer, one HIP graph",
+            "us_per_step": round(usc, 1), "launches": 6 * 20 + 4, "tokens_per_s": round(300 / usc * 1e6, 0)}
+        del Lc, KVc, wsl
         result["extras"] = extras
     if tuned:
         result["autotuned"] = tuned

@@ -345,6 +345,79 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
                    const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* ---- float glue of the averaging-attention decode step (Sections 3.1, 3.2) ----
+ * Everything here is binary32 on device, row-major, caller-owned; each call is
+ * one launch.  These are the operations between the integer products of a
+ * decoder layer at one decode position. */
+
+/* g = ((t - 1) g_prev + x) / t over n elements, t >= 1: the cumulative uniform
+ * average over the decoder positions seen so far, from the last step only
+ * (Section 3.2).  g may alias g_prev. */
+int mq_running_average_f32(const float* g_prev, const float* x, size_t n, int t, float* g, void* stream);
+
+/* out[m] = [a[m] ; b[m]] for M rows: a [M x da], b [M x db] -> out [M x (da + db)]
+ * (the gate's input is the layer input next to the averaged path). */
+int mq_concat2_f32(const float* a, size_t da, const float* b, size_t db, size_t M, float* out, void* stream);
+
+/* y = LN(a + r) gamma + beta per row of width d <= 8192 with the biased
+ * variance: residual connection + layer normalisation.  gamma, beta: [d]. */
+int mq_add_layer_norm_f32(const float* a, const float* r, const float* gamma, const float* beta,
+                          size_t M, size_t d, float eps, float* y, void* stream);
+
+/* Gate of the averaging block and the normalisation after it, fused:
+ * h = sigmoid(z[:, :d]) x + sigmoid(z[:, d:]) f,  y = LN(h + x) gamma + beta.
+ * x, f: [M x d]; z: [M x 2d], the gate product's output on [x ; f]. */
+int mq_gate_mix_layer_norm_f32(const float* x, const float* f, const float* z, const float* gamma,
+                               const float* beta, size_t M, size_t d, float eps, float* y, void* stream);
+
+/* Source attention of one query per sentence over that sentence's S source
+ * positions: q [M x d], K, V [M x S x d] (precomputed), `heads` heads of width
+ * d / heads: p = softmax_s(q_h . K_h[s] / sqrt(d / heads)), ctx_h = sum_s p[s] V_h[s].
+ * heads * S <= 4096, d divisible by heads. */
+int mq_cross_attention_f32(const float* q, const float* K, const float* V, size_t M, size_t S, size_t d,
+                           int heads, float* ctx, void* stream);
+
+/* One prepared 8-bit parameter product y = A . Wt^T + bias and one layer
+ * normalisation, as plain device pointers. */
+typedef struct mq_product {
+  const void* packed;   /* mq_prepare_weight(bits = 8) of Wt [N x K] */
+  const float* scale;   /* its multiplier, device float[1] */
+  const float* bias;    /* device float[N], or NULL */
+} mq_product;
+typedef struct mq_norm {
+  const float* gamma;   /* device float[d] */
+  const float* beta;    /* device float[d] */
+} mq_norm;
+/* Parameters of one decoder layer (host struct, device pointers inside). */
+typedef struct mq_aan_layer {
+  mq_product aan_ffn1;  /* [aan_ffn x d], ReLU after it */
+  mq_product aan_ffn2;  /* [d x aan_ffn] */
+  mq_product aan_gate;  /* [2d x 2d] on [x ; f] */
+  mq_norm ln1;
+  mq_product ctx_q;     /* [d x d] query projection of the source attention */
+  mq_product ctx_o;     /* [d x d] output projection */
+  mq_norm ln2;
+  mq_product ffn1;      /* [ffn x d], ReLU after it */
+  mq_product ffn2;      /* [d x ffn] */
+  mq_norm ln3;
+  size_t d, ffn, aan_ffn;
+} mq_aan_layer;
+
+/* One decoder layer at decode position t for M sentences (all int8 products
+ * with per-tensor abs-max multipliers, float glue in between):
+ *   g   = running average of x                         -> g_out [M x d]
+ *   f   = aan_ffn2(relu(aan_ffn1(g)))                  (use_ffn = 0: f = g)
+ *   y1  = LN(gate(x, f, aan_gate([x ; f])) + x)        (use_gate = 0: LN(f + x))
+ *   y2  = LN(ctx_o(attention(ctx_q(y1), K, V)) + y1)
+ *   y   = LN(ffn2(relu(ffn1(y2))) + y2)                -> y [M x d]
+ * use_ffn / use_gate = 0 give the "-ffn" / "-gate" variants of Table 2.
+ * ws: device, 256-byte aligned, mq_aan_layer_ws_bytes bytes, contents irrelevant.
+ * Only enqueues; y and g_out must not alias x or g_prev. */
+size_t mq_aan_layer_ws_bytes(size_t M, size_t d, size_t ffn, size_t aan_ffn);
+int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev, int t, const float* K,
+                     const float* V, size_t M, size_t S, int heads, int use_ffn, int use_gate, float eps,
+                     float* y, float* g_out, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,8 @@ __all__ = [
     "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_autotune_ws_bytes", "mq_autotune_gemm",
+    "mq_running_average_f32", "mq_concat2_f32", "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32",
+    "mq_cross_attention_f32", "mq_aan_layer_ws_bytes", "mq_aan_layer_f32", "AanLayer", "aan_layer",
     "PreparedWeight", "prepare_weight",
 ]
 
@@ -55,7 +57,26 @@ def exported_symbols():
             "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
-            "mq_autotune_ws_bytes", "mq_autotune_gemm"]
+            "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_running_average_f32", "mq_concat2_f32",
+            "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32", "mq_cross_attention_f32",
+            "mq_aan_layer_ws_bytes", "mq_aan_layer_f32"]
+
+
+
+# ---- C structs of the decoder-layer entry point (plain device pointers) -----
+
+class _CProduct(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+class _CNorm(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p)]
+
+
+class _CAanLayer(ctypes.Structure):
+    _fields_ = [("aan_ffn1", _CProduct), ("aan_ffn2", _CProduct), ("aan_gate", _CProduct), ("ln1", _CNorm),
+                ("ctx_q", _CProduct), ("ctx_o", _CProduct), ("ln2", _CNorm), ("ffn1", _CProduct), ("ffn2", _CProduct),
+                ("ln3", _CNorm), ("d", ctypes.c_size_t), ("ffn", ctypes.c_size_t), ("aan_ffn", ctypes.c_size_t)]
 
 
 def load_library():
@@ -111,6 +132,15 @@ def load_library():
     lib.mq_ffn_i16_ws_bytes.restype = sz
     lib.mq_ffn_i16_ws_bytes.argtypes = [sz, sz, sz]
     lib.mq_ffn_i16_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    cf = ctypes.c_float
+    lib.mq_running_average_f32.argtypes = [vp, vp, sz, ci, vp, vp]
+    lib.mq_concat2_f32.argtypes = [vp, sz, vp, sz, sz, vp, vp]
+    lib.mq_add_layer_norm_f32.argtypes = [vp, vp, vp, vp, sz, sz, cf, vp, vp]
+    lib.mq_gate_mix_layer_norm_f32.argtypes = [vp, vp, vp, vp, vp, sz, sz, cf, vp, vp]
+    lib.mq_cross_attention_f32.argtypes = [vp, vp, vp, sz, sz, sz, ci, vp, vp]
+    lib.mq_aan_layer_ws_bytes.restype = sz
+    lib.mq_aan_layer_ws_bytes.argtypes = [sz, sz, sz, sz]
+    lib.mq_aan_layer_f32.argtypes = [ctypes.POINTER(_CAanLayer), vp, vp, ci, vp, vp, sz, sz, ci, ci, ci, cf, vp, vp, vp, sz, vp]
     lib.mq_linear_ws_bytes.restype = sz
     lib.mq_linear_ws_bytes.argtypes = [ci, sz, sz]
     lib.mq_linear_f32.argtypes = [vp, sz, sz, vp, vp, vp, ci, sz, vp, ci, vp, vp, vp, sz, vp]
@@ -327,6 +357,42 @@ def mq_ffn_i16_f32(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_b
                                          _p(b2), _p(Y), _p(ws), ws_bytes, _stream(stream)), "mq_ffn_i16_f32")
 
 
+def mq_running_average_f32(g_prev, x, n, t, g, stream=None):
+    _check(load_library().mq_running_average_f32(_p(g_prev), _p(x), n, int(t), _p(g), _stream(stream)),
+           "mq_running_average_f32")
+
+
+def mq_concat2_f32(a, da, b, db, M, out, stream=None):
+    _check(load_library().mq_concat2_f32(_p(a), da, _p(b), db, M, _p(out), _stream(stream)), "mq_concat2_f32")
+
+
+def mq_add_layer_norm_f32(a, r, gamma, beta, M, d, eps, y, stream=None):
+    _check(load_library().mq_add_layer_norm_f32(_p(a), _p(r), _p(gamma), _p(beta), M, d, float(eps), _p(y),
+                                                _stream(stream)), "mq_add_layer_norm_f32")
+
+
+def mq_gate_mix_layer_norm_f32(x, f, z, gamma, beta, M, d, eps, y, stream=None):
+    _check(load_library().mq_gate_mix_layer_norm_f32(_p(x), _p(f), _p(z), _p(gamma), _p(beta), M, d, float(eps), _p(y),
+                                                     _stream(stream)), "mq_gate_mix_layer_norm_f32")
+
+
+def mq_cross_attention_f32(q, K, V, M, S, d, heads, ctx, stream=None):
+    _check(load_library().mq_cross_attention_f32(_p(q), _p(K), _p(V), M, S, d, int(heads), _p(ctx), _stream(stream)),
+           "mq_cross_attention_f32")
+
+
+def mq_aan_layer_ws_bytes(M, d, ffn, aan_ffn) -> int:
+    return int(load_library().mq_aan_layer_ws_bytes(M, d, ffn, aan_ffn))
+
+
+def mq_aan_layer_f32(layer, x, g_prev, t, K, V, M, S, heads, use_ffn, use_gate, eps, y, g_out, ws, ws_bytes,
+                     stream=None):
+    """layer: an AanLayer (see aan_layer); everything else as in include/mq.h."""
+    _check(load_library().mq_aan_layer_f32(ctypes.byref(layer.c), _p(x), _p(g_prev), int(t), _p(K), _p(V), M, S,
+                                           int(heads), int(bool(use_ffn)), int(bool(use_gate)), float(eps), _p(y),
+                                           _p(g_out), _p(ws), ws_bytes, _stream(stream)), "mq_aan_layer_f32")
+
+
 # ---- allocation helper (no arithmetic) --------------------------------------
 
 @dataclass
@@ -350,3 +416,31 @@ def prepare_weight(W: torch.Tensor, bits: int, transposed: bool = True, scale: t
     scale_out = torch.empty(1, dtype=torch.float32, device=W.device)
     mq_prepare_weight(W, transposed, N, K, bits, scale, scale_out, packed, stream)
     return PreparedWeight(packed, scale_out, bits, int(N), int(K))
+
+
+@dataclass
+class AanLayer:
+    """The C struct of one decoder layer plus the tensors that keep its device memory alive."""
+    c: object
+    keep: list
+
+
+def aan_layer(products: dict, norms: dict, d: int, ffn: int, aan_ffn: int) -> AanLayer:
+    """Fill an mq_aan_layer from prepared parameters (marshalling only).
+
+    products: name -> (PreparedWeight, bias tensor or None) for aan_ffn1, aan_ffn2, aan_gate, ctx_q, ctx_o, ffn1,
+    ffn2 (the averaging block's entries may be missing for the "-ffn" / "-gate" variants);
+    norms: name -> (gamma, beta) for ln1, ln2, ln3."""
+    c = _CAanLayer()
+    keep = []
+    for name in ("aan_ffn1", "aan_ffn2", "aan_gate", "ctx_q", "ctx_o", "ffn1", "ffn2"):
+        if name in products:
+            pw, bias = products[name]
+            setattr(c, name, _CProduct(pw.packed.data_ptr(), pw.scale.data_ptr(), None if bias is None else bias.data_ptr()))
+            keep += [pw, bias]
+    for name in ("ln1", "ln2", "ln3"):
+        gamma, beta = norms[name]
+        setattr(c, name, _CNorm(gamma.data_ptr(), beta.data_ptr()))
+        keep += [gamma, beta]
+    c.d, c.ffn, c.aan_ffn = d, ffn, aan_ffn
+    return AanLayer(c, keep)

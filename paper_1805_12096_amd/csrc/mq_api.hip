@@ -637,4 +637,160 @@ int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null, c
   return launch_gemm(a, kEpiDequant, s);
 }
 
+/* ---- float glue of the averaging-attention decode step -------------------- */
+
+int mq_running_average_f32(const float* g_prev, const float* x, size_t n, int t, float* g, void* stream) {
+  if (g_prev == nullptr || x == nullptr || g == nullptr) return MQ_ERR_NULL;
+  if (n == 0 || n > kMaxElems || t < 1) return MQ_ERR_SHAPE;
+  if (!aligned(g_prev, 4) || !aligned(x, 4) || !aligned(g, 4)) return MQ_ERR_ALIGN;
+  return launch_running_average(g_prev, x, n, t, g, as_stream(stream));
+}
+
+int mq_concat2_f32(const float* a, size_t da, const float* b, size_t db, size_t M, float* out, void* stream) {
+  if (a == nullptr || b == nullptr || out == nullptr) return MQ_ERR_NULL;
+  if (M == 0 || da == 0 || db == 0 || M >= kMaxDim || da >= kMaxDim || db >= kMaxDim) return MQ_ERR_SHAPE;
+  if (!aligned(a, 4) || !aligned(b, 4) || !aligned(out, 4)) return MQ_ERR_ALIGN;
+  return launch_concat2(a, da, b, db, M, out, as_stream(stream));
+}
+
+int mq_add_layer_norm_f32(const float* a, const float* r, const float* gamma, const float* beta, size_t M, size_t d,
+                          float eps, float* y, void* stream) {
+  if (a == nullptr || r == nullptr || gamma == nullptr || beta == nullptr || y == nullptr) return MQ_ERR_NULL;
+  if (M == 0 || d == 0 || M >= kMaxDim || d >= kMaxDim || !(eps >= 0.0f)) return MQ_ERR_SHAPE;
+  if (!aligned(a, 4) || !aligned(r, 4) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(y, 4)) return MQ_ERR_ALIGN;
+  return launch_add_layer_norm(a, r, gamma, beta, M, d, eps, y, as_stream(stream));
+}
+
+int mq_gate_mix_layer_norm_f32(const float* x, const float* f, const float* z, const float* gamma, const float* beta,
+                               size_t M, size_t d, float eps, float* y, void* stream) {
+  if (x == nullptr || f == nullptr || z == nullptr || gamma == nullptr || beta == nullptr || y == nullptr)
+    return MQ_ERR_NULL;
+  if (M == 0 || d == 0 || M >= kMaxDim || d >= kMaxDim / 2 || !(eps >= 0.0f)) return MQ_ERR_SHAPE;
+  if (!aligned(x, 4) || !aligned(f, 4) || !aligned(z, 4) || !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(y, 4))
+    return MQ_ERR_ALIGN;
+  return launch_gate_mix_layer_norm(x, f, z, gamma, beta, M, d, eps, y, as_stream(stream));
+}
+
+int mq_cross_attention_f32(const float* q, const float* K, const float* V, size_t M, size_t S, size_t d, int heads,
+                           float* ctx, void* stream) {
+  if (q == nullptr || K == nullptr || V == nullptr || ctx == nullptr) return MQ_ERR_NULL;
+  if (M == 0 || S == 0 || d == 0 || heads <= 0 || M >= kMaxDim || S >= kMaxDim || d >= kMaxDim || d % (size_t)heads != 0)
+    return MQ_ERR_SHAPE;
+  if (!aligned(q, 4) || !aligned(K, 4) || !aligned(V, 4) || !aligned(ctx, 4)) return MQ_ERR_ALIGN;
+  return launch_cross_attention(q, K, V, M, S, d, heads, ctx, as_stream(stream));
+}
+
+namespace mq {
+namespace {
+// Scratch layout of mq_aan_layer_f32: quantizer partials, two multipliers, one packed 8-bit activation
+// buffer sized for the widest product input, and the float intermediates of the layer.
+struct AanWs {
+  size_t off_part, off_gpart, off_scal, off_q, off_hid, off_f, off_cat, off_z, off_y1, off_qv, off_ctx, off_o, off_y2, off_ff, total;
+  AanWs(size_t M, size_t d, size_t ffn, size_t aan_ffn) {
+    const size_t widest = ffn > aan_ffn ? (ffn > 2 * d ? ffn : 2 * d) : (aan_ffn > 2 * d ? aan_ffn : 2 * d);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o = round_up(o + bytes, 256); return at; };
+    off_part = take(kAbsmaxPartials * sizeof(float));
+    off_gpart = take((running_average_partials(M * d) > M ? running_average_partials(M * d) : M) * sizeof(float));
+    off_scal = take(256);
+    off_q = take(PackedDims(8, M, widest).total_bytes());
+    off_hid = take(M * (ffn > aan_ffn ? ffn : aan_ffn) * sizeof(float));
+    off_f = take(M * d * sizeof(float));
+    off_cat = take(M * 2 * d * sizeof(float));
+    off_z = take(M * 2 * d * sizeof(float));
+    off_y1 = take(M * d * sizeof(float));
+    off_qv = take(M * d * sizeof(float));
+    off_ctx = take(M * d * sizeof(float));
+    off_o = take(M * d * sizeof(float));
+    off_y2 = take(M * d * sizeof(float));
+    off_ff = take(M * d * sizeof(float));
+    total = o;
+  }
+};
+bool product_ok(const mq_product& p) {
+  return p.packed != nullptr && p.scale != nullptr && aligned(p.packed, 16) && aligned(p.scale, 4) &&
+         (p.bias == nullptr || aligned(p.bias, 4));
+}
+bool norm_ok(const mq_norm& n) { return n.gamma != nullptr && n.beta != nullptr && aligned(n.gamma, 4) && aligned(n.beta, 4); }
+}  // namespace
+}  // namespace mq
+
+size_t mq_aan_layer_ws_bytes(size_t M, size_t d, size_t ffn, size_t aan_ffn) {
+  if (!dims_ok(M, ffn, d) || !dims_ok(M, aan_ffn, d) || !dims_ok(M, 2 * d, 2 * d)) return 0;
+  return AanWs(M, d, ffn, aan_ffn).total;
+}
+
+int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev, int t, const float* K, const float* V,
+                     size_t M, size_t S, int heads, int use_ffn, int use_gate, float eps, float* y, float* g_out,
+                     void* ws, size_t ws_bytes, void* stream) {
+  if (P == nullptr || x == nullptr || g_prev == nullptr || K == nullptr || V == nullptr || y == nullptr ||
+      g_out == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  const size_t d = P->d, ffn = P->ffn, aan_ffn = P->aan_ffn;
+  if (!dims_ok(M, ffn, d) || !dims_ok(M, aan_ffn, d) || !dims_ok(M, 2 * d, 2 * d) || S == 0 || S >= kMaxDim || t < 1 ||
+      heads <= 0 || d % (size_t)heads != 0 || !(eps >= 0.0f))
+    return MQ_ERR_SHAPE;
+  if (!product_ok(P->ctx_q) || !product_ok(P->ctx_o) || !product_ok(P->ffn1) || !product_ok(P->ffn2) ||
+      !norm_ok(P->ln1) || !norm_ok(P->ln2) || !norm_ok(P->ln3))
+    return MQ_ERR_NULL;
+  if (use_ffn && (!product_ok(P->aan_ffn1) || !product_ok(P->aan_ffn2))) return MQ_ERR_NULL;
+  if (use_gate && !product_ok(P->aan_gate)) return MQ_ERR_NULL;
+  if (!aligned(x, 16) || !aligned(g_prev, 4) || !aligned(K, 4) || !aligned(V, 4) || !aligned(y, 4) ||
+      !aligned(g_out, 16) || !aligned(ws, 256))
+    return MQ_ERR_ALIGN;
+  const AanWs L(M, d, ffn, aan_ffn);
+  if (ws_bytes < L.total) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* base = static_cast<uint8_t*>(ws);
+  float* part = reinterpret_cast<float*>(base + L.off_part);
+  float* sA = reinterpret_cast<float*>(base + L.off_scal);
+  void* qbuf = base + L.off_q;
+  auto fbuf = [&](size_t off) { return reinterpret_cast<float*>(base + off); };
+  float *hid = fbuf(L.off_hid), *f = fbuf(L.off_f), *cat = fbuf(L.off_cat), *z = fbuf(L.off_z), *y1 = fbuf(L.off_y1),
+        *qv = fbuf(L.off_qv), *ctx = fbuf(L.off_ctx), *o = fbuf(L.off_o), *y2 = fbuf(L.off_y2), *ff = fbuf(L.off_ff);
+  float* gpart = reinterpret_cast<float*>(base + L.off_gpart);
+  float* hmax = sA + 1;           // two words: max|hidden| of the two feed-forward networks, cleared by the first kernel
+  // One parameter product: quant_int of the input with its own abs-max multiplier, dot'_int, bias (+ReLU).
+  // The kernel that produced the input has already left partial maxima of it (np of them at `partials`), so the
+  // quantizer needs no abs-max pass of its own; inputs with more rows than the quantizer reduces per block take
+  // the separate pass.  out_amax: optional max|Y| by-product for the product that follows.
+  auto product = [&](const float* A, size_t Kdim, const mq_product& W, size_t N, int relu, float* Y,
+                     const float* partials, size_t np, float* out_amax) -> int {
+    int rc;
+    if (partials != nullptr && np <= kAbsmaxPartials)
+      rc = launch_quantize_pack_partials(A, M, Kdim, 8, partials, (unsigned)np, sA, qbuf, s);
+    else
+      rc = launch_absmax_quantize_pack(A, M, Kdim, 8, part, sA, qbuf, s);
+    if (rc != MQ_OK) return rc;
+    GemmArgs g{};
+    g.qA = qbuf; g.packedW = W.packed; g.bits = 8; g.M = M; g.N = N; g.K = Kdim;
+    g.sA = sA; g.sW = W.scale; g.bias = W.bias; g.relu = relu; g.Y = Y; g.out_amax = out_amax;
+    return launch_gemm_packed(g, kEpiDequant, s);
+  };
+  const size_t np_avg = running_average_partials(M * d);
+  int rc = launch_running_average(g_prev, x, M * d, t, g_out, s, gpart, reinterpret_cast<unsigned*>(hmax), 2);
+  if (rc != MQ_OK) return rc;
+  const float* fpath = g_out;
+  if (use_ffn) {
+    if ((rc = product(g_out, d, P->aan_ffn1, aan_ffn, 1, hid, gpart, np_avg, hmax)) != MQ_OK) return rc;
+    if ((rc = product(hid, aan_ffn, P->aan_ffn2, d, 0, f, hmax, 1, nullptr)) != MQ_OK) return rc;
+    fpath = f;
+  }
+  if (use_gate) {
+    if ((rc = launch_concat2(x, d, fpath, d, M, cat, s, gpart)) != MQ_OK) return rc;
+    if ((rc = product(cat, 2 * d, P->aan_gate, 2 * d, 0, z, gpart, M, nullptr)) != MQ_OK) return rc;
+    rc = launch_gate_mix_layer_norm(x, fpath, z, P->ln1.gamma, P->ln1.beta, M, d, eps, y1, s, gpart);
+  } else {
+    rc = launch_add_layer_norm(fpath, x, P->ln1.gamma, P->ln1.beta, M, d, eps, y1, s, gpart);
+  }
+  if (rc != MQ_OK) return rc;
+  if ((rc = product(y1, d, P->ctx_q, d, 0, qv, gpart, M, nullptr)) != MQ_OK) return rc;
+  if ((rc = launch_cross_attention(qv, K, V, M, S, d, heads, ctx, s, gpart)) != MQ_OK) return rc;
+  if ((rc = product(ctx, d, P->ctx_o, d, 0, o, gpart, M, nullptr)) != MQ_OK) return rc;
+  if ((rc = launch_add_layer_norm(o, y1, P->ln2.gamma, P->ln2.beta, M, d, eps, y2, s, gpart)) != MQ_OK) return rc;
+  if ((rc = product(y2, d, P->ffn1, ffn, 1, hid, gpart, M, hmax + 1)) != MQ_OK) return rc;
+  if ((rc = product(hid, ffn, P->ffn2, d, 0, ff, hmax + 1, 1, nullptr)) != MQ_OK) return rc;
+  return launch_add_layer_norm(ff, y2, P->ln3.gamma, P->ln3.beta, M, d, eps, y, s);
+}
+
 }  // extern "C"

@@ -109,6 +109,19 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
 constexpr unsigned kBarrierWords = 320;
 unsigned long long barrier_timeout_ticks();
 void set_barrier_timeout_ticks(unsigned long long ticks);
+// float glue of the averaging-attention decode step (mq_glue.hip).  `partial` (optional) receives one
+// max|output| per workgroup: running_average_partials(n) of them for the running average, M for the others.
+size_t running_average_partials(size_t n);
+int launch_running_average(const float* g_prev, const float* x, size_t n, int t, float* g, hipStream_t s,
+                           float* partial = nullptr, unsigned* clear = nullptr, unsigned nclear = 0);
+int launch_concat2(const float* a, size_t da, const float* b, size_t db, size_t M, float* out, hipStream_t s,
+                   float* partial = nullptr);
+int launch_add_layer_norm(const float* a, const float* r, const float* gamma, const float* beta, size_t M, size_t d,
+                          float eps, float* y, hipStream_t s, float* partial = nullptr);
+int launch_gate_mix_layer_norm(const float* x, const float* f, const float* z, const float* gamma, const float* beta,
+                               size_t M, size_t d, float eps, float* y, hipStream_t s, float* partial = nullptr);
+int launch_cross_attention(const float* q, const float* K, const float* V, size_t M, size_t S, size_t d, int heads,
+                           float* ctx, hipStream_t s, float* partial = nullptr);
 int launch_clear_words(unsigned* p, unsigned n, hipStream_t s);
 int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
                              hipStream_t s);
