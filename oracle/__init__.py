@@ -215,6 +215,35 @@ def greedy_output_layer(Hd, E, bits: int = 8, sA=None, sW=None, shortlist=None):
             "tok": tok, "maxlogit": val}
 
 
+def topk_log_softmax(Hd, E, k: int, bits: int = 8, sA=None, sW=None):
+    """Output layer for beam search with beam size k > 1 (Table 2, the b = 2 and b = 4 rows): the k most
+    probable words of every row with their log-probabilities, log p[n] = y[n] - log sum_n' exp(y[n']).
+
+    Logits y = (float) acc * u with u = 1 / (sA * sW) as in dequant_bias (no bias: tied output layer);
+    the normaliser is evaluated in binary64 from those binary32 logits.  The k best are chosen on the
+    integer sums (u > 0), ties towards the lower vocabulary index, best first."""
+    if sA is None:
+        sA = scale_from_amax(absmax(Hd), bits)
+    if sW is None:
+        sW = scale_from_amax(absmax(E), bits)
+    qA = quant_int(Hd, bits, sA)
+    qW = quant_int(E, bits, sW)
+    acc = dot_int(qA, qW)
+    M, N = acc.shape
+    if not 1 <= k <= N:
+        raise ValueError("k must be between 1 and the vocabulary size")
+    y32 = dequant_bias(acc, sA, sW)                       # binary32 logits, one rounding each
+    y = y32.astype(np.float64)
+    mx = y.max(axis=1, keepdims=True)
+    lse = np.log(np.exp(y - mx).sum(axis=1, keepdims=True)) + mx
+    tok = np.empty((M, k), dtype=np.int32)
+    for m in range(M):
+        order = np.lexsort((np.arange(N), -acc[m].astype(np.int64)))      # sum descending, index ascending
+        tok[m] = order[:k]
+    logprob = np.take_along_axis(y, tok.astype(np.int64), axis=1) - lse
+    return {"sA": np.float32(sA), "sW": np.float32(sW), "acc": acc, "tok": tok, "logprob": logprob, "lse": lse[:, 0]}
+
+
 def timed(fn, *args, **kw):
     t0 = time.perf_counter()
     out = fn(*args, **kw)

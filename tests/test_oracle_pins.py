@@ -375,3 +375,38 @@ def test_shortlisted_output_layer_is_argmax_over_the_listed_rows():
     assert np.array_equal(oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=keep)["tok"], full["tok"])
     with pytest.raises(ValueError):
         oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=[5, 5, 7])
+
+
+def test_topk_log_softmax_against_library_routines_and_special_cases():
+    # Beam search with beam size k > 1 (Table 2, b = 2 / b = 4) needs the k best words with normalised
+    # log-probabilities.  Pinned against scipy's log_softmax on the float product of the quantized integers,
+    # against numpy's stable argsort, and by closed forms.
+    from scipy.special import log_softmax
+    c = workloads.config3(M=7, V=300, d=48, seed_extra=9)
+    r = oracle.topk_log_softmax(c["Hd"], c["E"], 4)
+    u = np.float32(1) / (r["sA"] * r["sW"])
+    y = (r["acc"].astype(np.float32) * u).astype(np.float64)
+    lp = log_softmax(y, axis=1)
+    order = np.argsort(-r["acc"].astype(np.int64), axis=1, kind="stable")[:, :4]
+    assert np.array_equal(r["tok"], order)
+    assert np.allclose(r["logprob"], np.take_along_axis(lp, order, axis=1), rtol=0, atol=1e-12)
+    # the best word is the greedy arg-max, log-probabilities descend, and all V of them sum to one
+    assert np.array_equal(r["tok"][:, 0], oracle.greedy_output_layer(c["Hd"], c["E"])["tok"])
+    assert np.all(np.diff(r["logprob"], axis=1) <= 0)
+    full = oracle.topk_log_softmax(c["Hd"], c["E"], 300)
+    assert np.allclose(np.exp(full["logprob"]).sum(axis=1), 1.0, atol=1e-12)
+    assert np.array_equal(np.sort(full["tok"], axis=1), np.tile(np.arange(300), (7, 1)))
+    # identical embedding rows: every word has probability 1 / V, ties go to the lowest indices in order
+    E = np.tile(c["E"][:1], (16, 1))
+    t = oracle.topk_log_softmax(c["Hd"], E, 3)
+    assert np.array_equal(t["tok"], np.tile(np.arange(3), (7, 1)))
+    assert np.allclose(t["logprob"], -np.log(16.0), atol=1e-12)
+    # planted tie between a high and a low index
+    E2 = c["E"].copy()
+    E2[250] = E2[3]
+    t2 = oracle.topk_log_softmax(c["Hd"], E2, 300)
+    pos3 = np.argmax(t2["tok"] == 3, axis=1)
+    pos250 = np.argmax(t2["tok"] == 250, axis=1)
+    assert np.all(pos250 == pos3 + 1)
+    with pytest.raises(ValueError):
+        oracle.topk_log_softmax(c["Hd"], c["E"], 0)
