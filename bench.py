@@ -358,6 +358,26 @@ def main():
                                                                 tok, val, ws, nws))
         extras["output_layer_shortlist"] = {"shortlist_rows": int(sl.numel()), "argmax_product_only_us": round(us3s, 2)}
 
+        # beam search (Table 2, b = 2 / b = 4): 300 sentences x beam hypotheses, the k = beam best words per row with
+        # log-probabilities (softmax normaliser fused into the streaming kernel)
+        beam_out = {}
+        for beam in (2, 4):
+            rows_b = M * beam
+            Hb = torch.randn(rows_b, d, device=dev)
+            qb = torch.empty(mq.mq_packed_bytes(8, rows_b, d), dtype=torch.uint8, device=dev)
+            sb = torch.empty(1, dtype=torch.float32, device=dev)
+            mq.mq_quantize_absmax_pack_f32(Hb, rows_b, d, 8, qb, sb, qws, 4096)
+            nwb = mq.mq_topk_ws_bytes(rows_b, V, beam)
+            wsb = torch.empty(nwb, dtype=torch.uint8, device=dev)
+            tokb = torch.empty((rows_b, beam), dtype=torch.int32, device=dev)
+            lpb = torch.empty((rows_b, beam), dtype=torch.float32, device=dev)
+            usb = time_kernel(lambda: mq.mq_gemm_topk_packed(qb, pe.packed, None, 0, rows_b, V, d, sb, pe.scale, beam,
+                                                             tokb, lpb, wsb, nwb))
+            beam_out[f"beam{beam}"] = {"rows": rows_b, "us": round(usb, 2),
+                                       "TOPS": round(2 * rows_b * V * d / usb / 1e6, 1)}
+            del Hb, qb, wsb
+        extras["output_layer_beam_topk"] = beam_out
+
         # the same FFN block with the paper's fixed multipliers (127/2 on inputs clipped to [-2, 2]): no abs-max
         # pass, the intermediate is quantized in the first product's epilogue -> three launches
         sc = torch.full((1,), 63.5, dtype=torch.float32, device=dev)

@@ -345,6 +345,22 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
                    const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* Output layer for beam search with beam size > 1 (Table 2, the b = 2 and b = 4
+ * rows): for every row of the packed hidden states the k <= 4 most probable
+ * words, best first (ties towards the lower vocabulary id), with
+ * log p = y - log sum_n exp(y[n]),  y = (float) acc / (sA sW), the sum running
+ * over all N words (or over the short list when one is given: ascending ids,
+ * shortlist_len >= k; NULL = whole vocabulary).  The embedding streams through
+ * the chip once per 256 rows; logits are never stored.  tok: int32 [M x k],
+ * logprob: float [M x k].  Limits: K <= 512, N <= 1044480; MQ_ERR_UNSUPPORTED
+ * beyond.  The words are exact (chosen on the integer sums); the log-
+ * probabilities are binary32 (within 1e-4 of the binary64 value for logits of
+ * magnitude up to ~100).  ws: device, 16-byte aligned, mq_topk_ws_bytes(M, N, k). */
+size_t mq_topk_ws_bytes(size_t M, size_t N, int k);
+int mq_gemm_topk_packed(const void* packedA, const void* packedW, const int32_t* shortlist_or_null,
+                        size_t shortlist_len, size_t M, size_t N, size_t K, const float* sA, const float* sW,
+                        int k, int32_t* tok, float* logprob, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- float glue of the averaging-attention decode step (Sections 3.1, 3.2) ----
  * Everything here is binary32 on device, row-major, caller-owned; each call is
  * one launch.  These are the operations between the integer products of a

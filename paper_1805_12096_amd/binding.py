@@ -22,6 +22,7 @@ __all__ = [
     "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_autotune_ws_bytes", "mq_autotune_gemm",
+    "mq_topk_ws_bytes", "mq_gemm_topk_packed",
     "mq_running_average_f32", "mq_concat2_f32", "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32",
     "mq_cross_attention_f32", "mq_aan_layer_ws_bytes", "mq_aan_layer_f32", "AanLayer", "aan_layer",
     "PreparedWeight", "prepare_weight",
@@ -57,7 +58,7 @@ def exported_symbols():
             "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
-            "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_running_average_f32", "mq_concat2_f32",
+            "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_topk_ws_bytes", "mq_gemm_topk_packed", "mq_running_average_f32", "mq_concat2_f32",
             "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32", "mq_cross_attention_f32",
             "mq_aan_layer_ws_bytes", "mq_aan_layer_f32"]
 
@@ -133,6 +134,9 @@ def load_library():
     lib.mq_ffn_i16_ws_bytes.argtypes = [sz, sz, sz]
     lib.mq_ffn_i16_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     cf = ctypes.c_float
+    lib.mq_topk_ws_bytes.restype = sz
+    lib.mq_topk_ws_bytes.argtypes = [sz, sz, ci]
+    lib.mq_gemm_topk_packed.argtypes = [vp, vp, vp, sz, sz, sz, sz, vp, vp, ci, vp, vp, vp, sz, vp]
     lib.mq_running_average_f32.argtypes = [vp, vp, sz, ci, vp, vp]
     lib.mq_concat2_f32.argtypes = [vp, sz, vp, sz, sz, vp, vp]
     lib.mq_add_layer_norm_f32.argtypes = [vp, vp, vp, vp, sz, sz, cf, vp, vp]
@@ -355,6 +359,17 @@ def mq_ffn_i16_ws_bytes(M, d, f) -> int:
 def mq_ffn_i16_f32(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_bytes, stream=None):
     _check(load_library().mq_ffn_i16_f32(_p(A), M, d, f, _p(packedW1), _p(sW1), _p(b1), _p(packedW2), _p(sW2),
                                          _p(b2), _p(Y), _p(ws), ws_bytes, _stream(stream)), "mq_ffn_i16_f32")
+
+
+def mq_topk_ws_bytes(M, N, k) -> int:
+    return int(load_library().mq_topk_ws_bytes(M, N, int(k)))
+
+
+def mq_gemm_topk_packed(packedA, packedW, shortlist, shortlist_len, M, N, K, sA, sW, k, tok, logprob, ws, ws_bytes,
+                        stream=None):
+    _check(load_library().mq_gemm_topk_packed(_p(packedA), _p(packedW), _p(shortlist), shortlist_len, M, N, K, _p(sA),
+                                              _p(sW), int(k), _p(tok), _p(logprob), _p(ws), ws_bytes, _stream(stream)),
+           "mq_gemm_topk_packed")
 
 
 def mq_running_average_f32(g_prev, x, n, t, g, stream=None):

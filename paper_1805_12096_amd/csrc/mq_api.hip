@@ -430,6 +430,29 @@ int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int
                               as_stream(stream));
 }
 
+size_t mq_topk_ws_bytes(size_t M, size_t N, int k) {
+  if (M == 0 || N == 0 || M >= kMaxDim || N >= kMaxDim || k < 1 || k > 4) return 0;
+  return topk_stream_ws_bytes(M, k);
+}
+
+int mq_gemm_topk_packed(const void* packedA, const void* packedW, const int32_t* shortlist_or_null,
+                        size_t shortlist_len, size_t M, size_t N, size_t K, const float* sA, const float* sW, int k,
+                        int32_t* tok, float* logprob, void* ws, size_t ws_bytes, void* stream) {
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || tok == nullptr ||
+      logprob == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K) || k < 1 || k > 4 || (size_t)k > N) return MQ_ERR_SHAPE;
+  if (shortlist_or_null != nullptr && (shortlist_len == 0 || shortlist_len > N || (size_t)k > shortlist_len))
+    return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(tok, 4) ||
+      !aligned(logprob, 4) || !aligned(ws, 16) || (shortlist_or_null != nullptr && !aligned(shortlist_or_null, 4)))
+    return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_topk_ws_bytes(M, N, k)) return MQ_ERR_WORKSPACE;
+  if (!topk_stream_supported(M, N, K, k)) return MQ_ERR_UNSUPPORTED;
+  return launch_topk_stream(packedA, packedW, M, N, K, sA, sW, k, tok, logprob, ws, shortlist_or_null, shortlist_len,
+                            as_stream(stream));
+}
+
 int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
                    const float* sW, int32_t* tok, float* maxlogit, void* ws, size_t ws_bytes,
                    void* stream) {

@@ -56,6 +56,11 @@ struct ArgmaxParams {
   unsigned long long* partial;   // [M][gridDim.x]
   const int32_t* shortlist;      // optional: vocabulary rows to score, ascending; NULL = all N rows
   unsigned L;                    // candidates: shortlist length, or N
+  // beam search (BEAM > 1): partial holds [M][gridDim.x][BEAM] keys, norm [M][gridDim.x] (max, sum) pairs of
+  // the softmax normaliser in base 2, u2 = log2(e) / (sA sW) is formed in the kernel
+  float2* norm;
+  const float* sA;
+  const float* sW;
 };
 
 // What lane l feeds to the 16x16x64 MFMA for rows 16 u .. 16 u + 15 of a packed
@@ -83,7 +88,10 @@ __device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, 
 #define MQ_ASTAMP(i) do { } while (0)
 #endif
 
-template <int TPW, bool GATHER>
+// BEAM > 1 (beam search, Table 2's b = 2 and b = 4 rows): every accumulator register keeps its BEAM best
+// keys instead of one (sorted insertion: BEAM max / min pairs per candidate), and every sentence tile keeps
+// a running (max, sum) of 2^(logit log2 e) so that the k best words come with normalised log-probabilities.
+template <int TPW, bool GATHER, int BEAM = 1>
 __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p) {
   constexpr int KG = kKG, S = kStages;
   constexpr int STAGE = KG * kFragBytes;
@@ -160,10 +168,49 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   // -2^23, so a key whose sum field is -2^23 means "no candidate yet".
   constexpr int kNone = (int)0x80000000;
   int best[TPW][4];
+  int more_best[BEAM > 1 ? TPW : 1][4][BEAM > 1 ? BEAM - 1 : 1];     // places 2 .. BEAM of each register's list
+  float run_max[TPW], run_sum[TPW];                                    // softmax normaliser, base 2 (BEAM > 1)
+  float u2 = 0.f;
+  if constexpr (BEAM > 1) u2 = __fmul_rn(__fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW)), 1.44269504088896340736f);
 #pragma unroll
-  for (int i = 0; i < TPW; ++i)
+  for (int i = 0; i < TPW; ++i) {
+    run_max[i] = -INFINITY;
+    run_sum[i] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) best[i][r] = kNone;
+    for (int r = 0; r < 4; ++r) {
+      best[i][r] = kNone;
+      if constexpr (BEAM > 1)
+#pragma unroll
+        for (int j = 0; j < BEAM - 1; ++j) more_best[i][r][j] = kNone;
+    }
+  }
+  // one sentence tile's four new sums (one stage): keys into the sorted lists, logits into the normaliser;
+  // valid[r] = false leaves candidate r out (padding past the last candidate)
+  auto beam_update = [&](int i, const v4i& sums, int tag, bool v0, bool v1, bool v2, bool v3) {
+    const bool valid[4] = {v0, v1, v2, v3};
+    float f[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int key = valid[r] ? ((sums[r] << 8) | (tag & 255)) : kNone;
+      const int t0 = max(best[i][r], key);
+      key = min(best[i][r], key);
+      best[i][r] = t0;
+#pragma unroll
+      for (int j = 0; j < BEAM - 1; ++j) {
+        const int t = max(more_best[i][r][j], key);
+        key = min(more_best[i][r][j], key);
+        more_best[i][r][j] = t;
+      }
+      f[r] = valid[r] ? __fmul_rn((float)sums[r], u2) : -INFINITY;
+    }
+    const float mnew = fmaxf(fmaxf(run_max[i], fmaxf(f[0], f[1])), fmaxf(f[2], f[3]));
+    if (mnew > -INFINITY) {          // (no valid candidate so far: nothing to add, and inf - inf is avoided)
+      run_sum[i] = run_sum[i] * __builtin_amdgcn_exp2f(run_max[i] - mnew) + __builtin_amdgcn_exp2f(f[0] - mnew) +
+                   __builtin_amdgcn_exp2f(f[1] - mnew) + __builtin_amdgcn_exp2f(f[2] - mnew) +
+                   __builtin_amdgcn_exp2f(f[3] - mnew);
+      run_max[i] = mnew;
+    }
+  };
 
   // Before stage s is multiplied, stages s and s + 1 must have landed (s + 1 is read from LDS into
   // registers while s is multiplied).  Loads issued so far: stages 0 .. min(nlocal, s + S - 1) - 1.
@@ -211,9 +258,14 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 #pragma unroll
       for (int i = 0; i < NT; ++i)
         cur[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(e[g], hid[i][g], g == 0 ? zero : cur[i], 0, 0, 0);
+      if constexpr (BEAM == 1) {
 #pragma unroll
-      for (int j = g * PER; j < (g + 1) * PER && j < ITEMS; ++j)
-        best[j / 4][j % 4] = max(best[j / 4][j % 4], (prev[j / 4][j % 4] << 8) | (prev_tag & 255));
+        for (int j = g * PER; j < (g + 1) * PER && j < ITEMS; ++j)
+          best[j / 4][j % 4] = max(best[j / 4][j % 4], (prev[j / 4][j % 4] << 8) | (prev_tag & 255));
+      } else {
+        // one sentence tile of the stage before per MFMA group (stage 0 has no stage before it)
+        if (g < NT && s > 0) beam_update(g < TPW ? g : 0, prev[g < TPW ? g : 0], prev_tag, true, true, true, true);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -265,14 +317,82 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     const unsigned unit0 = (first + sl * stride) * 16 + 4 * (lane / 16);
     const int tag = 255 - (int)sl;
 #pragma unroll
-    for (int i = 0; i < TPW; ++i)
+    for (int i = 0; i < TPW; ++i) {
+      if constexpr (BEAM == 1) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int v = (sl % 2 == 0) ? acc0[i][r] : acc1[i][r];
-        if (unit0 + r < p.L) best[i][r] = max(best[i][r], (v << 8) | tag);
+        for (int r = 0; r < 4; ++r) {
+          const int v = (sl % 2 == 0) ? acc0[i][r] : acc1[i][r];
+          if (unit0 + r < p.L) best[i][r] = max(best[i][r], (v << 8) | tag);
+        }
+      } else {
+        if (i < ntl)
+          beam_update(i, (sl % 2 == 0) ? acc0[i] : acc1[i], tag, unit0 + 0 < p.L, unit0 + 1 < p.L, unit0 + 2 < p.L,
+                      unit0 + 3 < p.L);
       }
+    }
   }
 
+  if constexpr (BEAM > 1) {
+    // Per sentence tile: decode the 4 x BEAM register keys into (sum, lowest index) keys, keep the BEAM best,
+    // merge with the three other lane groups that hold candidates of the same sentence, and write the list
+    // and the normaliser's (max, sum) pair.
+    auto decode = [&](int k32) -> unsigned long long {
+      const int sum = k32 >> 8;
+      if (sum == -8388608) return 0ull;
+      const unsigned st = 255u - (unsigned)(k32 & 255);
+      const unsigned n = (first + st * stride) * 16 + 4 * (lane / 16);
+      return ((unsigned long long)((unsigned)sum ^ 0x80000000u) << 32) | (unsigned long long)(0xFFFFFFFFu - n);
+    };
+    auto insert = [&](unsigned long long (&top)[BEAM], unsigned long long k) {
+#pragma unroll
+      for (int j = 0; j < BEAM; ++j) {
+        const unsigned long long hi = top[j] > k ? top[j] : k;
+        k = top[j] > k ? k : top[j];
+        top[j] = hi;
+      }
+    };
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+      unsigned long long top[BEAM];
+#pragma unroll
+      for (int j = 0; j < BEAM; ++j) top[j] = 0ull;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        unsigned long long k = decode(best[i][r]);
+        if (k != 0ull) k -= (unsigned)r;                       // candidate index 4 (l / 16) + r: larger index, smaller key
+        insert(top, k);
+#pragma unroll
+        for (int j = 0; j < BEAM - 1; ++j) {
+          unsigned long long k2 = decode(more_best[i][r][j]);
+          if (k2 != 0ull) k2 -= (unsigned)r;
+          insert(top, k2);
+        }
+      }
+      float mx = run_max[i], sm = run_sum[i];
+#pragma unroll
+      for (int off = 16; off <= 32; off *= 2) {
+        unsigned long long other[BEAM];
+#pragma unroll
+        for (int j = 0; j < BEAM; ++j) other[j] = __shfl_xor(top[j], off, 64);
+#pragma unroll
+        for (int j = 0; j < BEAM; ++j) insert(top, other[j]);
+        const float omx = __shfl_xor(mx, off, 64), osm = __shfl_xor(sm, off, 64);
+        const float m2 = fmaxf(mx, omx);
+        if (m2 > -INFINITY) {
+          sm = sm * __builtin_amdgcn_exp2f(mx - m2) + osm * __builtin_amdgcn_exp2f(omx - m2);
+          mx = m2;
+        }
+      }
+      const unsigned m = (wave + kWaves * i) * 16 + lane % 16;
+      if (lane < 16 && m < p.M && i < ntl) {
+        const size_t at = (size_t)m * gridDim.x + blockIdx.x;
+#pragma unroll
+        for (int j = 0; j < BEAM; ++j) p.partial[at * BEAM + j] = top[j];
+        p.norm[at] = make_float2(mx, sm);
+      }
+    }
+    return;
+  }
   // decode the per-register winners, pick the best of the four (smaller word index on ties), merge the
   // four lane groups that share a sentence, and write one key per sentence
 #pragma unroll
@@ -334,14 +454,83 @@ __global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long*
   }
 }
 
-template <int TPW, bool GATHER>
+// Beam search: one wave per row.  Merges the per-workgroup lists into the k best (sum, lowest index) keys
+// and the per-workgroup (max, sum) pairs into log sum exp; writes tok [M x k] and logprob [M x k].
+template <int BEAM>
+__global__ __launch_bounds__(256) void k_topk_reduce(const unsigned long long* __restrict__ partial,
+                                                     const float2* __restrict__ norm, unsigned cols, unsigned M,
+                                                     unsigned k, const float* __restrict__ sA,
+                                                     const float* __restrict__ sW, int32_t* __restrict__ tok,
+                                                     float* __restrict__ logprob,
+                                                     const int32_t* __restrict__ shortlist) {
+  const int lane = threadIdx.x % 64;
+  const unsigned m = blockIdx.x * 4 + threadIdx.x / 64;
+  if (m >= M) return;
+  unsigned long long top[BEAM];
+#pragma unroll
+  for (int j = 0; j < BEAM; ++j) top[j] = 0ull;
+  float mx = -INFINITY, sm = 0.f;
+  for (unsigned g = lane; g < cols; g += 64) {
+    const size_t at = (size_t)m * cols + g;
+#pragma unroll
+    for (int j = 0; j < BEAM; ++j) {
+      unsigned long long key = partial[at * BEAM + j];
+#pragma unroll
+      for (int q = 0; q < BEAM; ++q) {
+        const unsigned long long hi = top[q] > key ? top[q] : key;
+        key = top[q] > key ? key : top[q];
+        top[q] = hi;
+      }
+    }
+    const float2 nm = norm[at];
+    const float m2 = fmaxf(mx, nm.x);
+    if (m2 > -INFINITY) {
+      sm = sm * __builtin_amdgcn_exp2f(mx - m2) + nm.y * __builtin_amdgcn_exp2f(nm.x - m2);
+      mx = m2;
+    }
+  }
+  // normaliser over the wave
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float omx = __shfl_xor(mx, off, 64), osm = __shfl_xor(sm, off, 64);
+    const float m2 = fmaxf(mx, omx);
+    if (m2 > -INFINITY) {
+      sm = sm * __builtin_amdgcn_exp2f(mx - m2) + osm * __builtin_amdgcn_exp2f(omx - m2);
+      mx = m2;
+    }
+  }
+  const float u = __fdiv_rn(1.0f, __fmul_rn(*sA, *sW));
+  const float lse = (mx + __builtin_amdgcn_logf(sm)) * 0.693147180559945309417f;     // log2 -> natural log
+  // k rounds: the wave's best key wins, the lane that held it moves its list up
+  for (unsigned j = 0; j < k; ++j) {
+    unsigned long long w = top[0];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const unsigned long long o = __shfl_xor(w, off, 64);
+      if (o > w) w = o;
+    }
+    if (top[0] == w && w != 0ull) {      // keys are unique (the index is part of the key)
+#pragma unroll
+      for (int q = 0; q + 1 < BEAM; ++q) top[q] = top[q + 1];
+      top[BEAM - 1] = 0ull;
+    }
+    if (lane == 0) {
+      const int sum = (int)((unsigned)(w >> 32) ^ 0x80000000u);
+      const unsigned pos = 0xFFFFFFFFu - (unsigned)(w & 0xFFFFFFFFull);
+      tok[(size_t)m * k + j] = shortlist != nullptr ? shortlist[pos] : (int32_t)pos;
+      logprob[(size_t)m * k + j] = __fmul_rn((float)sum, u) - lse;
+    }
+  }
+}
+
+template <int TPW, bool GATHER, int BEAM = 1>
 int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
   constexpr size_t smem = (size_t)kStages * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0)
 #ifdef MQ_TS
                           + 256
 #endif
       ;
-  auto kern = k_argmax_stream<TPW, GATHER>;
+  auto kern = k_argmax_stream<TPW, GATHER, BEAM>;
   static bool attr_done = false;
   if (!attr_done) {
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -373,6 +562,7 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
   p.partial = static_cast<unsigned long long*>(ws);
   p.shortlist = shortlist;
   p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
+  p.norm = nullptr; p.sA = sA; p.sW = sW;
   const PackedDims dW(8, N, K);
   static int cus = 0;               // compute units of the device, asked once
   if (cus == 0) {
@@ -406,6 +596,75 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
   hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, p.partial, grid, (unsigned)M,
                      sA, sW, tok, maxlogit, shortlist);
   return check_hip(hipGetLastError());
+}
+
+size_t topk_stream_ws_bytes(size_t M, int k) {
+  const size_t rows = M < 256 ? M : 256;           // rows are processed 256 at a time
+  const int beam = k <= 2 ? 2 : 4;
+  return round_up((size_t)256 * rows * beam * sizeof(unsigned long long), 256) + (size_t)256 * rows * sizeof(float2);
+}
+
+bool topk_stream_supported(size_t M, size_t N, size_t K, int k) {
+  (void)M;
+  return k >= 1 && k <= 4 && (size_t)k <= N && K <= 64 * kKG && N <= (size_t)255 * 256 * 16;
+}
+
+// Beam-search output layer: the k <= 4 best words of every row with log-probabilities.  Rows are processed in
+// chunks of 256 (two sentence tiles per wave), each chunk streaming the embedding once.
+int launch_topk_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                       const float* sW, int k, int32_t* tok, float* logprob, void* ws, const int32_t* shortlist,
+                       size_t shortlist_len, hipStream_t s) {
+  if (!topk_stream_supported(M, N, K, k)) return MQ_ERR_UNSUPPORTED;
+  if (shortlist != nullptr && (size_t)k > shortlist_len) return MQ_ERR_SHAPE;
+  const PackedDims dW(8, N, K), dAll(8, M, K);
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+  }
+  const size_t units = shortlist != nullptr ? (shortlist_len + 15) / 16 : dW.nblocks * 2;
+  unsigned grid = (unsigned)(units < (size_t)cus ? units : (size_t)cus);
+  if (grid > 256u) grid = 256u;
+  if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
+  const int beam = k <= 2 ? 2 : 4;
+  const size_t rows_max = M < 256 ? M : 256;
+  unsigned long long* keys = static_cast<unsigned long long*>(ws);
+  float2* norm = reinterpret_cast<float2*>(static_cast<uint8_t*>(ws) +
+                                           round_up((size_t)256 * rows_max * beam * sizeof(unsigned long long), 256));
+  for (size_t row0 = 0; row0 < M; row0 += 256) {
+    const size_t rows = M - row0 < 256 ? M - row0 : 256;
+    ArgmaxParams p;
+    p.packedA = static_cast<const uint8_t*>(packedA) + dAll.frag_offset(row0 / 32, 0);
+    p.packedW = static_cast<const uint8_t*>(packedW);
+    p.M = (unsigned)rows; p.N = (unsigned)N; p.K = (unsigned)K;
+    p.partial = keys; p.norm = norm; p.sA = sA; p.sW = sW;
+    p.shortlist = shortlist;
+    p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
+    const int tpw = (int)(((rows + 15) / 16 + kWaves - 1) / kWaves);
+    int rc;
+    if (shortlist != nullptr) {
+      if (beam == 2) rc = tpw == 1 ? launch_stream<1, true, 2>(p, grid, s) : launch_stream<2, true, 2>(p, grid, s);
+      else rc = tpw == 1 ? launch_stream<1, true, 4>(p, grid, s) : launch_stream<2, true, 4>(p, grid, s);
+    } else {
+      if (beam == 2) rc = tpw == 1 ? launch_stream<1, false, 2>(p, grid, s) : launch_stream<2, false, 2>(p, grid, s);
+      else rc = tpw == 1 ? launch_stream<1, false, 4>(p, grid, s) : launch_stream<2, false, 4>(p, grid, s);
+    }
+    if (rc != MQ_OK) return rc;
+    int32_t* tok_c = tok + row0 * (size_t)k;
+    float* lp_c = logprob + row0 * (size_t)k;
+    if (beam == 2)
+      hipLaunchKernelGGL((k_topk_reduce<2>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, keys, norm, grid,
+                         (unsigned)rows, (unsigned)k, sA, sW, tok_c, lp_c, shortlist);
+    else
+      hipLaunchKernelGGL((k_topk_reduce<4>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, keys, norm, grid,
+                         (unsigned)rows, (unsigned)k, sA, sW, tok_c, lp_c, shortlist);
+    rc = check_hip(hipGetLastError());
+    if (rc != MQ_OK) return rc;
+  }
+  return MQ_OK;
 }
 
 }  // namespace mq

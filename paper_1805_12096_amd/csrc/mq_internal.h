@@ -109,6 +109,11 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
 constexpr unsigned kBarrierWords = 320;
 unsigned long long barrier_timeout_ticks();
 void set_barrier_timeout_ticks(unsigned long long ticks);
+size_t topk_stream_ws_bytes(size_t M, int k);
+bool topk_stream_supported(size_t M, size_t N, size_t K, int k);
+int launch_topk_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
+                       const float* sW, int k, int32_t* tok, float* logprob, void* ws, const int32_t* shortlist,
+                       size_t shortlist_len, hipStream_t s);
 // float glue of the averaging-attention decode step (mq_glue.hip).  `partial` (optional) receives one
 // max|output| per workgroup: running_average_partials(n) of them for the running average, M for the others.
 size_t running_average_partials(size_t n);

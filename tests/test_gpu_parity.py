@@ -837,3 +837,68 @@ def test_autotune_freezes_a_variant_and_results_stay_identical():
                                                                       dtype=torch.uint8, device=DEV),
                                     mq.mq_autotune_ws_bytes(16, 64, 96, 128))
     assert 1 <= best16 <= 5
+
+
+# ------------------------------------------------ beam-search output layer
+
+def gpu_topk(Hd, E, k, shortlist=None):
+    pw = mq.prepare_weight(dev(E), 8)
+    pa, s = gpu_quantize_pack(Hd, 8)
+    M, K = Hd.shape
+    N = E.shape[0]
+    sl = None if shortlist is None else dev(np.asarray(shortlist, dtype=np.int32))
+    nbytes = mq.mq_topk_ws_bytes(M, N, k)
+    ws = torch.full((nbytes,), 0xC3, dtype=torch.uint8, device=DEV)
+    tok = torch.full((M, k), -7, dtype=torch.int32, device=DEV)
+    lp = torch.empty((M, k), dtype=torch.float32, device=DEV)
+    mq.mq_gemm_topk_packed(pa, pw.packed, sl, 0 if sl is None else sl.numel(), M, N, K, s, pw.scale, k, tok, lp, ws,
+                           nbytes)
+    return host(tok), host(lp)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,V,d", [(1, 4, 1), (12, 777, 64), (33, 4100, 96), (300, 36000, 512), (130, 9000, 192),
+                                   (600, 5000, 128)])
+def test_beam_output_layer_topk(M, V, d, k):
+    # Table 2's b = 2 / b = 4 rows: the k best words per row, exact, with log-probabilities within 1e-4
+    # (binary32 logits of magnitude <= ~30 here; the normaliser sums V terms in binary32).  M = 600 goes
+    # through three chunks of rows.
+    c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + k)
+    o = oracle.topk_log_softmax(c["Hd"], c["E"], k)
+    tok, lp = gpu_topk(c["Hd"], c["E"], k)
+    assert np.array_equal(tok, o["tok"])
+    assert np.allclose(lp, o["logprob"], rtol=0, atol=1e-4)
+
+
+def test_beam_output_layer_ties_and_crowded_lanes():
+    # all k best words in one accumulator register's stream: duplicates of the winning embedding row placed
+    # one workgroup-stride (256 units of 16 words) apart land in the same register of the same lane
+    c = workloads.config3(M=20, V=36000, d=64, seed_extra=123)
+    E = c["E"].copy()
+    h = c["Hd"][0] / np.abs(c["Hd"][0]).max() * np.abs(E).max()     # aligned with sentence 0, inside the abs-max
+    for j in range(4):
+        E[5 + 4096 * j] = h * (1.0 - 0.01 * j)
+    E[5 + 4096 * 4] = h                                              # exact tie with the first, higher index
+    o = oracle.topk_log_softmax(c["Hd"], E, 4)
+    tok, lp = gpu_topk(c["Hd"], E, 4)
+    assert list(o["tok"][0][:2]) == [5, 5 + 4096 * 4]
+    assert np.array_equal(tok, o["tok"])
+    assert np.allclose(lp, o["logprob"], rtol=0, atol=1e-4)
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_beam_output_layer_with_shortlist(k):
+    c = workloads.config3(M=64, V=9000, d=128, seed_extra=77)
+    rng = np.random.default_rng(5)
+    sl = np.sort(rng.choice(9000, size=1234, replace=False)).astype(np.int32)
+    qE = c["E"][sl]
+    # the short list is scored with the whole embedding's multiplier: quantize the whole, then gather
+    full = oracle.greedy_output_layer(c["Hd"], c["E"])
+    acc = oracle.dot_int(full["qA"], np.ascontiguousarray(full["qW"][sl]))
+    y = oracle.dequant_bias(acc, full["sA"], full["sW"]).astype(np.float64)
+    lse = np.log(np.exp(y - y.max(1, keepdims=True)).sum(1, keepdims=True)) + y.max(1, keepdims=True)
+    order = np.argsort(-acc.astype(np.int64), axis=1, kind="stable")[:, :k]
+    tok, lp = gpu_topk(c["Hd"], c["E"], k, shortlist=sl)
+    assert np.array_equal(tok, sl[order])
+    assert np.allclose(lp, np.take_along_axis(y, order, axis=1) - lse, rtol=0, atol=1e-4)
+    del qE
