@@ -520,6 +520,8 @@ int launch_pp_variant(const GemmArgs& a, int variant, hipStream_t s) {
       case 5: return launch_pp<8, 128, 128, 2, 2, 8, EPI>(a, s);   // small tile, deep pipeline (6 stages in flight)
       case 6: return launch_pp<8, 256, 128, 4, 2, 6, EPI>(a, s);   // 8 waves, 64x64 per wave, deep pipeline
       case 7: return launch_pp<8, 128, 64, 2, 2, 8, EPI>(a, s);    // very small tile for narrow results
+      case 8: return launch_pp<8, 128, 128, 4, 2, 6, EPI>(a, s);   // small tile, 8 waves (32x64 each): more loads in flight
+      case 9: return launch_pp<8, 128, 128, 2, 4, 6, EPI>(a, s);   // small tile, 8 waves (64x32 each)
       default: return MQ_ERR_UNSUPPORTED;
     }
   } else {
@@ -547,7 +549,7 @@ int fused_variant(const GemmArgs& a) {
 size_t tiles_of(int variant, size_t M, size_t N) {
   size_t bm = 256, bn = 256;
   switch (variant) {
-    case 3: case 5: bm = 128; bn = 128; break;
+    case 3: case 5: case 8: case 9: bm = 128; bn = 128; break;
     case 4: case 6: bm = 256; bn = 128; break;
     case 7: bm = 128; bn = 64; break;
     default: break;
@@ -556,7 +558,7 @@ size_t tiles_of(int variant, size_t M, size_t N) {
 }
 }  // namespace
 
-int packed_variant_count(int bits) { return bits == 8 ? 7 : 5; }
+int packed_variant_count(int bits) { return bits == 8 ? 9 : 5; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }

@@ -435,7 +435,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7], 16: [0, 1, 2, 3, 4, 5]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9], 16: [0, 1, 2, 3, 4, 5]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
