@@ -54,6 +54,8 @@ def parse_args():
     ap.add_argument("--no-autotune", action="store_true", help="keep the shape heuristic instead of timing tile variants")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size reference for scaling HBM counters")
+    ap.add_argument("--no-parity", action="store_true",
+                    help="skip the per-config parity / overflow report of the CPU leg")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the workload the oracle is timed on")
     return ap.parse_args()
 
@@ -510,7 +512,80 @@ def main():
                                   "kind": "oracle", "seconds": round(dt, 2),
                                   "sample": f"first {rows} of {w2.M} token rows of the same FFN workload, "
                                             "weights pre-quantized (memoized)"}
+        if not args.no_parity:
+            result["cpu_baseline"]["parity"] = parity_report(mq, torch, dev, to_dev, oracle)
     print(json.dumps(result))
+
+
+def parity_report(mq, torch, dev, to_dev, oracle):
+    """Per benchmark config: does the GPU path reproduce the oracle (quantized tensors, 32-bit sums, float outputs,
+    tokens), how many 32-bit sums wrapped, which seed.  Part of the CPU leg: the oracle recomputes everything."""
+    import numpy as np
+    import workloads
+    QT = {8: torch.int8, 16: torch.int16}
+    qws = torch.empty(mq.mq_quantize_absmax_ws_bytes(), dtype=torch.uint8, device=dev)
+
+    def gpu_product(A, Wt, bias, bits, relu):
+        M, K = A.shape
+        N = Wt.shape[0]
+        pw = mq.prepare_weight(to_dev(Wt), bits)
+        qa = torch.empty(mq.mq_packed_bytes(bits, M, K), dtype=torch.uint8, device=dev)
+        sa = torch.empty(1, dtype=torch.float32, device=dev)
+        mq.mq_quantize_absmax_pack_f32(to_dev(A), M, K, bits, qa, sa, qws, qws.numel())
+        q = torch.empty((M, K), dtype=QT[bits], device=dev)
+        mq.mq_unpack_weight(qa, bits, M, K, q)
+        C = torch.empty((M, N), dtype=torch.int32, device=dev)
+        mq.mq_gemm_i32_packed(qa, pw.packed, bits, M, N, K, C)
+        Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        mq.mq_gemm_dequant_packed(qa, pw.packed, bits, M, N, K, sa, pw.scale, None if bias is None else to_dev(bias),
+                                  relu, Y, None)
+        return q.cpu().numpy(), C.cpu().numpy(), Y.cpu().numpy()
+
+    def check_product(A, Wt, bias, bits, relu):
+        o = oracle.linear(A, Wt, bits, bias, relu)
+        q, C, Y = gpu_product(A, Wt, bias, bits, relu)
+        return ({"quantized": bool(np.array_equal(q, o["qA"])), "acc": bool(np.array_equal(C, o["acc"])),
+                 "out": bool(np.array_equal(Y, o["Y"])), "overflow_count": int(o["overflow_count"]),
+                 "overflow_fraction": round(o["overflow_count"] / o["acc"].size, 4)}, o["Y"])
+
+    def merge(parts):
+        out = {k: all(p_[k] for p_ in parts) for k in ("quantized", "acc", "out")}
+        out["overflow_count"] = [p_["overflow_count"] for p_ in parts]
+        out["overflow_fraction"] = [p_["overflow_fraction"] for p_ in parts]
+        return out
+
+    report = {}
+    c = workloads.config1()
+    r, _ = check_product(c["A"], c["Wt"], c["bias"], 16, False)
+    report["config1"] = dict(r, seed=workloads.BASE_SEED + 1)
+    for name, cfg, bits in (("config2", workloads.config2(), 8), ("config4", workloads.config4(), 16)):
+        r1, H = check_product(cfg["A"], cfg["W1t"], cfg["b1"], bits, True)
+        r2, _ = check_product(H, cfg["W2t"], cfg["b2"], bits, False)
+        report[name] = dict(merge([r1, r2]), seed=workloads.BASE_SEED + int(name[-1]))
+    c = workloads.config3()
+    o = oracle.greedy_output_layer(c["Hd"], c["E"])
+    M, d = c["Hd"].shape
+    V = c["E"].shape[0]
+    pe = mq.prepare_weight(to_dev(c["E"]), 8)
+    qa = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
+    sa = torch.empty(1, dtype=torch.float32, device=dev)
+    mq.mq_quantize_absmax_pack_f32(to_dev(c["Hd"]), M, d, 8, qa, sa, qws, qws.numel())
+    nws = mq.mq_argmax_ws_bytes(M, V)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    tok = torch.empty(M, dtype=torch.int32, device=dev)
+    val = torch.empty(M, dtype=torch.float32, device=dev)
+    mq.mq_gemm_argmax_packed(qa, pe.packed, M, V, d, sa, pe.scale, tok, val, ws, nws)
+    C = torch.empty((M, V), dtype=torch.int32, device=dev)
+    mq.mq_gemm_i32_packed(qa, pe.packed, 8, M, V, d, C)
+    report["config3"] = {"acc": bool(np.array_equal(C.cpu().numpy(), o["acc"])),
+                         "tokens": bool(np.array_equal(tok.cpu().numpy(), o["tok"])),
+                         "out": bool(np.array_equal(val.cpu().numpy(), o["maxlogit"])), "overflow_count": 0,
+                         "seed": workloads.BASE_SEED + 3}
+    c5 = workloads.config5()
+    parts = [check_product(g["A"], g["Wt"], g["bias"], 8, bool(g["relu"]))[0] for g in c5["gemms"][:7]]
+    report["config5"] = dict(merge(parts), what="the seven products of layer 0 (the other layers repeat their shapes)",
+                             seed=workloads.BASE_SEED + 5)
+    return report
 
 
 if __name__ == "__main__":
