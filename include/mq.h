@@ -269,9 +269,10 @@ int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size
 /* The same with the hidden states packed by mq_quantize_pack_f32 (8 bit): the
  * decode-step kernel.  The hidden states sit in registers, the embedding
  * streams through LDS exactly once, each block reports one candidate per
- * sentence and a second small kernel picks the winners.  Serves M <= 384 and
- * K <= 512 (MQ_ERR_UNSUPPORTED beyond; use mq_gemm_argmax there).  Same results,
- * same workspace query. */
+ * sentence and a second small kernel picks the winners.  Rows are processed
+ * 384 at a time (the embedding streams once per pass).  Serves K <= 512
+ * (MQ_ERR_UNSUPPORTED beyond; use mq_gemm_argmax there).  Same results, same
+ * workspace query. */
 int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
                           const float* sA, const float* sW, int32_t* tok, float* maxlogit,
                           void* ws, size_t ws_bytes, void* stream);

@@ -242,9 +242,6 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 #endif
     // everybody is past stage s - 1 (and has its copy of stage s in registers), so slot s - 1 can be refilled
     if (s + S - 1 < nlocal) issue(s + S - 1);
-#ifdef MQ_DBG_NOCOMPUTE
-    return;
-#endif
     // the next unit's LDS reads are spread between the MFMA groups: eight reads in a row would fill the
     // LDS queue (all eight waves read at the same time) and hold this wave's MFMAs back behind them
     const bool more = s + 1 < nlocal;
@@ -546,24 +543,17 @@ int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
 
 size_t argmax_stream_ws_bytes(size_t M) { return (size_t)kMaxBlocks * M * sizeof(unsigned long long); }
 
-// Limits: 3 tiles of 16 sentences per wave; sums must fit 24 bits (127^2 K < 2^23); at most 255 stages per workgroup.
+// Limits: sums must fit 24 bits (127^2 K < 2^23); at most 255 stages per workgroup.  Any number of rows: 384 per pass.
 bool argmax_stream_supported(size_t M, size_t N, size_t K) {
-  return M <= (size_t)kWaves * 3 * 16 && K <= 64 * kKG && N <= (size_t)255 * 256 * 16;
+  (void)M;
+  return K <= 64 * kKG && N <= (size_t)255 * 256 * 16;
 }
 
 int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
                          const float* sW, int32_t* tok, float* maxlogit, void* ws, const int32_t* shortlist,
                          size_t shortlist_len, hipStream_t s) {
   if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
-  ArgmaxParams p;
-  p.packedA = static_cast<const uint8_t*>(packedA);
-  p.packedW = static_cast<const uint8_t*>(packedW);
-  p.M = (unsigned)M; p.N = (unsigned)N; p.K = (unsigned)K;
-  p.partial = static_cast<unsigned long long*>(ws);
-  p.shortlist = shortlist;
-  p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
-  p.norm = nullptr; p.sA = sA; p.sW = sW;
-  const PackedDims dW(8, N, K);
+  const PackedDims dW(8, N, K), dAll(8, M, K);
   static int cus = 0;               // compute units of the device, asked once
   if (cus == 0) {
     int dev = 0, v = 0;
@@ -576,26 +566,41 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
   unsigned grid = (unsigned)(units < (size_t)cus ? units : (size_t)cus);
   if (grid > (unsigned)kMaxBlocks) grid = kMaxBlocks;
   if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
-  const size_t tiles = (M + 15) / 16;
-  const int tpw = (int)((tiles + kWaves - 1) / kWaves);
-  int rc;
-  if (shortlist != nullptr) {
-    switch (tpw) {
-      case 1: rc = launch_stream<1, true>(p, grid, s); break;
-      case 2: rc = launch_stream<2, true>(p, grid, s); break;
-      default: rc = launch_stream<3, true>(p, grid, s); break;
+  // rows beyond what one workgroup's registers hold (3 tiles of 16 sentences per wave) go in further passes
+  constexpr size_t kChunk = (size_t)kWaves * 3 * 16;
+  for (size_t row0 = 0; row0 < M; row0 += kChunk) {
+    const size_t rows = M - row0 < kChunk ? M - row0 : kChunk;
+    ArgmaxParams p;
+    p.packedA = static_cast<const uint8_t*>(packedA) + dAll.frag_offset(row0 / 32, 0);
+    p.packedW = static_cast<const uint8_t*>(packedW);
+    p.M = (unsigned)rows; p.N = (unsigned)N; p.K = (unsigned)K;
+    p.partial = static_cast<unsigned long long*>(ws);
+    p.shortlist = shortlist;
+    p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
+    p.norm = nullptr; p.sA = sA; p.sW = sW;
+    const size_t tiles = (rows + 15) / 16;
+    const int tpw = (int)((tiles + kWaves - 1) / kWaves);
+    int rc;
+    if (shortlist != nullptr) {
+      switch (tpw) {
+        case 1: rc = launch_stream<1, true>(p, grid, s); break;
+        case 2: rc = launch_stream<2, true>(p, grid, s); break;
+        default: rc = launch_stream<3, true>(p, grid, s); break;
+      }
+    } else {
+      switch (tpw) {
+        case 1: rc = launch_stream<1, false>(p, grid, s); break;
+        case 2: rc = launch_stream<2, false>(p, grid, s); break;
+        default: rc = launch_stream<3, false>(p, grid, s); break;
+      }
     }
-  } else {
-    switch (tpw) {
-      case 1: rc = launch_stream<1, false>(p, grid, s); break;
-      case 2: rc = launch_stream<2, false>(p, grid, s); break;
-      default: rc = launch_stream<3, false>(p, grid, s); break;
-    }
+    if (rc != MQ_OK) return rc;
+    hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, p.partial, grid,
+                       (unsigned)rows, sA, sW, tok + row0, maxlogit + row0, shortlist);
+    rc = check_hip(hipGetLastError());
+    if (rc != MQ_OK) return rc;
   }
-  if (rc != MQ_OK) return rc;
-  hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, p.partial, grid, (unsigned)M,
-                     sA, sW, tok, maxlogit, shortlist);
-  return check_hip(hipGetLastError());
+  return MQ_OK;
 }
 
 size_t topk_stream_ws_bytes(size_t M, int k) {

@@ -528,20 +528,30 @@ def test_greedy_packed_ties_padding_and_limits():
     tok, val = gpu_greedy_packed(Hneg, Eneg)
     assert np.array_equal(tok, o["tok"]) and np.array_equal(val, o["maxlogit"])
     # beyond the kernel's limits the call refuses instead of computing something else
-    pw = mq.prepare_weight(dev(E[:64]), 8)
-    big = np.zeros((385, 128), dtype=np.float32)
-    pa, s = gpu_quantize_pack(big, 8)
-    nbytes = mq.mq_argmax_ws_bytes(385, 64)
+    # (K = 576 > 512: the 32-bit keys of the streaming kernel could no longer hold the sums)
+    wide = np.zeros((64, 576), dtype=np.float32)
+    pw = mq.prepare_weight(dev(wide), 8)
+    pa, s = gpu_quantize_pack(np.zeros((5, 576), dtype=np.float32), 8)
+    nbytes = mq.mq_argmax_ws_bytes(5, 64)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-    tok_t = torch.empty(385, dtype=torch.int32, device=DEV)
-    val_t = torch.empty(385, dtype=torch.float32, device=DEV)
+    tok_t = torch.empty(5, dtype=torch.int32, device=DEV)
+    val_t = torch.empty(5, dtype=torch.float32, device=DEV)
     with pytest.raises(mq.MqError) as e:
-        mq.mq_gemm_argmax_packed(pa, pw.packed, 385, 64, 128, s, pw.scale, tok_t, val_t, ws, nbytes)
+        mq.mq_gemm_argmax_packed(pa, pw.packed, 5, 64, 576, s, pw.scale, tok_t, val_t, ws, nbytes)
     assert e.value.status == 6
 
 
 def test_config3_output_layer_full_packed():
     c = workloads.config3()
+    o = oracle.greedy_output_layer(c["Hd"], c["E"])
+    tok, val = gpu_greedy_packed(c["Hd"], c["E"])
+    assert np.array_equal(tok, o["tok"])
+    assert np.array_equal(val, o["maxlogit"])
+
+
+def test_greedy_packed_more_rows_than_one_pass_holds():
+    # 1000 rows: three passes of 384 rows each stream the embedding
+    c = workloads.config3(M=1000, V=5000, d=128, seed_extra=11)
     o = oracle.greedy_output_layer(c["Hd"], c["E"])
     tok, val = gpu_greedy_packed(c["Hd"], c["E"])
     assert np.array_equal(tok, o["tok"])
@@ -827,7 +837,7 @@ def test_autotune_freezes_a_variant_and_results_stay_identical():
     nbytes = mq.mq_autotune_ws_bytes(8, M, N, K)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     best, us = mq.mq_autotune_gemm(8, M, N, K, 20, ws, nbytes)
-    assert 1 <= best <= 7 and us > 0
+    assert 1 <= best <= 9 and us > 0
     pw = mq.prepare_weight(dev(p["Wt"]), 8)
     pa, s = gpu_quantize_pack(p["A"], 8)
     Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
