@@ -121,31 +121,51 @@ __global__ __launch_bounds__(kT) void k_layer_norm(const float* __restrict__ a, 
 }
 
 // One workgroup per sentence.  Scores of all heads and source positions into LDS (one wave per (head,
-// position) pair at a time, lanes over the head's width), softmax per head, then the context: thread j
-// of the model width sums p[s] V[s][j] over the source positions.
-__global__ __launch_bounds__(kT) void k_cross_attention(const float* __restrict__ q, const float* __restrict__ K,
-                                                        const float* __restrict__ V, unsigned S, unsigned d,
-                                                        unsigned heads, float* __restrict__ ctx,
-                                                        float* __restrict__ partial) {
+// position) pair, lanes over the head's width, four pairs per trip so that four rows of K are in flight
+// per wave instead of one: the loop is bound by memory latency, not by arithmetic), softmax per head, then
+// the context: thread j of the model width sums p[s] V[s][j] over the source positions.
+constexpr int kTA = 512;             // threads of the attention kernel
+
+__global__ __launch_bounds__(kTA) void k_cross_attention(const float* __restrict__ q, const float* __restrict__ K,
+                                                         const float* __restrict__ V, unsigned S, unsigned d,
+                                                         unsigned heads, float* __restrict__ ctx,
+                                                         float* __restrict__ partial) {
   __shared__ float sc[kMaxScores];
-  __shared__ float red[kT / kWave];
+  __shared__ float red[kTA / kWave];
+  constexpr unsigned NWV = kTA / kWave;
   const size_t m = blockIdx.x;
   const unsigned dh = d / heads;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const unsigned lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const float scale = __fdiv_rn(1.0f, sqrtf((float)dh));
   const float* qm = q + m * d;
   const float* Km = K + m * S * d;
   const float* Vm = V + m * S * d;
-  for (unsigned p = wave; p < heads * S; p += kT / kWave) {
-    const unsigned h = p / S, s = p % S;
-    float acc = 0.f;
-    for (unsigned j = lane; j < dh; j += kWave) acc = fmaf(qm[h * dh + j], Km[s * d + h * dh + j], acc);
-    acc = wave_sum_f(acc);
-    if (lane == 0) sc[p] = acc * scale;
+  const unsigned pairs = heads * S;
+  for (unsigned p0 = wave; p0 < pairs; p0 += 4 * NWV) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (unsigned j = lane; j < dh; j += kWave) {
+      float kv[4], qv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned p = p0 + u * NWV;
+        const unsigned pc = p < pairs ? p : p0;                 // past the end: a valid pair again, result unused
+        const unsigned h = pc / S, s = pc % S;
+        kv[u] = Km[(size_t)s * d + h * dh + j];
+        qv[u] = qm[h * dh + j];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[u] = fmaf(qv[u], kv[u], acc[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float t = wave_sum_f(acc[u]);
+      const unsigned p = p0 + u * NWV;
+      if (lane == 0 && p < pairs) sc[p] = t * scale;
+    }
   }
   __syncthreads();
   // softmax over the S positions of each head: one wave per head at a time
-  for (unsigned h = wave; h < heads; h += kT / kWave) {
+  for (unsigned h = wave; h < heads; h += NWV) {
     float mx = -INFINITY;
     for (unsigned s = lane; s < S; s += kWave) mx = fmaxf(mx, sc[h * S + s]);
 #pragma unroll
@@ -162,14 +182,151 @@ __global__ __launch_bounds__(kT) void k_cross_attention(const float* __restrict_
   }
   __syncthreads();
   float mx = 0.f;
-  for (unsigned j = threadIdx.x; j < d; j += kT) {
+  for (unsigned j = threadIdx.x; j < d; j += kTA) {
     const unsigned h = j / dh;
     float acc = 0.f;
-    for (unsigned s = 0; s < S; ++s) acc = fmaf(sc[h * S + s], Vm[s * d + j], acc);
+    unsigned s = 0;
+    for (; s + 4 <= S; s += 4) {                                   // four rows of V in flight
+      const float v0 = Vm[(size_t)s * d + j], v1 = Vm[(size_t)(s + 1) * d + j], v2 = Vm[(size_t)(s + 2) * d + j],
+                  v3 = Vm[(size_t)(s + 3) * d + j];
+      acc = fmaf(sc[h * S + s], v0, acc);
+      acc = fmaf(sc[h * S + s + 1], v1, acc);
+      acc = fmaf(sc[h * S + s + 2], v2, acc);
+      acc = fmaf(sc[h * S + s + 3], v3, acc);
+    }
+    for (; s < S; ++s) acc = fmaf(sc[h * S + s], Vm[(size_t)s * d + j], acc);
     ctx[m * d + j] = acc;
     mx = fmaxf(mx, fabsf(acc));
   }
-  if (partial != nullptr) block_absmax_out(mx, red, partial);
+  if (partial != nullptr) {
+    // (the helper is written for kT threads; here the workgroup is kTA wide)
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    __syncthreads();
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float r = red[0];
+#pragma unroll
+      for (unsigned k = 1; k < NWV; ++k) r = fmaxf(r, red[k]);
+      partial[blockIdx.x] = r;
+    }
+  }
+}
+
+// The same for the usual shapes (model width a multiple of 256, head width a power of two between 4 and 256):
+// every load is a float4, a wave reads whole 1 KB pieces of a K row and all heads' partial dot products of one
+// source position come out of one pass; the context phase splits the source positions over thread groups so
+// that every thread has several rows of V in flight.
+template <int CH>      // CH = d / 256: float4 pieces of a row per lane
+__global__ __launch_bounds__(kTA) void k_cross_attention_fast(const float* __restrict__ q, const float* __restrict__ K,
+                                                              const float* __restrict__ V, unsigned S, unsigned heads,
+                                                              float* __restrict__ ctx, float* __restrict__ partial) {
+  constexpr unsigned d = 256u * CH;
+  constexpr unsigned NWV = kTA / kWave;
+  constexpr unsigned COLS = d / 4;                 // float4 columns of a row
+  constexpr unsigned SG = kTA / COLS;              // groups of threads that share the source positions
+  static_assert(kTA % COLS == 0 && SG >= 1, "context phase layout");
+  __shared__ float sc[kMaxScores];
+  __shared__ float4 part[SG > 1 ? kTA : 1];
+  __shared__ float red[NWV];
+  const size_t m = blockIdx.x;
+  const unsigned dh = d / heads, grp = dh / 4;     // lanes per head inside a 256-float piece
+  const unsigned lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const float scale = __fdiv_rn(1.0f, sqrtf((float)dh));
+  const float4* q4 = reinterpret_cast<const float4*>(q + m * d);
+  const float4* K4 = reinterpret_cast<const float4*>(K + m * S * d);
+  const float4* V4 = reinterpret_cast<const float4*>(V + m * S * d);
+  float4 qr[CH];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) qr[c] = q4[c * 64 + lane];
+  for (unsigned s0 = wave; s0 < S; s0 += 4 * NWV) {
+    float4 kr[4][CH];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned s = s0 + u * NWV < S ? s0 + u * NWV : s0;       // past the end: a valid row again, result unused
+#pragma unroll
+      for (int c = 0; c < CH; ++c) kr[u][c] = K4[(size_t)s * COLS + c * 64 + lane];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned s = s0 + u * NWV;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        float a = fmaf(qr[c].x, kr[u][c].x, fmaf(qr[c].y, kr[u][c].y, fmaf(qr[c].z, kr[u][c].z, qr[c].w * kr[u][c].w)));
+        for (unsigned off = grp / 2; off >= 1; off >>= 1) a += __shfl_xor(a, off, kWave);
+        const unsigned h = (c * 256 + 4 * lane) / dh;
+        if (s < S && lane % grp == 0) sc[h * S + s] = a * scale;
+      }
+    }
+  }
+  __syncthreads();
+  for (unsigned h = wave; h < heads; h += NWV) {
+    float mx = -INFINITY;
+    for (unsigned s = lane; s < S; s += kWave) mx = fmaxf(mx, sc[h * S + s]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    float sum = 0.f;
+    for (unsigned s = lane; s < S; s += kWave) {
+      const float e = expf(sc[h * S + s] - mx);
+      sc[h * S + s] = e;
+      sum += e;
+    }
+    sum = wave_sum_f(sum);
+    const float inv = __fdiv_rn(1.0f, sum);
+    for (unsigned s = lane; s < S; s += kWave) sc[h * S + s] *= inv;
+  }
+  __syncthreads();
+  const unsigned col = threadIdx.x % COLS, sg = threadIdx.x / COLS;
+  const unsigned h = (4 * col) / dh;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  unsigned s = sg;
+  for (; s + 3 * SG < S; s += 4 * SG) {
+    const float4 v0 = V4[(size_t)s * COLS + col], v1 = V4[(size_t)(s + SG) * COLS + col],
+                 v2 = V4[(size_t)(s + 2 * SG) * COLS + col], v3 = V4[(size_t)(s + 3 * SG) * COLS + col];
+    const float p0 = sc[h * S + s], p1 = sc[h * S + s + SG], p2 = sc[h * S + s + 2 * SG], p3 = sc[h * S + s + 3 * SG];
+    acc.x = fmaf(p3, v3.x, fmaf(p2, v2.x, fmaf(p1, v1.x, fmaf(p0, v0.x, acc.x))));
+    acc.y = fmaf(p3, v3.y, fmaf(p2, v2.y, fmaf(p1, v1.y, fmaf(p0, v0.y, acc.y))));
+    acc.z = fmaf(p3, v3.z, fmaf(p2, v2.z, fmaf(p1, v1.z, fmaf(p0, v0.z, acc.z))));
+    acc.w = fmaf(p3, v3.w, fmaf(p2, v2.w, fmaf(p1, v1.w, fmaf(p0, v0.w, acc.w))));
+  }
+  for (; s < S; s += SG) {
+    const float4 v0 = V4[(size_t)s * COLS + col];
+    const float p0 = sc[h * S + s];
+    acc.x = fmaf(p0, v0.x, acc.x);
+    acc.y = fmaf(p0, v0.y, acc.y);
+    acc.z = fmaf(p0, v0.z, acc.z);
+    acc.w = fmaf(p0, v0.w, acc.w);
+  }
+  float mx = 0.f;
+  if constexpr (SG > 1) {
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (sg == 0) {
+#pragma unroll
+      for (unsigned g = 1; g < SG; ++g) {
+        const float4 o = part[g * COLS + col];
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+      }
+    }
+  }
+  if (sg == 0) {
+    reinterpret_cast<float4*>(ctx + m * d)[col] = acc;
+    mx = fmaxf(fmaxf(fabsf(acc.x), fabsf(acc.y)), fmaxf(fabsf(acc.z), fabsf(acc.w)));
+  }
+  if (partial != nullptr) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    __syncthreads();
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float r = red[0];
+#pragma unroll
+      for (unsigned k = 1; k < NWV; ++k) r = fmaxf(r, red[k]);
+      partial[blockIdx.x] = r;
+    }
+  }
 }
 
 }  // namespace
@@ -211,7 +368,23 @@ int launch_gate_mix_layer_norm(const float* x, const float* f, const float* z, c
 int launch_cross_attention(const float* q, const float* K, const float* V, size_t M, size_t S, size_t d, int heads,
                            float* ctx, hipStream_t s, float* partial) {
   if ((size_t)heads * S > (size_t)kMaxScores) return MQ_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(k_cross_attention, dim3((unsigned)M), dim3(kT), 0, s, q, K, V, (unsigned)S, (unsigned)d,
+  const size_t dh = d / (size_t)heads;
+  const bool pow2 = (dh & (dh - 1)) == 0;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+                       reinterpret_cast<uintptr_t>(ctx)) % 16 == 0;
+  if (vec_ok && pow2 && dh >= 4 && dh <= 256 && (d == 256 || d == 512 || d == 1024)) {
+    if (d == 256)
+      hipLaunchKernelGGL((k_cross_attention_fast<1>), dim3((unsigned)M), dim3(kTA), 0, s, q, K, V, (unsigned)S,
+                         (unsigned)heads, ctx, partial);
+    else if (d == 512)
+      hipLaunchKernelGGL((k_cross_attention_fast<2>), dim3((unsigned)M), dim3(kTA), 0, s, q, K, V, (unsigned)S,
+                         (unsigned)heads, ctx, partial);
+    else
+      hipLaunchKernelGGL((k_cross_attention_fast<4>), dim3((unsigned)M), dim3(kTA), 0, s, q, K, V, (unsigned)S,
+                         (unsigned)heads, ctx, partial);
+    return check_hip(hipGetLastError());
+  }
+  hipLaunchKernelGGL(k_cross_attention, dim3((unsigned)M), dim3(kTA), 0, s, q, K, V, (unsigned)S, (unsigned)d,
                      (unsigned)heads, ctx, partial);
   return check_hip(hipGetLastError());
 }

@@ -76,7 +76,8 @@ def test_gate_mix_layer_norm(M, d):
     assert close(host(y), glue.add_layer_norm(glue.gate_mix(x, f, z), x, gamma, beta, 1e-6))
 
 
-@pytest.mark.parametrize("M,S,d,heads", [(1, 1, 8, 1), (7, 5, 48, 3), (300, 25, 512, 8), (9, 130, 256, 4)])
+@pytest.mark.parametrize("M,S,d,heads", [(1, 1, 8, 1), (7, 5, 48, 3), (300, 25, 512, 8), (9, 130, 256, 4),
+                                          (5, 7, 1024, 16), (6, 9, 512, 4), (4, 3, 256, 64), (3, 6, 512, 2)])
 def test_cross_attention(M, S, d, heads):
     rng = np.random.default_rng(M + S + d)
     q = rng.standard_normal((M, d), dtype=np.float32) * np.float32(2)
