@@ -118,6 +118,8 @@ def main():
         that host launch overhead does not hide kernels of a few microseconds."""
         return time_events(graphed(fn, reps), iters, 3) / reps
 
+    QWS = mq.mq_quantize_absmax_ws_bytes()     # workspace of the abs-max + quant_int call
+
     # ------------------------------------------------------------ FFN workloads
     class FFN:
         def __init__(self, c, bits):
@@ -139,7 +141,7 @@ def main():
             self.Y = torch.empty((M, d), dtype=torch.float32, device=dev)
             self.ops = 2 * (2 * M * d * f)
             self.ws_bytes = mq.mq_ffn_ws_bytes(M, d, f) if bits == 8 else mq.mq_ffn_i16_ws_bytes(M, d, f)
-            self.ws = torch.empty(max(self.ws_bytes, 4096), dtype=torch.uint8, device=dev)
+            self.ws = torch.empty(max(self.ws_bytes, QWS), dtype=torch.uint8, device=dev)
             self.part_bytes = mq.mq_gemm_amax_ws_bytes(M, f)
             self.part = torch.empty(self.part_bytes, dtype=torch.uint8, device=dev)
 
@@ -187,7 +189,7 @@ def main():
 
         # building blocks of the fused step, for per-kernel timing
         def k_absmax_quant1(self):
-            mq.mq_quantize_absmax_pack_f32(self.A, self.M, self.d, self.bits, self.q1, self.s1, self.ws, 4096)
+            mq.mq_quantize_absmax_pack_f32(self.A, self.M, self.d, self.bits, self.q1, self.s1, self.ws, QWS)
 
         def k_gemm1_amax(self):
             mq.mq_gemm_amax_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1, self.p1.scale,
@@ -325,10 +327,10 @@ def main():
         val = torch.empty(M, dtype=torch.float32, device=dev)
 
         qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
-        qws = torch.empty(4096, dtype=torch.uint8, device=dev)
+        qws = torch.empty(QWS, dtype=torch.uint8, device=dev)
 
         def out_step():
-            mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, 4096)
+            mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, QWS)
             mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
 
         out_step()
@@ -344,7 +346,7 @@ def main():
 
         def cold_round():
             for q_ in pes:
-                mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, 4096)
+                mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, QWS)
                 mq.mq_gemm_argmax_packed(qp, q_.packed, M, V, d, s, q_.scale, tok, val, ws, nws)
 
         us3c = time_events(graphed(cold_round), max(5, args.steps // 10), 2) / len(pes)
@@ -373,7 +375,7 @@ def main():
             Hb = torch.randn(rows_b, d, device=dev)
             qb = torch.empty(mq.mq_packed_bytes(8, rows_b, d), dtype=torch.uint8, device=dev)
             sb = torch.empty(1, dtype=torch.float32, device=dev)
-            mq.mq_quantize_absmax_pack_f32(Hb, rows_b, d, 8, qb, sb, qws, 4096)
+            mq.mq_quantize_absmax_pack_f32(Hb, rows_b, d, 8, qb, sb, qws, QWS)
             nwb = mq.mq_topk_ws_bytes(rows_b, V, beam)
             wsb = torch.empty(nwb, dtype=torch.uint8, device=dev)
             tokb = torch.empty((rows_b, beam), dtype=torch.int32, device=dev)
@@ -425,7 +427,7 @@ def main():
         Y1_ = torch.empty((384, 512), dtype=torch.float32, device=dev)
 
         def c1_step():
-            mq.mq_quantize_absmax_pack_f32(A1, 384, 512, 16, q1_, s1_, qws, 4096)
+            mq.mq_quantize_absmax_pack_f32(A1, 384, 512, 16, q1_, s1_, qws, QWS)
             mq.mq_gemm_dequant_packed(q1_, p1_.packed, 16, 384, 512, 512, s1_, p1_.scale, b1_, False, Y1_, None)
 
         c1_step()
@@ -448,9 +450,9 @@ def main():
 
         def c5_step():
             for Ad, pw_, b_, relu_, N5, K5, qbuf, sbuf, Ybuf in g5:
-                mq.mq_quantize_absmax_pack_f32(Ad, 300, K5, 8, qbuf, sbuf, qws, 4096)
+                mq.mq_quantize_absmax_pack_f32(Ad, 300, K5, 8, qbuf, sbuf, qws, QWS)
                 mq.mq_gemm_dequant_packed(qbuf, pw_.packed, 8, 300, N5, K5, sbuf, pw_.scale, b_, relu_, Ybuf, None)
-            mq.mq_quantize_absmax_pack_f32(Hd5, M, d, 8, qp, s, qws, 4096)
+            mq.mq_quantize_absmax_pack_f32(Hd5, M, d, 8, qp, s, qws, QWS)
             mq.mq_gemm_argmax_packed(qp, pe5.packed, M, V, d, s, pe5.scale, tok, val, ws, nws)
 
         c5_step()
@@ -484,7 +486,7 @@ def main():
             for l_, layer_ in enumerate(Lc):
                 mq.mq_aan_layer_f32(layer_, xs[l_], gpc[l_], cc["t"], KVc[l_][0], KVc[l_][1], 300, 25, cc["heads"], True,
                                     True, 1e-6, xs[l_ + 1], gnc[l_], wsl, nwl)
-            mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, 4096)
+            mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, QWS)
             mq.mq_gemm_argmax_packed(qp, pec.packed, M, V, d, s, pec.scale, tok, val, ws, nws)
 
         chained_step()

@@ -144,9 +144,9 @@ int mq_set_quantize_single_pass(int enable) {
   return MQ_OK;
 }
 
-size_t mq_quantize_absmax_ws_bytes(void) {
-  static_assert(kAbsmaxPartials * sizeof(float) >= kBarrierWords * sizeof(unsigned), "one workspace serves both forms");
-  return kAbsmaxPartials * sizeof(float);
+size_t mq_quantize_absmax_ws_bytes(void) {      // one workspace serves both forms
+  const size_t partials = kAbsmaxPartials * sizeof(float), barrier = round_up(kBarrierWords * sizeof(unsigned), 256);
+  return partials > barrier ? partials : barrier;
 }
 
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,

@@ -6,7 +6,7 @@
 // of its share, waits until all shares are known, and converts from registers.
 //
 // Protocol.  `barrier` points to kBarrierWords words that are zero when the kernel starts.  Workgroup b
-// stores the bit pattern of its (non-negative, non-NaN) maximum, plus one, in word b; bit patterns of
+// stores the bit pattern of its (non-negative, non-NaN) maximum, plus one, in word b (of every copy of the slot array); bit patterns of
 // such floats order like unsigned integers.  Then it reads all words until none is zero: the read that
 // ends the wait also delivers every maximum.  Only device-scope stores and loads touch these words: no
 // counter, no read-modify-write on a shared address, no cache write-back or invalidation.  The wait
@@ -27,7 +27,11 @@
 namespace mq {
 
 constexpr unsigned kBarrierSlots = 256;
-static_assert(kBarrierSlots % 64 == 0 && kBarrierSlots + 1 <= kBarrierWords, "barrier layout");
+// Every workgroup's value is stored in kBarrierCopies copies of the slot array and a workgroup polls only copy
+// blockIdx.x % kBarrierCopies: loads of one cache line from the whole chip are served one after the other
+// (about 12 ns each), so 256 pollers on one copy would take 3 us per round, 32 take 0.4 us.
+constexpr unsigned kBarrierCopies = 8;
+static_assert(kBarrierSlots % 64 == 0 && kBarrierCopies * kBarrierSlots + 1 <= kBarrierWords, "barrier layout");
 
 // Maximum of an unsigned value over the 64 lanes, the same in every lane: inside rows of 16 lanes by
 // data-parallel-primitive moves (swap neighbours, swap pairs, mirror the half rows, mirror the rows),
@@ -44,7 +48,10 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
 
 // One thread of the workgroup publishes the workgroup's maximum m (m >= 0, not NaN).
 __device__ __forceinline__ void grid_max_publish(unsigned* barrier, float m) {
-  __hip_atomic_store(barrier + blockIdx.x, __float_as_uint(m) + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+  for (unsigned c = 0; c < kBarrierCopies; ++c)
+    __hip_atomic_store(barrier + c * kBarrierSlots + blockIdx.x, __float_as_uint(m) + 1u, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Called by all 64 lanes of ONE wave of the workgroup after grid_max_publish: waits for every workgroup's
@@ -53,6 +60,7 @@ __device__ __forceinline__ void grid_max_publish(unsigned* barrier, float m) {
 __device__ __forceinline__ float grid_max_collect(unsigned* barrier, unsigned long long ticks) {
   const int lane = threadIdx.x % 64;
   const unsigned total = gridDim.x;
+  const unsigned* mine = barrier + (blockIdx.x % kBarrierCopies) * kBarrierSlots;
   const unsigned long long t0 = wall_clock64();       // the same value in every lane
   unsigned best;
   bool gave_up = false;
@@ -62,14 +70,14 @@ __device__ __forceinline__ float grid_max_collect(unsigned* barrier, unsigned lo
 #pragma unroll
     for (unsigned k = 0; k < kBarrierSlots / 64; ++k) {
       const unsigned i = lane + 64 * k;
-      const unsigned v = i < total ? __hip_atomic_load(barrier + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+      const unsigned v = i < total ? __hip_atomic_load(mine + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
       all = all && v != 0u;
       best = max(best, v);
     }
     if (__all(all)) break;
     if (gave_up) break;                                // that was the one read after giving up
     if (wall_clock64() - t0 >= ticks) {
-      if (lane == 0) (void)atomicOr(barrier + kBarrierSlots, 1u);
+      if (lane == 0) (void)atomicOr(barrier + kBarrierCopies * kBarrierSlots, 1u);
       gave_up = true;
       __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the atomic is done before the next read is issued
       continue;
@@ -81,7 +89,7 @@ __device__ __forceinline__ float grid_max_collect(unsigned* barrier, unsigned lo
 
 // True if some workgroup of this launch gave up waiting (to be read after the caller's own collect).
 __device__ __forceinline__ bool grid_max_failed(unsigned* barrier) {
-  return __hip_atomic_load(barrier + kBarrierSlots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+  return __hip_atomic_load(barrier + kBarrierCopies * kBarrierSlots, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
 }
 
 }  // namespace mq

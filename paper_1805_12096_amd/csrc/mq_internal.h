@@ -104,9 +104,9 @@ int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int 
 size_t gemm_amax_partials(size_t M, size_t N);
 int launch_gemm_amax_partial(const GemmArgs& a, float* partials, hipStream_t s);
 int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, void* packed_out, hipStream_t s);
-// Words of the grid-wide barrier of the single-pass re-quantizing product: one slot per workgroup
+// Words of the grid-wide barrier of the single-pass kernels: eight copies of one slot per workgroup
 // (at most 256) and a sticky failure word, rounded up.
-constexpr unsigned kBarrierWords = 320;
+constexpr unsigned kBarrierWords = 8 * 256 + 64;
 unsigned long long barrier_timeout_ticks();
 void set_barrier_timeout_ticks(unsigned long long ticks);
 size_t topk_stream_ws_bytes(size_t M, int k);
