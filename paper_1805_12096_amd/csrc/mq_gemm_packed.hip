@@ -427,86 +427,46 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       __syncthreads();                             // every wave is done reading the last stage
       uint8_t* scratch = smem + wave * kFragBytes;
       const bool relu = p.relu != 0;
-      // FAST: after ReLU with the multiplier taken from a finite maximum every y s2 lies in [0, 127.0001] and is
-      // no NaN, so neither the clamp nor the NaN rule can act, and the conversion shrinks to one addition:
-      // t + 1.5 * 2^23 rounds t to the nearest integer (ties to even, the adder's own rounding) and leaves that
-      // integer in the low mantissa bits, whose low byte is the quantized value; four such bytes are gathered
-      // with byte permutes.
-      auto store_tiles = [&](auto interior_tag, auto fast_tag) {
+      auto store_tiles = [&](auto interior_tag) {
         constexpr bool INTERIOR = decltype(interior_tag)::value;
-        constexpr bool FAST = decltype(fast_tag)::value;
-        // every 32 x 32 sub-tile of the wave gets a 1 KB LDS area of its own when the stages leave room, so all
-        // words are written, then all fragments read back and stored, with one wait in between instead of two
-        // per sub-tile
-        constexpr bool WIDE = (size_t)NW * TM * TN * kFragBytes <= (size_t)S * STAGE;
-        uint8_t* area = WIDE ? smem + (size_t)wave * TM * TN * kFragBytes : scratch;
 #pragma unroll
         for (int nt = 0; nt < TN; ++nt) {
 #pragma unroll
           for (int mt = 0; mt < TM; ++mt) {
-            uint8_t* sub = WIDE ? area + (nt * TM + mt) * kFragBytes : area;
             const unsigned m = wm0 + mt * 32 + lj;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              uint32_t word;
-              if constexpr (FAST) {
-                uint32_t w[4];
+              int qv[4];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                  const float y = __int_as_float(acc[mt][nt][0][4 * q + t]);
-                  w[t] = __float_as_uint(__fadd_rn(__fmul_rn(y, s2), 12582912.0f));
+              for (int t = 0; t < 4; ++t) {
+                const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
+                float y;
+                if constexpr (EPI == kPCoop) {
+                  y = __int_as_float(acc[mt][nt][0][4 * q + t]);    // converted while waiting for the maximum
+                } else {
+                  y = fmaf((float)acc[mt][nt][0][4 * q + t], u, biasv[SWAPPED ? nt : 0][4 * q + t]);
+                  if (relu) y = fmaxf(y, 0.0f);                     // NaN -> 0 like (y > 0) ? y : 0
                 }
-                word = __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0400u) | __builtin_amdgcn_perm(w[3], w[2], 0x04000c0cu);
-              } else {
-                int qv[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                  const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
-                  float y;
-                  if constexpr (EPI == kPCoop) {
-                    y = __int_as_float(acc[mt][nt][0][4 * q + t]);    // converted while waiting for the maximum
-                  } else {
-                    y = fmaf((float)acc[mt][nt][0][4 * q + t], u, biasv[SWAPPED ? nt : 0][4 * q + t]);
-                    if (relu) y = fmaxf(y, 0.0f);                     // NaN -> 0 like (y > 0) ? y : 0
-                  }
-                  const int v = quant8(y, s2);
-                  qv[t] = (INTERIOR || (n < p.N && m < p.M)) ? v : 0;   // padding stays zero
-                }
-                word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) | ((uint32_t)(qv[2] & 0xFF) << 16) |
-                       ((uint32_t)(qv[3] & 0xFF) << 24);
+                const int v = quant8(y, s2);
+                qv[t] = (INTERIOR || (n < p.N && m < p.M)) ? v : 0;   // padding stays zero
               }
+              const uint32_t word = (uint32_t)(qv[0] & 0xFF) | ((uint32_t)(qv[1] & 0xFF) << 8) |
+                                    ((uint32_t)(qv[2] & 0xFF) << 16) | ((uint32_t)(qv[3] & 0xFF) << 24);
               // slot of row m in the fragment: lj + 32 (K half); the 4 bytes sit at 8 (q % 2) + 4 lh
-              *reinterpret_cast<uint32_t*>(sub + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
+              *reinterpret_cast<uint32_t*>(scratch + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
             }
-            if constexpr (!WIDE) {
-              // the wave reads back what it wrote itself: only its own LDS operations need to be complete
-              __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
-              const u4 v = *reinterpret_cast<const u4*>(sub + lane * 16);
-              const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
-              if (INTERIOR || (mrow < dO.Np && ncol < dO.Kp))
-                *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
-              __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
-            }
+            // the wave reads back what it wrote itself: only its own LDS operations need to be complete
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+            const u4 v = *reinterpret_cast<const u4*>(scratch + lane * 16);
+            const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
+            if (INTERIOR || (mrow < dO.Np && ncol < dO.Kp))
+              *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
           }
         }
-        if constexpr (WIDE) {
-          __builtin_amdgcn_s_waitcnt(0xC07F);          // the wave's own LDS writes are complete
-#pragma unroll
-          for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < TM; ++mt) {
-              const u4 v = *reinterpret_cast<const u4*>(area + (nt * TM + mt) * kFragBytes + lane * 16);
-              const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
-              if (INTERIOR || (mrow < dO.Np && ncol < dO.Kp))
-                *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16) = v;
-            }
-        }
       };
-      bool fast = false;
-      if constexpr (EPI == kPCoop) fast = interior && relu && red[0] < INFINITY;     // red[0]: the grid's max|y|
-      if (fast) store_tiles(std::true_type{}, std::true_type{});
-      else if (interior) store_tiles(std::true_type{}, std::false_type{});
-      else store_tiles(std::false_type{}, std::false_type{});
+      if (interior) store_tiles(std::true_type{});
+      else store_tiles(std::false_type{});
       MQ_STAMP(5);
       if constexpr (EPI == kPCoop) {
         if (blockIdx.x == 0 && tid == 0) {
