@@ -543,7 +543,7 @@ namespace {
 int fused_variant(const GemmArgs& a) {
   int v = forced_variant();
   if (v <= 0) v = tuned_variant(8, a.M, a.N, a.K);
-  if (v <= 0 || v == 2) v = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200 ? 1 : 3;
+  if (v <= 0 || v == 2 || v > 9) v = ((a.M + 255) / 256) * ((a.N + 255) / 256) >= 200 ? 1 : 3;
   return v;
 }
 size_t tiles_of(int variant, size_t M, size_t N) {
@@ -558,7 +558,7 @@ size_t tiles_of(int variant, size_t M, size_t N) {
 }
 }  // namespace
 
-int packed_variant_count(int bits) { return bits == 8 ? 9 : 5; }
+int packed_variant_count(int bits) { return bits == 8 ? 10 : 5; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
@@ -652,13 +652,14 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
       const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
       v = t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3);
     } else {
-      // small problems (a decode step's 300 sentences) are latency bound: the 128 x 64 tile with its deep
-      // pipeline gives more workgroups and the shortest prologue
+      // small problems (a decode step's 300 sentences) are latency bound: the split-K kernel (variant 10)
+      // fetches all operands of a workgroup in one round trip
       const size_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256);
       const size_t t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128);
-      v = t256 >= 200 ? 1 : (t128 >= 128 ? 3 : 7);
+      v = a.M <= 512 ? 10 : (t256 >= 200 ? 1 : (t128 >= 128 ? 3 : 7));
     }
   }
+  if (a.bits == 8 && v == 10) return launch_gemm_small(a, epi, s);
   if (a.bits == 8)
     return epi == kEpiRaw ? launch_pp_variant<8, kPRaw>(a, v, s) : launch_pp_variant<8, kPDequant>(a, v, s);
   return epi == kEpiRaw ? launch_pp_variant<16, kPRaw>(a, v, s) : launch_pp_variant<16, kPDequant>(a, v, s);

@@ -85,6 +85,8 @@ void set_forced_variant(int v);
 int forced_variant();
 // Both operands packed (activations from launch_quantize_pack); a.qA is the packed activation buffer.
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s);
+// Split-K form for few rows (8 bit, raw or dequantizing epilogue); launch_gemm_packed's variant 10.
+int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s);
 int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                          void* packed, hipStream_t s);
 int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);

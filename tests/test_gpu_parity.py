@@ -435,12 +435,13 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9], 16: [0, 1, 2, 3, 4, 5]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], 16: [0, 1, 2, 3, 4, 5]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (33, 31, 65), (129, 130, 80), (300, 70, 512), (260, 517, 96),
-                                   (2, 1000, 2048), (513, 258, 320)])
+                                   (2, 1000, 2048), (513, 258, 320), (300, 64, 4100), (70, 40, 9000),
+                                   (320, 1030, 1024)])
 def test_gemm_packed_full_range_all_variants(dtype, M, N, K):
     rng = np.random.default_rng(M * 1000003 + N * 1009 + K + 1)
     lim = 127 if dtype == np.int8 else 32767
@@ -837,7 +838,7 @@ def test_autotune_freezes_a_variant_and_results_stay_identical():
     nbytes = mq.mq_autotune_ws_bytes(8, M, N, K)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     best, us = mq.mq_autotune_gemm(8, M, N, K, 20, ws, nbytes)
-    assert 1 <= best <= 9 and us > 0
+    assert 1 <= best <= 10 and us > 0
     pw = mq.prepare_weight(dev(p["Wt"]), 8)
     pa, s = gpu_quantize_pack(p["A"], 8)
     Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
