@@ -297,10 +297,16 @@ int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int
 size_t mq_linear_ws_bytes(int bits, size_t M, size_t K);
 
 /* Float-in, float-out replacement for Y = A * B + bias with a prepared
- * parameter: abs-max and quant_int of A (or quant_int with the given multiplier
- * if sA_or_null is not NULL), then mq_gemm_dequant.  A composition of the calls
- * above on the same stream; nothing else is computed.
- * A: device float [M x K], 16-byte aligned.  ws as for mq_gemm_argmax. */
+ * parameter (Section 4.3: the integer product as a drop-in for the float one):
+ * abs-max and quant_int of A (or quant_int with the given multiplier if
+ * sA_or_null is not NULL), dot'_int, dequantize + bias (+ReLU), with the results
+ * of mq_quantize_f32 + mq_gemm_dequant bit for bit.  Two or three launches on
+ * `stream`; for 8-bit products with at most 512 rows and K a multiple of 32 up
+ * to 1024 (a decode step) quant_int runs inside the product kernel: one launch
+ * with a given multiplier, two with abs-max.
+ * A: device float [M x K], 16-byte aligned.  out_amax: optional device float
+ * that is raised to max|Y| (the caller zeroes it).  ws: device workspace of
+ * mq_linear_ws_bytes bytes, 16-byte aligned, contents irrelevant. */
 int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null,
                   const void* packedW, const float* sW, int bits, size_t N,
                   const float* bias, int relu, float* Y, float* out_amax,

@@ -52,12 +52,12 @@ hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
 // Layout of the scratch area used by mq_linear_f32 / mq_gemm_argmax.
 struct LinearWs {
-  size_t off_scale, off_rowsum, off_q, total;
+  size_t off_scale, off_q, off_part, total;
   LinearWs(int bits, size_t M, size_t K) {
-    off_scale = 0;                       // float amax/scale
-    off_rowsum = 256;                    // int32 [M]
-    off_q = round_up(off_rowsum + M * sizeof(int32_t), 256);
-    total = off_q + round_up(M * K * (size_t)(bits / 8), 256);
+    off_scale = 0;                       // float multiplier
+    off_q = 256;                         // packed quantized activations
+    off_part = off_q + round_up(PackedDims(bits, M, K).total_bytes(), 256);     // partial maxima
+    total = off_part + kAbsmaxPartials * sizeof(float);
   }
 };
 
@@ -642,23 +642,32 @@ int mq_linear_f32(const float* A, size_t M, size_t K, const float* sA_or_null, c
   hipStream_t s = as_stream(stream);
   uint8_t* base = static_cast<uint8_t*>(ws);
   float* scale = reinterpret_cast<float*>(base + L.off_scale);
-  int32_t* rowsum = reinterpret_cast<int32_t*>(base + L.off_rowsum);
+  float* part = reinterpret_cast<float*>(base + L.off_part);
   void* q = base + L.off_q;
   const float* sA = sA_or_null;
-  int rc;
-  if (sA == nullptr) {
-    rc = launch_absmax(A, M * K, scale, s);
-    if (rc != MQ_OK) return rc;
-    rc = launch_scale(scale, bits, scale, s);
-    if (rc != MQ_OK) return rc;
-    sA = scale;
-  }
-  rc = launch_quantize(A, M, K, bits, sA, q, bits == 16 ? rowsum : nullptr, s);
-  if (rc != MQ_OK) return rc;
   GemmArgs a{};
-  a.qA = q; a.rowsumA = rowsum; a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
-  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
-  return launch_gemm(a, kEpiDequant, s);
+  a.packedW = packedW; a.bits = bits; a.M = M; a.N = N; a.K = K;
+  a.sW = sW; a.bias = bias; a.relu = relu != 0; a.Y = Y; a.out_amax = out_amax;
+  int rc;
+  if (bits == 8 && gemm_small_f32_supported(M, N, K)) {
+    // decode-sized input: quant_int happens inside the product's operand fetch (same arithmetic, same
+    // results), one launch with a given multiplier, two with abs-max
+    if (sA != nullptr) return launch_gemm_small_f32(A, sA, 0, nullptr, a, s);
+    unsigned np = 0;
+    rc = launch_absmax_partials(A, M * K, part, &np, s);
+    if (rc != MQ_OK) return rc;
+    return launch_gemm_small_f32(A, part, np, scale, a, s);
+  }
+  // general case: quant_int straight into fragment order, then the packed product
+  if (sA == nullptr) {
+    rc = launch_absmax_quantize_pack(A, M, K, bits, part, scale, q, s);
+    sA = scale;
+  } else {
+    rc = launch_quantize_pack(A, M, K, bits, sA, q, s);
+  }
+  if (rc != MQ_OK) return rc;
+  a.qA = q; a.sA = sA;
+  return launch_gemm_packed(a, kEpiDequant, s);
 }
 
 /* ---- float glue of the averaging-attention decode step -------------------- */
@@ -781,6 +790,13 @@ int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev,
   auto product = [&](const float* A, size_t Kdim, const mq_product& W, size_t N, int relu, float* Y,
                      const float* partials, size_t np, float* out_amax) -> int {
     int rc;
+    if (partials != nullptr && np <= kAbsmaxPartials && gemm_small_f32_supported(M, N, Kdim)) {
+      // short K: quant_int inside the product's operand fetch, no quantizing launch
+      GemmArgs g{};
+      g.packedW = W.packed; g.bits = 8; g.M = M; g.N = N; g.K = Kdim;
+      g.sW = W.scale; g.bias = W.bias; g.relu = relu; g.Y = Y; g.out_amax = out_amax;
+      return launch_gemm_small_f32(A, partials, (unsigned)np, sA, g, s);
+    }
     if (partials != nullptr && np <= kAbsmaxPartials)
       rc = launch_quantize_pack_partials(A, M, Kdim, 8, partials, (unsigned)np, sA, qbuf, s);
     else

@@ -150,6 +150,197 @@ int launch_small(const GemmArgs& a, int dequant, hipStream_t s) {
   return check_hip(hipGetLastError());
 }
 
+
+// quant_int fused into the operand fetch (Section 4.2: activations are quantized on every call): A comes as
+// fp32 rows, each lane loads the 16 floats of its fragment slot, multiplies by the multiplier, rounds to
+// nearest even, clamps and packs them into the 16 operand bytes.  The multiplier is either given or formed
+// here from partial maxima left by the kernel that produced A (127 / max, one correctly rounded division,
+// as the separate quantizer does).  Every column block of a row block repeats the conversion of that row
+// block; that is cheap next to a launch as long as K is short (the fp32 rows are four times the bytes).
+struct SmallF32Params {
+  const float* A;            // [M x K] fp32, K a multiple of 32, rows 16-byte aligned
+  const float* scale;        // multiplier (npartial == 0) or partial maxima
+  unsigned npartial;
+  float* scale_out;          // receives the multiplier (workgroup 0)
+  const uint8_t* packedW;
+  unsigned M, N, K, tiles_n;
+  const float* sW;
+  const float* bias;
+  int relu;
+  float* Y;
+  float* out_amax;
+};
+
+__device__ __forceinline__ uint32_t quant_pack4(float4 v, float s) {
+  auto q = [&](float x) -> uint32_t {
+    const float r = rintf(__fmul_rn(x, s));
+    int i;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(i) : "v"(r));      // saturates, NaN -> 0
+    return (uint32_t)(min(max(i, -127), 127) & 0xFF);
+  };
+  return q(v.x) | (q(v.y) << 8) | (q(v.z) << 16) | (q(v.w) << 24);
+}
+
+// TNW: 32-column blocks per workgroup; KS waves split K; a round is 4 fragments (128 elements of K).
+// Each wave reads its own run of K from the fp32 rows in whole 512-byte pieces (two rows per load
+// instruction), converts, and turns the bytes into operand fragments through a private piece of LDS:
+// fragment f of a round sits at f * kPitch, K half h of a row at h * kHalf inside it (the paddings
+// spread the 4-byte writes of a row over the banks), 16 bytes per row.
+template <int TNW, int KS>
+__global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params p) {
+  constexpr int KW = 4;
+  constexpr int kHalf = 512 + 16, kPitch = 2 * kHalf;
+  extern __shared__ __attribute__((aligned(16))) int part[];      // [KS][TNW * 1024], then the staging pieces
+  __shared__ float red[KS];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  uint8_t* stage = reinterpret_cast<uint8_t*>(part + KS * TNW * 1024) + wave * (KW * kPitch);
+  const PackedDims dW(8, p.N, p.K);
+  const unsigned tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
+  const unsigned ksl = p.K / 32;                                  // slices that hold real elements
+  const unsigned per = (ksl + KS - 1) / KS;
+  const unsigned kb_begin = wave * per;
+  const unsigned kb_end = kb_begin + per < ksl ? kb_begin + per : ksl;
+  const int lj = lane % 32, lh = lane / 32;
+
+  const uint8_t* w_src[TNW];
+#pragma unroll
+  for (int c = 0; c < TNW; ++c) {
+    unsigned nb = tile_n * TNW + c;
+    if (nb >= dW.nblocks) nb = (unsigned)dW.nblocks - 1;
+    w_src[c] = p.packedW + dW.frag_offset(nb, 0) + lane * 16;
+  }
+  // load i of a round: row 2 i + lane / 32 of the tile, floats 4 (lane % 32) .. + 3 of the round's 128
+  // (rows past the end repeat the last one; their results are never stored)
+  const float* a_src[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    unsigned row = tile_m * 32 + 2 * i + lh;
+    if (row >= p.M) row = p.M - 1;
+    a_src[i] = p.A + (size_t)row * p.K + 4 * lj;
+  }
+  // where this lane's four bytes of load i go: fragment lj / 8, K half (lj / 4) % 2, row 2 i + lh, byte 4 (lj % 4)
+  uint8_t* st_dst = stage + (lj / 8) * kPitch + ((lj / 4) % 2) * kHalf + lh * 16 + 4 * (lj % 4);
+
+  float4 fa[16];
+  u4 fw[TNW][KW];
+  auto fetch = [&](unsigned kb0) {
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      const unsigned kb = kb0 + j < kb_end ? kb0 + j : kb_end - 1;
+#pragma unroll
+      for (int c = 0; c < TNW; ++c) fw[c][j] = *reinterpret_cast<const u4*>(w_src[c] + (size_t)kb * kFragBytes);
+    }
+    // a lane whose fragment lies past the run reads the run's last fragment instead (a valid address, unused)
+    const unsigned kb = kb0 + lj / 8 < kb_end ? kb0 + lj / 8 : kb_end - 1;
+    const ptrdiff_t off = (ptrdiff_t)kb * 32 - (ptrdiff_t)(lj / 8) * 32;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) fa[i] = *reinterpret_cast<const float4*>(a_src[i] + off);
+  };
+  if (kb_begin < kb_end) fetch(kb_begin);        // the first round is on its way while the multiplier is formed
+
+  float s;
+  if (p.npartial != 0) {
+    float m = 0.f;
+    for (unsigned i = tid; i < p.npartial; i += KS * 64) m = fmaxf(m, p.scale[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    float amax = red[0];
+#pragma unroll
+    for (int w = 1; w < KS; ++w) amax = fmaxf(amax, red[w]);
+    s = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
+  } else {
+    s = *p.scale;
+  }
+  if (blockIdx.x == 0 && tid == 0 && p.scale_out != nullptr) *p.scale_out = s;
+
+  v16i acc[TNW];
+#pragma unroll
+  for (int c = 0; c < TNW; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0;
+  for (unsigned kb0 = kb_begin; kb0 < kb_end; kb0 += KW) {
+    if (kb0 != kb_begin) fetch(kb0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<uint32_t*>(st_dst + i * 32) = quant_pack4(fa[i], s);
+    // the wave reads back what it wrote itself: LDS operations of one wave complete in order
+    u4 a[KW];
+#pragma unroll
+    for (int j = 0; j < KW; ++j) a[j] = *reinterpret_cast<const u4*>(stage + j * kPitch + lh * kHalf + lj * 16);
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      if (kb0 + j < kb_end) {
+#pragma unroll
+        for (int c = 0; c < TNW; ++c)
+          acc[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a[j]), as_v4i(fw[c][j]), acc[c], 0, 0, 0);
+      }
+    }
+  }
+
+  int* mine = part + wave * (TNW * 1024);
+#pragma unroll
+  for (int c = 0; c < TNW; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mine[(c * 16 + r) * 64 + lane] = acc[c][r];
+  __syncthreads();
+
+  const float u = __fdiv_rn(1.0f, __fmul_rn(s, *p.sW));
+  float local_amax = 0.f;
+  constexpr int PER_THREAD = TNW * 1024 / (KS * 64);
+  static_assert(PER_THREAD >= 1 && PER_THREAD * KS * 64 == TNW * 1024, "elements must divide over the threads");
+#pragma unroll
+  for (int i = 0; i < PER_THREAD; ++i) {
+    const int e = tid + i * KS * 64;
+    unsigned v = 0;
+#pragma unroll
+    for (int w = 0; w < KS; ++w) v += (unsigned)part[w * (TNW * 1024) + e];      // mod 2^32
+    const int c = e / 1024, r = (e / 64) % 16;
+    const unsigned n = (tile_n * TNW + c) * 32 + lj;
+    const unsigned m = tile_m * 32 + 8 * (r / 4) + 4 * lh + r % 4;
+    if (n < p.N && m < p.M) {
+      float y = fmaf((float)(int)v, u, p.bias != nullptr ? p.bias[n] : 0.0f);
+      if (p.relu) y = (y > 0.0f) ? y : 0.0f;
+      p.Y[(size_t)m * p.N + n] = y;
+      local_amax = fmaxf(local_amax, fabsf(y));
+    }
+  }
+  if (p.out_amax != nullptr) {
+    __shared__ float wave_amax[KS];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
+    if (lane == 0) wave_amax[wave] = local_amax;
+    __syncthreads();
+    if (tid == 0) {
+      float mx = wave_amax[0];
+#pragma unroll
+      for (int w = 1; w < KS; ++w) mx = fmaxf(mx, wave_amax[w]);
+      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+      const unsigned bits = __float_as_uint(mx);
+      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+    }
+  }
+}
+
+template <int TNW, int KS>
+int launch_small_f32(SmallF32Params p, hipStream_t s) {
+  constexpr size_t smem = (size_t)KS * TNW * 1024 * sizeof(int) + (size_t)KS * 4 * 2 * (512 + 16);
+  const PackedDims dW(8, p.N, p.K);
+  const size_t tiles_m = (p.M + 31) / 32, tiles_n = (dW.nblocks + TNW - 1) / TNW;
+  p.tiles_n = (unsigned)tiles_n;
+  if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
+  auto kern = k_gemm_small_f32<TNW, KS>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    if (rc != MQ_OK) return rc;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(KS * 64), smem, s, p);
+  return check_hip(hipGetLastError());
+}
+
 template <int TMW>
 int launch_small_tmw(const GemmArgs& a, int dequant, size_t kfrags, hipStream_t s) {
   // one round of loads per wave where K allows: 4 waves up to K = 512, 8 up to 2048
@@ -173,6 +364,35 @@ int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   // two row blocks per workgroup only when that still leaves a workgroup for every compute unit
   const bool wide = ((dA.nblocks + 1) / 2) * dW.nblocks >= 256;
   return wide ? launch_small_tmw<2>(a, dequant, dA.kfrags, s) : launch_small_tmw<1>(a, dequant, dA.kfrags, s);
+}
+
+// Whether quantizing inside the product pays: few rows, K short enough that re-reading the fp32 rows once
+// per column tile stays below the cost of a separate quantizing launch.
+bool gemm_small_f32_supported(size_t M, size_t N, size_t K) {
+  return M >= 1 && M <= 512 && N >= 1 && K >= 32 && K % 32 == 0 && K <= 1024;
+}
+
+// quant_int(A) + dot'_int + dequantize + bias (+ReLU) (+max|y|) in one launch; see k_gemm_small_f32.
+// scale: the multiplier (npartial == 0) or npartial partial maxima of |A|.
+int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial, float* scale_out, const GemmArgs& a,
+                          hipStream_t s) {
+  if (!gemm_small_f32_supported(a.M, a.N, a.K) || a.bits != 8) return MQ_ERR_UNSUPPORTED;
+  SmallF32Params p{};
+  p.A = A; p.scale = scale; p.npartial = npartial; p.scale_out = scale_out;
+  p.packedW = static_cast<const uint8_t*>(a.packedW);
+  p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
+  p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  const PackedDims dW(8, a.N, a.K);
+  const size_t ksl = a.K / 32;
+  // two column blocks per workgroup (half the re-reads of A) when that still leaves 160 workgroups; four
+  // were slower (7.7 against 6.9 us for 300 x 2048 x 512)
+  const bool wide = ((a.M + 31) / 32) * ((dW.nblocks + 1) / 2) >= 160;
+  if (wide) {
+    if (ksl <= 16) return launch_small_f32<2, 4>(p, s);
+    return launch_small_f32<2, 8>(p, s);
+  }
+  if (ksl <= 16) return launch_small_f32<1, 4>(p, s);
+  return launch_small_f32<1, 8>(p, s);
 }
 
 }  // namespace mq

@@ -87,6 +87,11 @@ int forced_variant();
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // Split-K form for few rows (8 bit, raw or dequantizing epilogue); launch_gemm_packed's variant 10.
 int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s);
+// The same with quant_int of fp32 activations done in the operand fetch (8 bit, dequantizing epilogue):
+// `scale` is the multiplier (npartial == 0) or npartial partial maxima of |A|; a.qA, a.sA are not used.
+bool gemm_small_f32_supported(size_t M, size_t N, size_t K);
+int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial, float* scale_out, const GemmArgs& a,
+                          hipStream_t s);
 int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                          void* packed, hipStream_t s);
 int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
@@ -97,6 +102,7 @@ constexpr unsigned kAbsmaxPartials = 1024;   // floats of scratch launch_absmax_
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
                                 float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr,
                                 unsigned nclear = 0);
+int launch_absmax_partials(const float* x, size_t n, float* partials, unsigned* count, hipStream_t s);
 int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
                                       float* scale_out, void* packed, hipStream_t s);
 int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,

@@ -569,6 +569,14 @@ int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, 
 // abs-max + quant_int into the packed layout in two launches, no atomics, no fill:
 // partial maxima to `partials` (kAbsmaxPartials floats), then quantization with the multiplier
 // formed from them; scale_out[0] receives the multiplier.
+// Partial maxima of |x| only (at most kAbsmaxPartials of them); *count receives how many were written.
+int launch_absmax_partials(const float* x, size_t n, float* partials, unsigned* count, hipStream_t s) {
+  const unsigned g1 = grid_for(n, (size_t)kThreads * 8, kAbsmaxPartials);
+  hipLaunchKernelGGL(k_absmax_partial, dim3(g1), dim3(kThreads), 0, s, x, n, partials, (unsigned*)nullptr, 0u);
+  *count = g1;
+  return check_hip(hipGetLastError());
+}
+
 int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bits, float* partials,
                                 float* scale_out, void* packed, hipStream_t s, unsigned* clear, unsigned nclear) {
   const size_t n = rows * cols;

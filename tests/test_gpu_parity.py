@@ -238,6 +238,31 @@ def test_mq_linear_f32_is_the_composition():
         assert host(am)[0] == o["Y"].max()
 
 
+@pytest.mark.parametrize("M,N,K,relu,fixed", [(300, 2048, 512, True, False), (300, 512, 512, False, False),
+                                              (300, 1024, 1024, False, False), (1, 1, 32, False, False),
+                                              (33, 70, 96, True, False), (512, 100, 768, False, True),
+                                              (300, 512, 2048, False, False), (77, 40, 100, True, False),
+                                              (290, 333, 992, True, True)])
+def test_mq_linear_f32_decode_sizes(M, N, K, relu, fixed):
+    # few rows, 8 bit: quant_int runs inside the product kernel when K is a multiple of 32 up to 1024
+    # (the other shapes here take the separate quantizer); either way the oracle's linear layer, bit for bit
+    p = workloads.random_problem(M * 7 + N * 3 + K, M, N, K)
+    A = np.clip(p["A"], -2, 2) if fixed else p["A"]
+    o = oracle.linear(A, p["Wt"], 8, p["bias"], relu, sA=63.5 if fixed else None)
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    nbytes = mq.mq_linear_ws_bytes(8, M, K)
+    ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    sA = torch.full((1,), 63.5, dtype=torch.float32, device=DEV) if fixed else None
+    for bias in (dev(p["bias"]), None):
+        want = o["Y"] if bias is not None else oracle.linear(A, p["Wt"], 8, None, relu, sA=63.5 if fixed else None)["Y"]
+        am.zero_()
+        mq.mq_linear_f32(dev(A), M, K, sA, pw.packed, pw.scale, 8, N, bias, relu, Y, am, ws, nbytes)
+        assert np.array_equal(host(Y), want)
+        assert host(am)[0] == np.abs(want).max()
+
+
 # -------------------------------------------------------------------- arg-max
 
 def gpu_greedy(Hd, E, pw=None):
@@ -500,7 +525,8 @@ def gpu_greedy_packed(Hd, E):
 
 
 @pytest.mark.parametrize("M,V,d", [(1, 1, 1), (3, 17, 8), (12, 777, 64), (33, 4100, 96), (130, 129, 512), (300, 3000, 512),
-                                   (384, 9000, 192), (97, 20000, 128), (257, 33, 300)])
+                                   (384, 9000, 192), (97, 20000, 128), (257, 33, 300), (320, 5000, 448),
+                                   (261, 40000, 512)])
 def test_greedy_packed_small(M, V, d):
     c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + 5)
     o = oracle.greedy_output_layer(c["Hd"], c["E"])
