@@ -22,7 +22,10 @@ namespace {
 template <int TMW, int KS, int KW>
 __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const int dequant) {
   extern __shared__ __attribute__((aligned(16))) int part[];      // [KS][TMW * 1024]
-  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  // The wave index, and with it the wave's run of K, must be wave-uniform to the COMPILER (scalar registers,
+  // scalar branches): a matrix instruction under a lane mask is executed even when the mask is empty.
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
   const unsigned tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
   const unsigned kfrags = (unsigned)dA.kfrags;
@@ -105,9 +108,10 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
       }
     }
   }
-  if (dequant && p.out_amax != nullptr) {
-    // block-wide maximum, then at most one atomic per block; the running maximum only grows, so a block
-    // that cannot raise it skips the atomic
+  if (dequant && (p.out_amax != nullptr || p.partial != nullptr)) {
+    // block-wide maximum of |y|: one value per workgroup in p.partial (no atomics; the next quantizer reduces
+    // them), and/or raised into *p.out_amax with at most one atomic per block; the running maximum only
+    // grows, so a block that cannot raise it skips the atomic
     __shared__ float wave_amax[KS];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
@@ -117,9 +121,12 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
       float mx = wave_amax[0];
 #pragma unroll
       for (int w = 1; w < KS; ++w) mx = fmaxf(mx, wave_amax[w]);
-      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
-      const unsigned bits = __float_as_uint(mx);
-      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+      if (p.partial != nullptr) p.partial[blockIdx.x] = mx;
+      if (p.out_amax != nullptr) {
+        unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+        const unsigned bits = __float_as_uint(mx);
+        if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+      }
     }
   }
 }
@@ -137,6 +144,7 @@ int launch_small(const GemmArgs& a, int dequant, hipStream_t s) {
   p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  p.partial = a.partial;
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
   auto kern = k_gemm_small<TMW, KS, KW>;
   static bool attr_done = false;
@@ -169,6 +177,7 @@ struct SmallF32Params {
   int relu;
   float* Y;
   float* out_amax;
+  float* partial_out;        // optional: max|y| of every workgroup
 };
 
 __device__ __forceinline__ uint32_t quant_pack4(float4 v, float s) {
@@ -192,7 +201,8 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
   constexpr int kHalf = 512 + 16, kPitch = 2 * kHalf;
   extern __shared__ __attribute__((aligned(16))) int part[];      // [KS][TNW * 1024], then the staging pieces
   __shared__ float red[KS];
-  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);      // scalar, see k_gemm_small
   uint8_t* stage = reinterpret_cast<uint8_t*>(part + KS * TNW * 1024) + wave * (KW * kPitch);
   const PackedDims dW(8, p.N, p.K);
   const unsigned tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
@@ -264,10 +274,14 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
     if (kb0 != kb_begin) fetch(kb0);
 #pragma unroll
     for (int i = 0; i < 16; ++i) *reinterpret_cast<uint32_t*>(st_dst + i * 32) = quant_pack4(fa[i], s);
-    // the wave reads back what it wrote itself: LDS operations of one wave complete in order
+    // The wave reads back what it wrote itself: LDS operations of one wave complete in order, so the
+    // hardware needs no wait.  The compiler does: words are written and 16-byte vectors read, types it may
+    // take for non-aliasing, so both sides are fenced against compile-time motion.
+    asm volatile("" ::: "memory");
     u4 a[KW];
 #pragma unroll
     for (int j = 0; j < KW; ++j) a[j] = *reinterpret_cast<const u4*>(stage + j * kPitch + lh * kHalf + lj * 16);
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int j = 0; j < KW; ++j) {
       if (kb0 + j < kb_end) {
@@ -305,7 +319,8 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
       local_amax = fmaxf(local_amax, fabsf(y));
     }
   }
-  if (p.out_amax != nullptr) {
+  if (p.out_amax != nullptr || p.partial_out != nullptr) {
+    // as in k_gemm_small: one maximum per workgroup, without atomics, and/or the raised word
     __shared__ float wave_amax[KS];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
@@ -315,9 +330,12 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
       float mx = wave_amax[0];
 #pragma unroll
       for (int w = 1; w < KS; ++w) mx = fmaxf(mx, wave_amax[w]);
-      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
-      const unsigned bits = __float_as_uint(mx);
-      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+      if (p.partial_out != nullptr) p.partial_out[blockIdx.x] = mx;
+      if (p.out_amax != nullptr) {
+        unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+        const unsigned bits = __float_as_uint(mx);
+        if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+      }
     }
   }
 }
@@ -355,6 +373,19 @@ int launch_small_tmw(const GemmArgs& a, int dequant, size_t kfrags, hipStream_t 
 
 }  // namespace
 
+// Workgroups of launch_gemm_small / launch_gemm_small_f32 for a shape = maxima written to GemmArgs::partial.
+size_t gemm_small_partials(size_t M, size_t N, size_t K) {
+  const PackedDims dA(8, M, K), dW(8, N, K);
+  const bool wide = ((dA.nblocks + 1) / 2) * dW.nblocks >= 256;
+  return (wide ? (dA.nblocks + 1) / 2 : dA.nblocks) * dW.nblocks;
+}
+size_t gemm_small_f32_partials(size_t M, size_t N, size_t K) {
+  const PackedDims dW(8, N, K);
+  const size_t rbs = (M + 31) / 32;
+  const bool wide = rbs * ((dW.nblocks + 1) / 2) >= 160;
+  return rbs * (wide ? (dW.nblocks + 1) / 2 : dW.nblocks);
+}
+
 // Split-K product for few rows: 8-bit packed operands, raw sums or dequantize + bias (+ReLU) (+max|y|).
 // Any shape is computed correctly; it is the fast choice when the result is small.
 int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s) {
@@ -381,7 +412,7 @@ int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial,
   p.A = A; p.scale = scale; p.npartial = npartial; p.scale_out = scale_out;
   p.packedW = static_cast<const uint8_t*>(a.packedW);
   p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
-  p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax; p.partial_out = a.partial;
   const PackedDims dW(8, a.N, a.K);
   const size_t ksl = a.K / 32;
   // two column blocks per workgroup (half the re-reads of A) when that still leaves 160 workgroups; four

@@ -87,6 +87,10 @@ int forced_variant();
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // Split-K form for few rows (8 bit, raw or dequantizing epilogue); launch_gemm_packed's variant 10.
 int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s);
+// With the dequantizing epilogue both small-product launchers also write max|y| of every workgroup to
+// a.partial (if not NULL): gemm_small_partials / gemm_small_f32_partials values.
+size_t gemm_small_partials(size_t M, size_t N, size_t K);
+size_t gemm_small_f32_partials(size_t M, size_t N, size_t K);
 // The same with quant_int of fp32 activations done in the operand fetch (8 bit, dequantizing epilogue):
 // `scale` is the multiplier (npartial == 0) or npartial partial maxima of |A|; a.qA, a.sA are not used.
 bool gemm_small_f32_supported(size_t M, size_t N, size_t K);
