@@ -360,7 +360,11 @@ int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws,
   if (rc == MQ_OK) rc = check_hip(hipMemcpyAsync(scal, ones, sizeof ones, hipMemcpyHostToDevice, s));
   if (rc != MQ_OK) return rc;
   hipEvent_t e0, e1;
-  if (check_hip(hipEventCreate(&e0)) != MQ_OK || check_hip(hipEventCreate(&e1)) != MQ_OK) return MQ_ERR_HIP;
+  if (check_hip(hipEventCreate(&e0)) != MQ_OK) return MQ_ERR_HIP;
+  if (check_hip(hipEventCreate(&e1)) != MQ_OK) {
+    (void)hipEventDestroy(e0);
+    return MQ_ERR_HIP;
+  }
   GemmArgs a{};
   a.qA = pa; a.packedW = pw; a.bits = bits; a.M = M; a.N = N; a.K = K;
   a.sA = scal; a.sW = scal + 1; a.relu = 0; a.Y = Y;
@@ -372,18 +376,18 @@ int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws,
     rc = launch_gemm_packed(a, kEpiDequant, s);          // untimed first call: code upload, attribute set-up
     if (rc == MQ_ERR_UNSUPPORTED) continue;
     if (rc != MQ_OK) break;
-    hipEventRecord(e0, s);
+    rc = check_hip(hipEventRecord(e0, s));
     for (int i = 0; i < runs && rc == MQ_OK; ++i) rc = launch_gemm_packed(a, kEpiDequant, s);
-    hipEventRecord(e1, s);
+    if (rc == MQ_OK) rc = check_hip(hipEventRecord(e1, s));
     if (rc != MQ_OK) break;
     if (check_hip(hipEventSynchronize(e1)) != MQ_OK) { rc = MQ_ERR_HIP; break; }
     float ms = 0.f;
-    hipEventElapsedTime(&ms, e0, e1);
+    if (check_hip(hipEventElapsedTime(&ms, e0, e1)) != MQ_OK) { rc = MQ_ERR_HIP; break; }
     if (best == 0 || ms < best_ms) { best = v; best_ms = ms; }
   }
   set_forced_variant(saved);
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (rc != MQ_OK && rc != MQ_ERR_UNSUPPORTED) return rc;
   if (best == 0) return MQ_ERR_UNSUPPORTED;
   set_tuned_variant(bits, M, N, K, best);

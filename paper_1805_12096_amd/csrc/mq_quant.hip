@@ -29,8 +29,12 @@ __global__ void k_clear_words(uint32_t* p, unsigned n) {
 
 // |x| of a non-NaN float orders like its bit pattern, so the grid-wide maximum
 // is an integer atomicMax.  fmaxf drops NaN operands.
-__global__ __launch_bounds__(kThreads) void k_absmax(const float* __restrict__ x, size_t n,
-                                                     uint32_t* __restrict__ amax_bits) {
+// Workgroups of 1024 threads, at most 512 of them: every workgroup may end in one atomic on the same word,
+// and those are served one after the other (2048 small workgroups ending together took 25 us for that alone).
+constexpr int kAbsmaxThreads = 1024;
+__global__ __launch_bounds__(kAbsmaxThreads) void k_absmax(const float* __restrict__ x, size_t n,
+                                                           uint32_t* __restrict__ amax_bits) {
+  constexpr int kThreads = kAbsmaxThreads;
   const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
   const size_t nthreads = (size_t)gridDim.x * kThreads;
   const size_t nvec = n / 4;
@@ -183,9 +187,9 @@ unsigned grid_for(size_t work_items, size_t per_block, unsigned cap) {
 
 int launch_absmax(const float* x, size_t n, float* amax, hipStream_t s) {
   hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(1), 0, s, reinterpret_cast<uint32_t*>(amax), 0u);
-  // 16 floats per thread and pass; cap the grid at 8 blocks per compute unit
-  const unsigned grid = grid_for(n, (size_t)kThreads * 16, 2048);
-  hipLaunchKernelGGL(k_absmax, dim3(grid), dim3(kThreads), 0, s, x, n, reinterpret_cast<uint32_t*>(amax));
+  // 16 floats per thread and pass; at most two workgroups per compute unit
+  const unsigned grid = grid_for(n, (size_t)kAbsmaxThreads * 16, 512);
+  hipLaunchKernelGGL(k_absmax, dim3(grid), dim3(kAbsmaxThreads), 0, s, x, n, reinterpret_cast<uint32_t*>(amax));
   return check_hip(hipGetLastError());
 }
 
