@@ -113,6 +113,32 @@ def main():
                 fn()
         return g.replay
 
+    STEPS_PER_GRAPH = 10
+
+    def time_steps(fn, steps, warm):
+        """Microseconds per step over EXACTLY `steps` steps after `warm` untimed ones.  Steps are replayed as HIP
+        graphs of STEPS_PER_GRAPH consecutive steps (the remainder one step at a time): a graph launch costs
+        several microseconds of its own, which a loop over batches would not pay once per batch."""
+        one = graphed(fn, 1)
+        many = graphed(fn, STEPS_PER_GRAPH) if steps >= STEPS_PER_GRAPH and not args.no_graph else None
+        for _ in range(warm):
+            one()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        done = 0
+        if many is not None:
+            for _ in range(steps // STEPS_PER_GRAPH):
+                many()
+                done += STEPS_PER_GRAPH
+        while done < steps:
+            one()
+            done += 1
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps
+
     def time_kernel(fn, reps=10, iters=20):
         """Average duration of one call of fn (us): `reps` back-to-back copies replayed as one graph, so
         that host launch overhead does not hide kernels of a few microseconds."""
@@ -235,7 +261,7 @@ def main():
         step = w.fused_step if fused else w.step
         step()
         torch.cuda.synchronize()
-        us = time_events(graphed(step), steps, warmup)
+        us = time_steps(step, steps, warmup)
         if fused:
             w.step()            # leaves s2 / q2 of the unfused chain in place for the gemm2 timing
         per_kernel = {}
@@ -267,7 +293,7 @@ def main():
     c2 = workloads.config2()
     w2, us2, pk2 = run_ffn(c2, 8, args.steps, args.warmup, fused=True)
     tops2 = w2.ops / us2 / 1e6
-    us2_chain = time_events(graphed(w2.step), args.steps, args.warmup)     # the same block call by call, H in fp32
+    us2_chain = time_steps(w2.step, args.steps, args.warmup)     # the same block call by call, H in fp32
 
     # the dominant launch of the timed step: the single-pass first product (the longest one; the second product is
     # within a few percent of it, so the choice is fixed rather than left to run-to-run noise), else the longest
@@ -296,7 +322,8 @@ def main():
         "config": {"workload": "transformer-base FFN int8: [8192x512]x[512x2048]+bias+ReLU, requantize, "
                                "[8192x2048]x[2048x512]+bias; per-tensor abs-max scales",
                    "M": w2.M, "d": w2.d, "ffn": w2.f, "graph": not args.no_graph,
-                   "path": "mq_ffn_i8_f32 (5 launches, H never stored in fp32)"},
+                   "steps_per_graph": 1 if args.no_graph else STEPS_PER_GRAPH,
+                   "path": "mq_ffn_i8_f32 (4 launches, H never stored in fp32)"},
         "unfused_chain": {"us_per_step": round(us2_chain, 2), "TOPS": round(w2.ops / us2_chain / 1e6, 2),
                           "what": "abs-max, scale, quant_int, product(+max|H|), scale, quant_int, product as 9 launches, "
                                   "H stored and re-read in fp32"},
@@ -402,7 +429,7 @@ def main():
             mq.mq_gemm_dequant_packed(w2.q2, w2.p2f.packed, 8, w2.M, w2.d, w2.f, sc, w2.p2f.scale, w2.b2, False, w2.Y, None)
 
         fixed_step()
-        usf = time_events(graphed(fixed_step), args.steps, args.warmup)
+        usf = time_steps(fixed_step, args.steps, args.warmup)
         extras["ffn_base_int8_fixed_multipliers"] = {
             "what": "same block, multipliers fixed at 63.5 as in the paper (no abs-max), 3 launches",
             "us_per_step": round(usf, 2), "TOPS": round(w2.ops / usf / 1e6, 1)}
@@ -434,7 +461,7 @@ def main():
             mq.mq_gemm_dequant_packed(q1_, p1_.packed, 16, 384, 512, 512, s1_, p1_.scale, b1_, False, Y1_, None)
 
         c1_step()
-        us1 = time_events(graphed(c1_step), args.steps, args.warmup)
+        us1 = time_steps(c1_step, args.steps, args.warmup)
         extras["single_int16_product_384x512x512"] = {"us_per_call": round(us1, 2), "launches": 3,
                                                       "TOPS_useful": round(2 * 384 * 512 * 512 / us1 / 1e6, 2)}
 

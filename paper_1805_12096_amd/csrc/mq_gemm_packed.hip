@@ -558,7 +558,7 @@ size_t tiles_of(int variant, size_t M, size_t N) {
 }
 }  // namespace
 
-int packed_variant_count(int bits) { return bits == 8 ? 10 : 5; }
+int packed_variant_count(int bits) { return bits == 8 ? 10 : 6; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
@@ -650,7 +650,7 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // every compute unit work, smaller tiles for small problems.
     if (a.bits == 16) {
       const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
-      v = t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3);
+      v = a.M <= 512 ? 6 : (t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3));
     } else {
       // small problems (a decode step's 300 sentences) are latency bound: the split-K kernel (variant 10)
       // fetches all operands of a workgroup in one round trip
@@ -659,7 +659,7 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
       v = a.M <= 512 ? 10 : (t256 >= 200 ? 1 : (t128 >= 128 ? 3 : 7));
     }
   }
-  if (a.bits == 8 && v == 10) return launch_gemm_small(a, epi, s);
+  if ((a.bits == 8 && v == 10) || (a.bits == 16 && v == 6)) return launch_gemm_small(a, epi, s);
   if (a.bits == 8)
     return epi == kEpiRaw ? launch_pp_variant<8, kPRaw>(a, v, s) : launch_pp_variant<8, kPDequant>(a, v, s);
   return epi == kEpiRaw ? launch_pp_variant<16, kPRaw>(a, v, s) : launch_pp_variant<16, kPDequant>(a, v, s);

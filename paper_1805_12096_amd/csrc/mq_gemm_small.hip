@@ -19,14 +19,20 @@ namespace mq {
 namespace {
 
 // TMW: 32-row blocks per workgroup; KS: waves (= parts of K); KW: fragments per operand row block and round.
-template <int TMW, int KS, int KW>
+// BITS == 16: every fragment is two byte planes (high byte; low byte with its top bit flipped) and a result
+// tile takes four products into three accumulators (hh, hl + lh, ll); a wave's partial sum is their
+// recombination 2^16 hh + 2^8 mid + ll (mod 2^32), which adds up over the waves like the 8-bit sums, and the
+// plane offsets are corrected once at the end: + 128 (rowsum[m] + colsum[n]) - 16384 K.
+template <int BITS, int TMW, int KS, int KW>
 __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const int dequant) {
+  constexpr int NPL = BITS == 16 ? 2 : 1;
+  constexpr int NACC = BITS == 16 ? 3 : 1;
   extern __shared__ __attribute__((aligned(16))) int part[];      // [KS][TMW * 1024]
   const int tid = threadIdx.x, lane = tid % 64;
   // The wave index, and with it the wave's run of K, must be wave-uniform to the COMPILER (scalar registers,
   // scalar branches): a matrix instruction under a lane mask is executed even when the mask is empty.
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-  const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
+  const PackedDims dA(BITS, p.M, p.K), dW(BITS, p.N, p.K);
   const unsigned tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
   const unsigned kfrags = (unsigned)dA.kfrags;
   const unsigned per = (kfrags + KS - 1) / KS;
@@ -43,28 +49,42 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
   }
   const uint8_t* w_src = p.packedW + dW.frag_offset(tile_n, 0) + lane * 16;
 
-  v16i acc[TMW];
+  v16i acc[TMW][NACC];
 #pragma unroll
   for (int mt = 0; mt < TMW; ++mt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[mt][r] = 0;
+    for (int c = 0; c < NACC; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][c][r] = 0;
 
   for (unsigned kb0 = kb_begin; kb0 < kb_end; kb0 += KW) {
-    u4 fa[TMW][KW], fw[KW];
+    u4 fa[TMW][KW][NPL], fw[KW][NPL];
 #pragma unroll
     for (int j = 0; j < KW; ++j) {
       // a fragment past this wave's run is read from the run's last one (a valid address) and not used
       const unsigned kb = kb0 + j < kb_end ? kb0 + j : kb_end - 1;
-      fw[j] = *reinterpret_cast<const u4*>(w_src + (size_t)kb * kFragBytes);
 #pragma unroll
-      for (int mt = 0; mt < TMW; ++mt) fa[mt][j] = *reinterpret_cast<const u4*>(a_src[mt] + (size_t)kb * kFragBytes);
+      for (int pl = 0; pl < NPL; ++pl) {
+        fw[j][pl] = *reinterpret_cast<const u4*>(w_src + ((size_t)kb * NPL + pl) * kFragBytes);
+#pragma unroll
+        for (int mt = 0; mt < TMW; ++mt)
+          fa[mt][j][pl] = *reinterpret_cast<const u4*>(a_src[mt] + ((size_t)kb * NPL + pl) * kFragBytes);
+      }
     }
 #pragma unroll
     for (int j = 0; j < KW; ++j) {
       if (kb0 + j < kb_end) {
 #pragma unroll
-        for (int mt = 0; mt < TMW; ++mt)
-          acc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j]), as_v4i(fw[j]), acc[mt], 0, 0, 0);
+        for (int mt = 0; mt < TMW; ++mt) {
+          if constexpr (BITS == 8) {
+            acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j][0]), as_v4i(fw[j][0]), acc[mt][0], 0, 0, 0);
+          } else {
+            acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j][0]), as_v4i(fw[j][0]), acc[mt][0], 0, 0, 0);
+            acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j][0]), as_v4i(fw[j][1]), acc[mt][1], 0, 0, 0);
+            acc[mt][2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j][1]), as_v4i(fw[j][1]), acc[mt][2], 0, 0, 0);
+            acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(fa[mt][j][1]), as_v4i(fw[j][0]), acc[mt][1], 0, 0, 0);
+          }
+        }
       }
     }
   }
@@ -74,7 +94,11 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
 #pragma unroll
   for (int mt = 0; mt < TMW; ++mt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) mine[(mt * 16 + r) * 64 + lane] = acc[mt][r];
+    for (int r = 0; r < 16; ++r) {
+      unsigned v = (unsigned)acc[mt][0][r];
+      if constexpr (BITS == 16) v = (v << 16) + ((unsigned)acc[mt][1][r] << 8) + (unsigned)acc[mt][2][r];
+      mine[(mt * 16 + r) * 64 + lane] = (int)v;
+    }
   __syncthreads();
 
   // Every thread adds up KS partial sums for TMW * 1024 / (KS * 64) elements.  Its elements all have
@@ -98,6 +122,11 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
     const int mt = e / 1024, r = (e / 64) % 16;
     const unsigned m = (tile_m * TMW + mt) * 32 + 8 * (r / 4) + 4 * lh + r % 4;
     if (n_ok && m < p.M) {
+      if constexpr (BITS == 16) {
+        const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
+        const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
+        v += 128u * ((unsigned)rowsum[m] + (unsigned)colsum[n]) - 16384u * p.K;
+      }
       if (dequant) {
         float y = fmaf((float)(int)v, u, bias);
         if (p.relu) y = (y > 0.0f) ? y : 0.0f;
@@ -131,11 +160,11 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
   }
 }
 
-template <int TMW, int KS, int KW>
+template <int BITS, int TMW, int KS, int KW>
 int launch_small(const GemmArgs& a, int dequant, hipStream_t s) {
   constexpr size_t smem = (size_t)KS * TMW * 1024 * sizeof(int);
   static_assert(smem <= 128 * 1024, "LDS budget");
-  const PackedDims dA(8, a.M, a.K), dW(8, a.N, a.K);
+  const PackedDims dA(BITS, a.M, a.K), dW(BITS, a.N, a.K);
   Params p{};
   p.qA = static_cast<const uint8_t*>(a.qA);
   p.packedW = static_cast<const uint8_t*>(a.packedW);
@@ -146,7 +175,7 @@ int launch_small(const GemmArgs& a, int dequant, hipStream_t s) {
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
   p.partial = a.partial;
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
-  auto kern = k_gemm_small<TMW, KS, KW>;
+  auto kern = k_gemm_small<BITS, TMW, KS, KW>;
   static bool attr_done = false;
   if (!attr_done) {
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -359,16 +388,21 @@ int launch_small_f32(SmallF32Params p, hipStream_t s) {
   return check_hip(hipGetLastError());
 }
 
-template <int TMW>
+template <int BITS, int TMW>
 int launch_small_tmw(const GemmArgs& a, int dequant, size_t kfrags, hipStream_t s) {
   // one round of loads per wave where K allows: 4 waves up to K = 512, 8 up to 2048
-  if (kfrags <= 16) return launch_small<TMW, 4, 4>(a, dequant, s);
-  if (kfrags <= 32) return launch_small<TMW, 8, 4>(a, dequant, s);
-  if (kfrags <= 64) return launch_small<TMW, 8, 8>(a, dequant, s);
-  // 16 waves leave 128 registers per lane, too few for the two-row-block form: that one stays at 8 waves
-  // and takes several rounds
-  if constexpr (TMW == 2) return launch_small<2, 8, 8>(a, dequant, s);
-  else return launch_small<1, 16, 8>(a, dequant, s);
+  if (kfrags <= 16) return launch_small<BITS, TMW, 4, 4>(a, dequant, s);
+  if (kfrags <= 32) return launch_small<BITS, TMW, 8, 4>(a, dequant, s);
+  if constexpr (BITS == 16) {
+    // two byte planes and three accumulators per tile: four fragments per round, several rounds
+    return launch_small<16, TMW, 8, 4>(a, dequant, s);
+  } else {
+    if (kfrags <= 64) return launch_small<8, TMW, 8, 8>(a, dequant, s);
+    // 16 waves leave 128 registers per lane, too few for the two-row-block form: that one stays at 8 waves
+    // and takes several rounds
+    if constexpr (TMW == 2) return launch_small<8, 2, 8, 8>(a, dequant, s);
+    else return launch_small<8, 1, 16, 8>(a, dequant, s);
+  }
 }
 
 }  // namespace
@@ -386,15 +420,17 @@ size_t gemm_small_f32_partials(size_t M, size_t N, size_t K) {
   return rbs * (wide ? (dW.nblocks + 1) / 2 : dW.nblocks);
 }
 
-// Split-K product for few rows: 8-bit packed operands, raw sums or dequantize + bias (+ReLU) (+max|y|).
+// Split-K product for few rows: packed operands of either width, raw sums or dequantize + bias (+ReLU) (+max|y|).
 // Any shape is computed correctly; it is the fast choice when the result is small.
 int launch_gemm_small(const GemmArgs& a, Epilogue epi, hipStream_t s) {
-  if (a.bits != 8 || (epi != kEpiRaw && epi != kEpiDequant)) return MQ_ERR_UNSUPPORTED;
-  const PackedDims dA(8, a.M, a.K), dW(8, a.N, a.K);
+  if ((a.bits != 8 && a.bits != 16) || (epi != kEpiRaw && epi != kEpiDequant)) return MQ_ERR_UNSUPPORTED;
+  const PackedDims dA(a.bits, a.M, a.K), dW(a.bits, a.N, a.K);
   const int dequant = epi == kEpiDequant;
   // two row blocks per workgroup only when that still leaves a workgroup for every compute unit
   const bool wide = ((dA.nblocks + 1) / 2) * dW.nblocks >= 256;
-  return wide ? launch_small_tmw<2>(a, dequant, dA.kfrags, s) : launch_small_tmw<1>(a, dequant, dA.kfrags, s);
+  if (a.bits == 16)
+    return wide ? launch_small_tmw<16, 2>(a, dequant, dA.kfrags, s) : launch_small_tmw<16, 1>(a, dequant, dA.kfrags, s);
+  return wide ? launch_small_tmw<8, 2>(a, dequant, dA.kfrags, s) : launch_small_tmw<8, 1>(a, dequant, dA.kfrags, s);
 }
 
 // Whether quantizing inside the product pays: few rows, K short enough that re-reading the fp32 rows once

@@ -263,6 +263,33 @@ def test_mq_linear_f32_decode_sizes(M, N, K, relu, fixed):
         assert host(am)[0] == np.abs(want).max()
 
 
+def test_mq_linear_f32_decode_sizes_special_values():
+    # quant_int inside the product kernel: ties to even, clipping, infinities, NaN -> 0, an all-zero input
+    M, N, K = 40, 48, 64
+    rng = np.random.default_rng(4242)
+    A = rng.standard_normal((M, K), dtype=np.float32)
+    A[0, :8] = (np.arange(8, dtype=np.float32) + np.float32(0.5)) / np.float32(63.5)      # x * 63.5 = k + 0.5
+    A[1, :6] = [np.inf, -np.inf, np.nan, 1e30, -1e30, -0.0]
+    A[2, :] = 0.0
+    Wt = rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.05)
+    bias = rng.standard_normal(N, dtype=np.float32) * np.float32(0.1)
+    pw = mq.prepare_weight(dev(Wt), 8)
+    nbytes = mq.mq_linear_ws_bytes(8, M, K)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    sA = torch.full((1,), 63.5, dtype=torch.float32, device=DEV)
+    want = oracle.linear(A, Wt, 8, bias, False, sA=63.5)
+    mq.mq_linear_f32(dev(A), M, K, sA, pw.packed, pw.scale, 8, N, dev(bias), False, Y, None, ws, nbytes)
+    assert np.array_equal(host(Y), want["Y"])
+    Z = np.zeros((M, K), dtype=np.float32)                     # abs-max of zeros: multiplier 1, output = bias
+    mq.mq_linear_f32(dev(Z), M, K, None, pw.packed, pw.scale, 8, N, dev(bias), False, Y, None, ws, nbytes)
+    assert np.array_equal(host(Y), oracle.linear(Z, Wt, 8, bias, False)["Y"])
+    B = A.copy()
+    B[1, :6] = [3.0, -3.0, np.nan, 2.5, -2.5, -0.0]            # abs-max skips the NaN
+    mq.mq_linear_f32(dev(B), M, K, None, pw.packed, pw.scale, 8, N, dev(bias), False, Y, None, ws, nbytes)
+    assert np.array_equal(host(Y), oracle.linear(B, Wt, 8, bias, False)["Y"])
+
+
 # -------------------------------------------------------------------- arg-max
 
 def gpu_greedy(Hd, E, pw=None):
@@ -460,7 +487,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], 16: [0, 1, 2, 3, 4, 5]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], 16: [0, 1, 2, 3, 4, 5, 6]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
@@ -873,7 +900,7 @@ def test_autotune_freezes_a_variant_and_results_stay_identical():
     best16, _ = mq.mq_autotune_gemm(16, 64, 96, 128, 5, torch.empty(mq.mq_autotune_ws_bytes(16, 64, 96, 128),
                                                                       dtype=torch.uint8, device=DEV),
                                     mq.mq_autotune_ws_bytes(16, 64, 96, 128))
-    assert 1 <= best16 <= 5
+    assert 1 <= best16 <= 6
 
 
 # ------------------------------------------------ beam-search output layer
