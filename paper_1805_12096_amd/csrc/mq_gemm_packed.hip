@@ -75,8 +75,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   const int wave = tid / 64;
   const int wm = wave / WN, wn = wave % WN;
 #ifdef MQ_TS
-  if (EPI == kPCoop && tid == 0) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8] = wall_clock64();
+  // instrumented builds only: wall-clock stamps per workgroup, behind the barrier words (single-pass kernel)
+  // or behind the max|y| word (dequantizing kernel called with a large enough buffer there)
+#define MQ_STAMP(i) do { if (tid == 0) { \
+    if (EPI == kPCoop) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); \
+    else if (EPI == kPDequant && p.out_amax != nullptr) reinterpret_cast<unsigned long long*>(p.out_amax)[8 + blockIdx.x * 8 + (i)] = wall_clock64(); } } while (0)
+#else
+#define MQ_STAMP(i) do { } while (0)
 #endif
+  MQ_STAMP(0);
   unsigned tile_m, tile_n;
   tile_coords(p.tiles_m, p.tiles_n, BM >= 1024 ? 1u : 1024u / BM, tile_m, tile_n);
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
@@ -201,6 +208,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
     else wait_vmcnt(0);
     block_barrier();
+    MQ_STAMP(2);                  // first stage landed
 #pragma unroll
     for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
 
@@ -251,11 +259,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     wait_vmcnt(0);     // dummy loads of the tail must not outlive the stages' reuse in the epilogue
   }
 
-#ifdef MQ_TS
-#define MQ_STAMP(i) do { if (EPI == kPCoop && tid == 0) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define MQ_STAMP(i) do { } while (0)
-#endif
   MQ_STAMP(1);
   if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop) {
     static_assert(BITS == 8, "fused epilogues are 8 bit");
@@ -479,6 +482,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
     store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
         acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum);
+    MQ_STAMP(5);
   }
 }
 
