@@ -23,7 +23,9 @@ namespace mq {
 
 namespace {
 
-enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3, kPCoop = 4 };
+// kPCoopFast: kPCoop for the common case the launcher can see in advance -- ReLU on and no tile reaching past the
+// matrix -- where the re-quantization shrinks to one rounding addition per element (see the store below).
+enum PackedEpilogue { kPRaw = 0, kPDequant = 1, kPAmax = 2, kPRequant = 3, kPCoop = 4, kPCoopFast = 5 };
 
 // One element of quant_int (8 bit): binary32 multiply, round half to even, clamp, NaN -> 0.
 __device__ __forceinline__ int quant8(float x, float s) {
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   // instrumented builds only: wall-clock stamps per workgroup, behind the barrier words (single-pass kernel)
   // or behind the max|y| word (dequantizing kernel called with a large enough buffer there)
 #define MQ_STAMP(i) do { if (tid == 0) { \
-    if (EPI == kPCoop) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); \
+    if (EPI == kPCoop || EPI == kPCoopFast) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); \
     else if (EPI == kPDequant && p.out_amax != nullptr) reinterpret_cast<unsigned long long*>(p.out_amax)[8 + blockIdx.x * 8 + (i)] = wall_clock64(); } } while (0)
 #else
 #define MQ_STAMP(i) do { } while (0)
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     if constexpr (BITS == 8) {
       // the re-quantizing epilogue wants consecutive n in one lane (4 bytes = one store), i.e. the
       // parameter as operand `a`; everything else wants consecutive n across lanes
-      acc[mt][nt][0] = (EPI == kPRequant || EPI == kPCoop)
+      acc[mt][nt][0] = (EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast)
                            ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[nt][0], F.a[mt][0], acc[mt][nt][0], 0, 0, 0)
                            : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][0], F.b[nt][0], acc[mt][nt][0], 0, 0, 0);
     } else {
@@ -260,14 +262,17 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   }
 
   MQ_STAMP(1);
-  if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop) {
+  if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast) {
     static_assert(BITS == 8, "fused epilogues are 8 bit");
+    constexpr bool COOP = EPI == kPCoop || EPI == kPCoopFast;
+    constexpr bool FASTC = EPI == kPCoopFast;
+    const bool relu_on = FASTC || p.relu != 0;
     __shared__ float red[NW];
     const int lj = lane % 32, lh = lane / 32;
     const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
     const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
     // a tile with no row or column past the end needs no masking anywhere below
-    const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
+    const bool interior = FASTC || (m0 + BM <= p.M && n0 + BN <= p.N);
     constexpr bool SWAPPED = EPI != kPAmax;
     // bias[n] without a branch (a branch per element makes every load wait for the one before): the
     // index is clamped into the vector, and without a bias some readable address stands in
@@ -295,14 +300,14 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     // the conversion and the fused multiply-add round monotonically), so max|y| over the rows of a
     // column is reached at the largest or the smallest sum (whatever the sign of u): the rows are reduced as integers and the
     // float expression is evaluated once (with ReLU) or twice per column instead of once per element.
-    if constexpr (EPI == kPAmax || EPI == kPCoop) {
+    if constexpr (EPI == kPAmax || COOP) {
       float local = 0.f;
       // with ReLU and u > 0 only the largest sum of a column matters
-      const bool max_only = p.relu != 0 && u > 0.0f;
+      const bool max_only = relu_on && u > 0.0f;
       auto column = [&](int imax, int imin, unsigned n, float bias) {
         if (n < p.N && imax >= imin) {                       // imax < imin: no valid row in this lane
           const float hi = fmaf((float)imax, u, bias), lo = fmaf((float)imin, u, bias);
-          if (p.relu) local = fmaxf(local, fmaxf(hi, lo));   // max(relu(y)) = max(0, y at an extreme sum)
+          if (relu_on) local = fmaxf(local, fmaxf(hi, lo));   // max(relu(y)) = max(0, y at an extreme sum)
           else local = fmaxf(local, fmaxf(fabsf(hi), fabsf(lo)));
         }
       };
@@ -349,9 +354,14 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
             }
         }
       };
-      if (interior && max_only) reduce_rows(std::true_type{}, std::true_type{});
-      else if (interior) reduce_rows(std::true_type{}, std::false_type{});
-      else reduce_rows(std::false_type{}, std::false_type{});
+      if constexpr (FASTC) {
+        if (max_only) reduce_rows(std::true_type{}, std::true_type{});
+        else reduce_rows(std::true_type{}, std::false_type{});
+      } else {
+        if (interior && max_only) reduce_rows(std::true_type{}, std::true_type{});
+        else if (interior) reduce_rows(std::true_type{}, std::false_type{});
+        else reduce_rows(std::false_type{}, std::false_type{});
+      }
 #ifdef MQ_TS
       if (local == 12345.f) return;
       MQ_STAMP(7);
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 #pragma unroll
               for (int j = 0; j < 16; ++j) {
                 float y = fmaf((float)acc[mt][nt][0][j], u, biasv[SWAPPED ? nt : 0][j]);
-                if (p.relu) y = fmaxf(y, 0.0f);
+                if (relu_on) y = fmaxf(y, 0.0f);
                 acc[mt][nt][0][j] = __float_as_int(y);
               }
         };
@@ -403,7 +413,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 
     if constexpr (EPI != kPAmax) {
       float s2;
-      if constexpr (EPI == kPCoop) {
+      if constexpr (COOP) {
         const float amax = red[0];
         s2 = (amax > 0.0f) ? __fdiv_rn(127.0f, amax) : 1.0f;
       } else if (p.partial != nullptr) {
@@ -429,7 +439,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       const PackedDims dO(8, p.M, p.N);
       __syncthreads();                             // every wave is done reading the last stage
       uint8_t* scratch = smem + wave * kFragBytes;
-      const bool relu = p.relu != 0;
+      const bool relu = relu_on;
       auto store_tiles = [&](auto interior_tag) {
         constexpr bool INTERIOR = decltype(interior_tag)::value;
 #pragma unroll
@@ -444,7 +454,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
               for (int t = 0; t < 4; ++t) {
                 const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
                 float y;
-                if constexpr (EPI == kPCoop) {
+                if constexpr (COOP) {
                   y = __int_as_float(acc[mt][nt][0][4 * q + t]);    // converted while waiting for the maximum
                 } else {
                   y = fmaf((float)acc[mt][nt][0][4 * q + t], u, biasv[SWAPPED ? nt : 0][4 * q + t]);
@@ -468,10 +478,41 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
           }
         }
       };
-      if (interior) store_tiles(std::true_type{});
-      else store_tiles(std::false_type{});
+      // kPCoopFast: after ReLU every y lies in [0, max] (NaN became 0), and the multiplier is 127 / max rounded,
+      // so y s2 <= 127 (1 + 2^-23)^2 rounds to at most 127: no clamp can act and no NaN can arrive.  The
+      // conversion is then one addition: t + 1.5 * 2^23 rounds t to the nearest integer (ties to even: the
+      // adder's own rounding, the same as rint of the same t) and leaves it in the low mantissa bits, whose low
+      // byte is the quantized value; byte permutes gather four of them.  An infinite max gives s2 = 0 and
+      // products 0 or (inf * 0 =) NaN, whose low byte is 0 like the clamp-and-NaN rule's result.
+      auto store_tiles_fast = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < TN; ++nt) {
+#pragma unroll
+          for (int mt = 0; mt < TM; ++mt) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              uint32_t w[4];
+#pragma unroll
+              for (int t = 0; t < 4; ++t)
+                w[t] = __float_as_uint(__fadd_rn(__fmul_rn(__int_as_float(acc[mt][nt][0][4 * q + t]), s2), 12582912.0f));
+              const uint32_t word = __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0400u) | __builtin_amdgcn_perm(w[3], w[2], 0x04000c0cu);
+              *reinterpret_cast<uint32_t*>(scratch + (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh) = word;
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): the wave's own writes
+            const u4 v = *reinterpret_cast<const u4*>(scratch + lane * 16);
+            *reinterpret_cast<u4*>(p.packed_out + dO.frag_offset((wm0 + mt * 32) / 32, (wn0 + nt * 32) / 32) + lane * 16) = v;
+            __builtin_amdgcn_s_waitcnt(0xC07F);      // the read must finish before the next sub-tile overwrites
+          }
+        }
+      };
+      if constexpr (FASTC) {
+        store_tiles_fast();
+      } else {
+        if (interior) store_tiles(std::true_type{});
+        else store_tiles(std::false_type{});
+      }
       MQ_STAMP(5);
-      if constexpr (EPI == kPCoop) {
+      if constexpr (COOP) {
         if (blockIdx.x == 0 && tid == 0) {
           *p.s_out = grid_max_failed(p.barrier) ? __builtin_nanf("") : s2;
         }
@@ -603,8 +644,11 @@ int launch_coop(const GemmArgs& a, hipStream_t s) {
   p.barrier = a.barrier;
   p.barrier_ticks = barrier_timeout_ticks();
   if (a.barrier == nullptr) return MQ_ERR_NULL;
-  auto kern = k_gemm_pp<8, BM, BN, WM, WN, S, kPCoop>;
-  static int max_blocks = -1;       // workgroups the device can hold at once, asked once
+  // ReLU and no partial tile: the kernel whose re-quantization is one addition per element
+  const bool fast = a.relu != 0 && a.M % BM == 0 && a.N % BN == 0;
+  auto kern = fast ? k_gemm_pp<8, BM, BN, WM, WN, S, kPCoopFast> : k_gemm_pp<8, BM, BN, WM, WN, S, kPCoop>;
+  static int max_blocks_of[2] = {-1, -1};       // workgroups the device can hold at once, asked once per kernel
+  int& max_blocks = max_blocks_of[fast ? 1 : 0];
   if (max_blocks < 0) {
     int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));

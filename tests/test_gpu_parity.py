@@ -760,7 +760,7 @@ def test_two_pass_requantizing_product():
     assert torch.equal(out, ref.packed)
 
 
-@pytest.mark.parametrize("shape", [(1, 1, 1), (300, 520, 256), (1000, 1100, 128)])
+@pytest.mark.parametrize("shape", [(1, 1, 1), (300, 520, 256), (1000, 1100, 128), (512, 768, 192), (256, 256, 64)])
 def test_single_pass_requantizing_product(shape):
     # one pass over the operands, the sums waiting in registers while the grid agrees on max|y|;
     # called twice on one workspace (it clears its two words itself)
@@ -779,6 +779,31 @@ def test_single_pass_requantizing_product(shape):
         s2 = torch.empty(1, dtype=torch.float32, device=DEV)
         out = torch.full((mq.mq_packed_bytes(8, M, N),), 0x22, dtype=torch.uint8, device=DEV)
         mq.mq_gemm_requant_single_packed(pa, pw.packed, M, N, K, s, pw.scale, bias, True, ws, nb, s2, out)
+        assert host(s2)[0] == os2
+        assert torch.equal(out, ref.packed)
+
+
+@pytest.mark.parametrize("shape", [(512, 768, 192), (300, 520, 256)])
+def test_single_pass_requantizing_product_special_bias(shape):
+    # whole tiles + ReLU take the kernel whose re-quantization is a single rounding addition per element;
+    # a NaN bias (ReLU turns it into 0) and an infinite one (max = inf, multiplier 0, every output 0)
+    # must come out as the clamp-and-NaN rule gives them.  The second shape takes the general kernel.
+    M, N, K = shape
+    p = workloads.random_problem(911 + M, M, N, K)
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    pa, s = gpu_quantize_pack(p["A"], 8)
+    nb = mq.mq_gemm_amax_ws_bytes(M, N)
+    ws = torch.full((nb,), 0xA5, dtype=torch.uint8, device=DEV)
+    for special in (np.nan, np.inf):
+        bias = p["bias"].copy()
+        bias[N // 3] = special
+        o = oracle.linear(p["A"], p["Wt"], 8, bias, True)
+        os2 = oracle.scale_from_amax(oracle.absmax(o["Y"]), 8)
+        oq = oracle.quant_int(o["Y"], 8, os2)
+        ref = mq.prepare_weight(dev(oq.astype(np.float32)), 8, scale=torch.ones(1, dtype=torch.float32, device=DEV))
+        s2 = torch.empty(1, dtype=torch.float32, device=DEV)
+        out = torch.full((mq.mq_packed_bytes(8, M, N),), 0x22, dtype=torch.uint8, device=DEV)
+        mq.mq_gemm_requant_single_packed(pa, pw.packed, M, N, K, s, pw.scale, dev(bias), True, ws, nb, s2, out)
         assert host(s2)[0] == os2
         assert torch.equal(out, ref.packed)
 
