@@ -91,6 +91,10 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
   const PackedDims dA(BITS, p.M, p.K), dW(BITS, p.N, p.K);
   const unsigned KT = (unsigned)(dA.Kp / 64);
+  // the fused epilogues' dequantization factor: its two loads and the division are out of the way early
+  float u_early = 0.f;
+  if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast)
+    u_early = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
 
   // Source of this wave's j-th load of a stage: fragment i = wave * L + j of the
   // stage; fragments [0, FA) are A's, the rest the parameter's.  Row blocks past
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     const bool relu_on = FASTC || p.relu != 0;
     __shared__ float red[NW];
     const int lj = lane % 32, lh = lane / 32;
-    const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+    const float u = u_early;
     const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
     // a tile with no row or column past the end needs no masking anywhere below
     const bool interior = FASTC || (m0 + BM <= p.M && n0 + BN <= p.N);
