@@ -143,6 +143,8 @@ int launch_clear_words(unsigned* p, unsigned n, hipStream_t s);
 int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
                              hipStream_t s);
 int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
+// Tiled 8-bit product with two extra waves per workgroup that only load (mq_gemm_prod.hip); variants 11 .. 13.
+int launch_gemm_prod(const GemmArgs& a, Epilogue epi, int which, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
 int tuned_variant(int bits, size_t M, size_t N, size_t K);
 void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant);
