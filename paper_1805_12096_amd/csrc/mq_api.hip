@@ -730,14 +730,16 @@ namespace {
 // Scratch layout of mq_aan_layer_f32: quantizer partials, two multipliers, one packed 8-bit activation
 // buffer sized for the widest product input, and the float intermediates of the layer.
 struct AanWs {
-  size_t off_part, off_gpart, off_hpart, off_scal, off_q, off_hid, off_f, off_cat, off_z, off_y1, off_qv, off_ctx, off_o, off_y2, off_ff, total;
+  size_t off_part, off_gpart, off_xpart, off_hpart, off_hpart2, off_scal, off_q, off_hid, off_f, off_cat, off_z, off_y1, off_qv, off_ctx, off_o, off_y2, off_ff, total;
   AanWs(size_t M, size_t d, size_t ffn, size_t aan_ffn) {
     const size_t widest = ffn > aan_ffn ? (ffn > 2 * d ? ffn : 2 * d) : (aan_ffn > 2 * d ? aan_ffn : 2 * d);
     size_t o = 0;
     auto take = [&](size_t bytes) { const size_t at = o; o = round_up(o + bytes, 256); return at; };
     off_part = take(kAbsmaxPartials * sizeof(float));
     off_gpart = take((running_average_partials(M * d) > M ? running_average_partials(M * d) : M) * sizeof(float));
+    off_xpart = take(running_average_partials(M * d) * sizeof(float));
     off_hpart = take(kAbsmaxPartials * sizeof(float));
+    off_hpart2 = take(kAbsmaxPartials * sizeof(float));
     off_scal = take(256);
     off_q = take(PackedDims(8, M, widest).total_bytes());
     off_hid = take(M * (ffn > aan_ffn ? ffn : aan_ffn) * sizeof(float));
@@ -796,7 +798,10 @@ int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev,
         *qv = fbuf(L.off_qv), *ctx = fbuf(L.off_ctx), *o = fbuf(L.off_o), *y2 = fbuf(L.off_y2), *ff = fbuf(L.off_ff);
   float* gpart = reinterpret_cast<float*>(base + L.off_gpart);
   float* hpart = reinterpret_cast<float*>(base + L.off_hpart);
-  float* hmax = sA + 1;           // two words: max|hidden| of the two feed-forward networks, cleared by the first kernel
+  float* hpart2 = reinterpret_cast<float*>(base + L.off_hpart2);
+  float* xpart = reinterpret_cast<float*>(base + L.off_xpart);
+  float* hmax = sA + 1;           // three words: max|.| of three products' outputs where no per-workgroup maxima are
+                                  // available, cleared by the first kernel
   // One parameter product: quant_int of the input with its own abs-max multiplier, dot'_int, bias (+ReLU).
   // The kernel that produced the input has already left partial maxima of it (np of them at `partials`), so the
   // quantizer needs no abs-max pass of its own; inputs with more rows than the quantizer reduces per block take
@@ -805,7 +810,7 @@ int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev,
   const float* out_partials = nullptr;
   size_t out_np = 0;
   auto product = [&](const float* A, size_t Kdim, const mq_product& W, size_t N, int relu, float* Y,
-                     const float* partials, size_t np, bool want_max, float* hword) -> int {
+                     const float* partials, size_t np, bool want_max, float* hword, float* out_buf) -> int {
     int rc;
     GemmArgs g{};
     g.packedW = W.packed; g.bits = 8; g.M = M; g.N = N; g.K = Kdim;
@@ -815,7 +820,7 @@ int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev,
       // short K: quant_int inside the product's operand fetch, no quantizing launch
       if (want_max) {
         const size_t wg = gemm_small_f32_partials(M, N, Kdim);
-        if (wg <= kAbsmaxPartials) { g.partial = hpart; out_partials = hpart; out_np = wg; }
+        if (wg <= kAbsmaxPartials) { g.partial = out_buf; out_partials = out_buf; out_np = wg; }
         else { g.out_amax = hword; out_partials = hword; out_np = 1; }
       }
       return launch_gemm_small_f32(A, partials, (unsigned)np, sA, g, s);
@@ -826,36 +831,55 @@ int mq_aan_layer_f32(const mq_aan_layer* P, const float* x, const float* g_prev,
       rc = launch_absmax_quantize_pack(A, M, Kdim, 8, part, sA, qbuf, s);
     if (rc != MQ_OK) return rc;
     g.qA = qbuf; g.sA = sA;
+    if (want_max && M <= 512 && gemm_small_partials(M, N, Kdim) <= kAbsmaxPartials) {
+      // decode-sized: the split-K kernel leaves one maximum per workgroup
+      g.partial = out_buf; out_partials = out_buf; out_np = gemm_small_partials(M, N, Kdim);
+      return launch_gemm_small(g, kEpiDequant, s);
+    }
     if (want_max) { g.out_amax = hword; out_partials = hword; out_np = 1; }
     return launch_gemm_packed(g, kEpiDequant, s);
   };
   const size_t np_avg = running_average_partials(M * d);
-  int rc = launch_running_average(g_prev, x, M * d, t, g_out, s, gpart, reinterpret_cast<unsigned*>(hmax), 2);
+  int rc = launch_running_average(g_prev, x, M * d, t, g_out, s, gpart, reinterpret_cast<unsigned*>(hmax), 3, xpart);
   if (rc != MQ_OK) return rc;
   const float* fpath = g_out;
+  const float* fpart = gpart;     // partial maxima of |f|
+  size_t fnp = np_avg;
   if (use_ffn) {
-    if ((rc = product(g_out, d, P->aan_ffn1, aan_ffn, 1, hid, gpart, np_avg, true, hmax)) != MQ_OK) return rc;
+    if ((rc = product(g_out, d, P->aan_ffn1, aan_ffn, 1, hid, gpart, np_avg, true, hmax, hpart)) != MQ_OK) return rc;
     const float* hp = out_partials;
     const size_t hn = out_np;
-    if ((rc = product(hid, aan_ffn, P->aan_ffn2, d, 0, f, hp, hn, false, nullptr)) != MQ_OK) return rc;
+    if ((rc = product(hid, aan_ffn, P->aan_ffn2, d, 0, f, hp, hn, use_gate != 0, hmax + 2, hpart2)) != MQ_OK) return rc;
     fpath = f;
+    fpart = out_partials;
+    fnp = out_np;
   }
   if (use_gate) {
-    if ((rc = launch_concat2(x, d, fpath, d, M, cat, s, gpart)) != MQ_OK) return rc;
-    if ((rc = product(cat, 2 * d, P->aan_gate, 2 * d, 0, z, gpart, M, false, nullptr)) != MQ_OK) return rc;
+    GemmArgs gg{};
+    gg.packedW = P->aan_gate.packed; gg.bits = 8; gg.M = M; gg.N = 2 * d; gg.K = 2 * d;
+    gg.sW = P->aan_gate.scale; gg.bias = P->aan_gate.bias; gg.relu = 0; gg.Y = z;
+    if (gemm_small_f32_supported(M, 2 * d, 2 * d) && d % 4 == 0 && fpart != nullptr && fnp >= 1) {
+      // the gate's input [x, f] is read from its two pieces (with their partial maxima) inside the product
+      // kernel: the concatenation is never stored and its launch disappears
+      rc = launch_gemm_small_f32_pair(x, d, xpart, (unsigned)np_avg, fpath, fpart, (unsigned)fnp, sA, gg, s);
+      if (rc != MQ_OK) return rc;
+    } else {
+      if ((rc = launch_concat2(x, d, fpath, d, M, cat, s, gpart)) != MQ_OK) return rc;
+      if ((rc = product(cat, 2 * d, P->aan_gate, 2 * d, 0, z, gpart, M, false, nullptr, nullptr)) != MQ_OK) return rc;
+    }
     rc = launch_gate_mix_layer_norm(x, fpath, z, P->ln1.gamma, P->ln1.beta, M, d, eps, y1, s, gpart);
   } else {
     rc = launch_add_layer_norm(fpath, x, P->ln1.gamma, P->ln1.beta, M, d, eps, y1, s, gpart);
   }
   if (rc != MQ_OK) return rc;
-  if ((rc = product(y1, d, P->ctx_q, d, 0, qv, gpart, M, false, nullptr)) != MQ_OK) return rc;
+  if ((rc = product(y1, d, P->ctx_q, d, 0, qv, gpart, M, false, nullptr, nullptr)) != MQ_OK) return rc;
   if ((rc = launch_cross_attention(qv, K, V, M, S, d, heads, ctx, s, gpart)) != MQ_OK) return rc;
-  if ((rc = product(ctx, d, P->ctx_o, d, 0, o, gpart, M, false, nullptr)) != MQ_OK) return rc;
+  if ((rc = product(ctx, d, P->ctx_o, d, 0, o, gpart, M, false, nullptr, nullptr)) != MQ_OK) return rc;
   if ((rc = launch_add_layer_norm(o, y1, P->ln2.gamma, P->ln2.beta, M, d, eps, y2, s, gpart)) != MQ_OK) return rc;
-  if ((rc = product(y2, d, P->ffn1, ffn, 1, hid, gpart, M, true, hmax + 1)) != MQ_OK) return rc;
+  if ((rc = product(y2, d, P->ffn1, ffn, 1, hid, gpart, M, true, hmax + 1, hpart)) != MQ_OK) return rc;
   const float* hp2 = out_partials;
   const size_t hn2 = out_np;
-  if ((rc = product(hid, ffn, P->ffn2, d, 0, ff, hp2, hn2, false, nullptr)) != MQ_OK) return rc;
+  if ((rc = product(hid, ffn, P->ffn2, d, 0, ff, hp2, hn2, false, nullptr, nullptr)) != MQ_OK) return rc;
   return launch_add_layer_norm(ff, y2, P->ln3.gamma, P->ln3.beta, M, d, eps, y, s);
 }
 

@@ -195,9 +195,13 @@ int launch_small(const GemmArgs& a, int dequant, hipStream_t s) {
 // as the separate quantizer does).  Every column block of a row block repeats the conversion of that row
 // block; that is cheap next to a launch as long as K is short (the fp32 rows are four times the bytes).
 struct SmallF32Params {
-  const float* A;            // [M x K] fp32, K a multiple of 32, rows 16-byte aligned
+  const float* A;            // [M x K] fp32, K a multiple of 32, rows 16-byte aligned; with A2: [M x K1], columns 0 .. K1 - 1
+  const float* A2;           // optional second piece [M x (K - K1)]: columns K1 .. K - 1 of the input
+  unsigned K1;
   const float* scale;        // multiplier (npartial == 0) or partial maxima
   unsigned npartial;
+  const float* scale2;       // more partial maxima (the second piece's), npartial2 of them
+  unsigned npartial2;
   float* scale_out;          // receives the multiplier (workgroup 0)
   const uint8_t* packedW;
   unsigned M, N, K, tiles_n;
@@ -250,13 +254,14 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
   }
   // load i of a round: row 2 i + lane / 32 of the tile, floats 4 (lane % 32) .. + 3 of the round's 128
   // (rows past the end repeat the last one; their results are never stored)
-  const float* a_src[16];
+  unsigned a_row[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     unsigned row = tile_m * 32 + 2 * i + lh;
     if (row >= p.M) row = p.M - 1;
-    a_src[i] = p.A + (size_t)row * p.K + 4 * lj;
+    a_row[i] = row;
   }
+  const unsigned ld1 = p.A2 != nullptr ? p.K1 : p.K, ld2 = p.K - p.K1;
   // where this lane's four bytes of load i go: fragment lj / 8, K half (lj / 4) % 2, row 2 i + lh, byte 4 (lj % 4)
   uint8_t* st_dst = stage + (lj / 8) * kPitch + ((lj / 4) % 2) * kHalf + lh * 16 + 4 * (lj % 4);
 
@@ -271,9 +276,14 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
     }
     // a lane whose fragment lies past the run reads the run's last fragment instead (a valid address, unused)
     const unsigned kb = kb0 + lj / 8 < kb_end ? kb0 + lj / 8 : kb_end - 1;
-    const ptrdiff_t off = (ptrdiff_t)kb * 32 - (ptrdiff_t)(lj / 8) * 32;
+    const unsigned col = kb * 32 + 4 * (lj % 8);               // this lane's first column of the input
+    // two-piece input: the piece, its row stride and the column inside it (K1 is a multiple of 4, so a lane's
+    // four floats never straddle the pieces)
+    const bool second = p.A2 != nullptr && col >= p.K1;
+    const float* base = second ? p.A2 + (col - p.K1) : p.A + col;
+    const unsigned ld = second ? ld2 : ld1;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) fa[i] = *reinterpret_cast<const float4*>(a_src[i] + off);
+    for (int i = 0; i < 16; ++i) fa[i] = *reinterpret_cast<const float4*>(base + (size_t)a_row[i] * ld);
   };
   if (kb_begin < kb_end) fetch(kb_begin);        // the first round is on its way while the multiplier is formed
 
@@ -281,6 +291,7 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
   if (p.npartial != 0) {
     float m = 0.f;
     for (unsigned i = tid; i < p.npartial; i += KS * 64) m = fmaxf(m, p.scale[i]);
+    for (unsigned i = tid; i < p.npartial2; i += KS * 64) m = fmaxf(m, p.scale2[i]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
     if (lane == 0) red[wave] = m;
@@ -441,11 +452,9 @@ bool gemm_small_f32_supported(size_t M, size_t N, size_t K) {
 
 // quant_int(A) + dot'_int + dequantize + bias (+ReLU) (+max|y|) in one launch; see k_gemm_small_f32.
 // scale: the multiplier (npartial == 0) or npartial partial maxima of |A|.
-int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial, float* scale_out, const GemmArgs& a,
-                          hipStream_t s) {
+namespace {
+int launch_small_f32_any(SmallF32Params p, const GemmArgs& a, hipStream_t s) {
   if (!gemm_small_f32_supported(a.M, a.N, a.K) || a.bits != 8) return MQ_ERR_UNSUPPORTED;
-  SmallF32Params p{};
-  p.A = A; p.scale = scale; p.npartial = npartial; p.scale_out = scale_out;
   p.packedW = static_cast<const uint8_t*>(a.packedW);
   p.M = (unsigned)a.M; p.N = (unsigned)a.N; p.K = (unsigned)a.K;
   p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax; p.partial_out = a.partial;
@@ -460,6 +469,23 @@ int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial,
   }
   if (ksl <= 16) return launch_small_f32<1, 4>(p, s);
   return launch_small_f32<1, 8>(p, s);
+}
+}  // namespace
+
+int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial, float* scale_out, const GemmArgs& a,
+                          hipStream_t s) {
+  SmallF32Params p{};
+  p.A = A; p.scale = scale; p.npartial = npartial; p.scale_out = scale_out;
+  return launch_small_f32_any(p, a, s);
+}
+
+int launch_gemm_small_f32_pair(const float* A1, size_t K1, const float* part1, unsigned n1, const float* A2,
+                               const float* part2, unsigned n2, float* scale_out, const GemmArgs& a, hipStream_t s) {
+  if (K1 == 0 || K1 >= a.K || K1 % 4 != 0 || n1 == 0 || n2 == 0) return MQ_ERR_UNSUPPORTED;
+  SmallF32Params p{};
+  p.A = A1; p.A2 = A2; p.K1 = (unsigned)K1;
+  p.scale = part1; p.npartial = n1; p.scale2 = part2; p.npartial2 = n2; p.scale_out = scale_out;
+  return launch_small_f32_any(p, a, s);
 }
 
 }  // namespace mq

@@ -52,16 +52,19 @@ __device__ __forceinline__ void block_absmax_out(float v, float* red, float* __r
 __global__ __launch_bounds__(kT) void k_running_average(const float* __restrict__ g_prev, const float* __restrict__ x,
                                                         size_t n, float tm1, float t, float* __restrict__ g,
                                                         float* __restrict__ partial, unsigned* __restrict__ clear,
-                                                        unsigned nclear) {
+                                                        unsigned nclear, float* __restrict__ partial_x) {
   __shared__ float red[kT / kWave];
   const size_t i = (size_t)blockIdx.x * kT + threadIdx.x;
-  float v = 0.f;
+  float v = 0.f, xv = 0.f;
   if (i < n) {
-    v = __fdiv_rn(__fmaf_rn(tm1, g_prev[i], x[i]), t);
+    xv = x[i];
+    v = __fdiv_rn(__fmaf_rn(tm1, g_prev[i], xv), t);
     g[i] = v;
   }
   if (clear != nullptr && blockIdx.x == 0 && threadIdx.x < nclear) clear[threadIdx.x] = 0u;   // later kernels' maxima
   if (partial != nullptr) block_absmax_out(fabsf(v), red, partial);       // fmaxf drops NaN
+  // max|x| as well (the gate's product takes [x, f] as its input and needs the maximum of both halves)
+  if (partial_x != nullptr) block_absmax_out(fabsf(xv), red, partial_x);
 }
 
 __global__ __launch_bounds__(kT) void k_concat2(const float* __restrict__ a, unsigned da, const float* __restrict__ b,
@@ -335,11 +338,11 @@ __global__ __launch_bounds__(kTA) void k_cross_attention_fast(const float* __res
 size_t running_average_partials(size_t n) { return (n + kT - 1) / kT; }
 
 int launch_running_average(const float* g_prev, const float* x, size_t n, int t, float* g, hipStream_t s, float* partial,
-                           unsigned* clear, unsigned nclear) {
+                           unsigned* clear, unsigned nclear, float* partial_x) {
   const size_t blocks = (n + kT - 1) / kT;
   if (blocks > 0x7FFFFFFFull || nclear > (unsigned)kT) return MQ_ERR_SHAPE;
   hipLaunchKernelGGL(k_running_average, dim3((unsigned)blocks), dim3(kT), 0, s, g_prev, x, n, (float)(t - 1), (float)t, g,
-                     partial, clear, nclear);
+                     partial, clear, nclear, partial_x);
   return check_hip(hipGetLastError());
 }
 

@@ -96,6 +96,10 @@ size_t gemm_small_f32_partials(size_t M, size_t N, size_t K);
 bool gemm_small_f32_supported(size_t M, size_t N, size_t K);
 int launch_gemm_small_f32(const float* A, const float* scale, unsigned npartial, float* scale_out, const GemmArgs& a,
                           hipStream_t s);
+// The same for an input given as two row-major pieces side by side, [A1 (K1 columns) | A2 (a.K - K1 columns)], each with
+// partial maxima of its own (n1, n2 >= 1): the concatenation is never stored.  K1 must be a multiple of 4.
+int launch_gemm_small_f32_pair(const float* A1, size_t K1, const float* part1, unsigned n1, const float* A2,
+                               const float* part2, unsigned n2, float* scale_out, const GemmArgs& a, hipStream_t s);
 int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, const float* scale,
                          void* packed, hipStream_t s);
 int launch_argmax_init(unsigned long long* keys, size_t M, hipStream_t s);
@@ -130,7 +134,8 @@ int launch_topk_stream(const void* packedA, const void* packedW, size_t M, size_
 // max|output| per workgroup: running_average_partials(n) of them for the running average, M for the others.
 size_t running_average_partials(size_t n);
 int launch_running_average(const float* g_prev, const float* x, size_t n, int t, float* g, hipStream_t s,
-                           float* partial = nullptr, unsigned* clear = nullptr, unsigned nclear = 0);
+                           float* partial = nullptr, unsigned* clear = nullptr, unsigned nclear = 0,
+                           float* partial_x = nullptr);     // partial_x: the same number of maxima of |x|
 int launch_concat2(const float* a, size_t da, const float* b, size_t db, size_t M, float* out, hipStream_t s,
                    float* partial = nullptr);
 int launch_add_layer_norm(const float* a, const float* r, const float* gamma, const float* beta, size_t M, size_t d,
