@@ -548,6 +548,20 @@ def main():
                                   "kind": "oracle", "seconds": round(dt, 2),
                                   "sample": f"first {rows} of {w2.M} token rows of the same FFN workload, "
                                             "weights pre-quantized (memoized)"}
+        # the latency-bound configs on the oracle, all host threads and one thread (seconds per call)
+        nthr = oracle.num_threads()
+        c1o, c3o = workloads.config1(), workloads.config3()
+        side = {}
+        for label, n_ in (("all_threads", nthr), ("one_thread", 1)):
+            oracle.set_num_threads(n_)
+            t0 = time.perf_counter()
+            oracle.linear(c1o["A"], c1o["Wt"], 16, c1o["bias"], False)
+            t1 = time.perf_counter()
+            oracle.greedy_output_layer(c3o["Hd"], c3o["E"])
+            t2 = time.perf_counter()
+            side[label] = {"config1_int16_product_s": round(t1 - t0, 4), "config3_output_layer_s": round(t2 - t1, 3)}
+        oracle.set_num_threads(nthr)
+        result["cpu_baseline"]["other_configs"] = side
         if not args.no_parity:
             result["cpu_baseline"]["parity"] = parity_report(mq, torch, dev, to_dev, oracle)
     print(json.dumps(result))
