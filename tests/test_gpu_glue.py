@@ -128,9 +128,13 @@ def assert_chained_close(got, want, what, max_rows_off):
 @pytest.mark.parametrize("use_ffn,use_gate", [(True, True), (False, True), (False, False), (True, False)])
 @pytest.mark.parametrize("shape", [dict(M=6, d=32, ffn=64, aan_ffn=48, S=4, heads=4),
                                    dict(M=300, d=512, ffn=2048, aan_ffn=2048, S=25, heads=8),
-                                   dict(M=130, d=512, ffn=2048, aan_ffn=512, S=25, heads=8)])
+                                   dict(M=130, d=512, ffn=2048, aan_ffn=512, S=25, heads=8),
+                                   dict(M=40, d=1024, ffn=160, aan_ffn=96, S=5, heads=16),
+                                   dict(M=24, d=48, ffn=40, aan_ffn=72, S=3, heads=4)])
 def test_decoder_layer_matches_oracle(shape, use_ffn, use_gate):
-    # the last shape is the paper's own averaging block (inner width = model width, Section 3.2)
+    # the third shape is the paper's own averaging block (inner width = model width, Section 3.2); the fourth has a
+    # gate input wider than the in-kernel quantizer takes (concatenated copy + separate quantizer), the fifth has
+    # widths that are no multiples of 32 (no product of it quantizes in the kernel)
     c = workloads.config5_chained(M=shape["M"], layers=1, d=shape["d"], ffn=shape["ffn"], aan_ffn=shape["aan_ffn"],
                                   S=shape["S"], V=8, t=20, seed_extra=shape["M"])
     P, (K, V) = c["layers"][0], c["KV"][0]
