@@ -146,6 +146,62 @@ def test_decoder_layer_matches_oracle(shape, use_ffn, use_gate):
     assert_chained_close(host(y), want_y, "layer output", 0.10)
 
 
+def test_decoder_layer_and_output_layer_replayed_as_a_graph():
+    # the launch configuration of bench.py's chained decode step: layers and the greedy output layer in one HIP
+    # graph.  Every replay (other inputs, refilled workspaces, eager work in between) must give the eager bits.
+    c = workloads.config5_chained(M=300, layers=2, V=5000)
+    layers = [prepare_layer(P, 512, 2048, 2048) for P in c["layers"]]
+    KV = [(dev(k), dev(v)) for k, v in c["KV"]]
+    gp = [dev(g) for g in c["g_prev"]]
+    gn = [torch.empty_like(g) for g in gp]
+    M, d, V = 300, 512, 5000
+    xs = [dev(c["x0"])] + [torch.empty((M, d), dtype=torch.float32, device=DEV) for _ in layers]
+    nwl = mq.mq_aan_layer_ws_bytes(M, d, 2048, 2048)
+    wsl = torch.full((nwl,), 0x11, dtype=torch.uint8, device=DEV)
+    pe = mq.prepare_weight(dev(c["E"]), 8)
+    qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=DEV)
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    qn = mq.mq_quantize_absmax_ws_bytes()
+    qws = torch.empty(qn, dtype=torch.uint8, device=DEV)
+    nws = mq.mq_argmax_ws_bytes(M, V)
+    ws = torch.empty(nws, dtype=torch.uint8, device=DEV)
+    tok = torch.empty(M, dtype=torch.int32, device=DEV)
+    val = torch.empty(M, dtype=torch.float32, device=DEV)
+
+    def step():
+        for l, layer in enumerate(layers):
+            mq.mq_aan_layer_f32(layer, xs[l], gp[l], c["t"], KV[l][0], KV[l][1], M, 25, c["heads"], True, True,
+                                glue.LN_EPS, xs[l + 1], gn[l], wsl, nwl)
+        mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, qn)
+        mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+        step()
+    x0 = dev(c["x0"])
+    for r, factor in enumerate((1.0, -0.75, 2.0)):
+        xs[0].copy_(x0 * factor)
+        step()
+        torch.cuda.synchronize()
+        want = (xs[-1].clone(), tok.clone(), val.clone(), gn[0].clone())
+        for t_ in (xs[-1], val, gn[0]):
+            t_.fill_(float("nan"))
+        tok.fill_(-1)
+        wsl.fill_(0x40 + r)
+        ws.fill_(0x50 + r)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xs[-1], want[0]) and torch.equal(tok, want[1]) and torch.equal(val, want[2]), f"replay {r}"
+        assert torch.equal(gn[0], want[3])
+
+
 def test_full_decode_step_matches_oracle():
     # Six layers with their real dependencies, then the tied output layer with greedy arg-max.
     # Per-tensor abs-max multipliers make a free-running chain sensitive: once a rounding flip reaches the

@@ -688,6 +688,59 @@ def test_ffn_fused_full_size_equals_unfused_and_sampled_oracle():
     assert np.array_equal(Yf[rows], o2["Y"])
 
 
+def capture_graph(fn, reps):
+    """HIP graph of `reps` consecutive calls of fn, captured the way bench.py does it."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            fn()
+    return g
+
+
+def test_ffn_block_replayed_as_a_graph_of_several_steps():
+    # the launch configuration bench.py times: graphs of consecutive mq_ffn_i8_f32 calls at config 2's size.
+    # Every replay (with eager work of the program's own and synchronizations in between, and a different input
+    # each time) must give the eager call's bits; the eager result is pinned to the oracle on sampled rows.
+    c = workloads.config2()
+    M, d = c["A"].shape
+    f = c["W1t"].shape[0]
+    p1 = mq.prepare_weight(dev(c["W1t"]), 8)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 8)
+    b1, b2 = dev(c["b1"]), dev(c["b2"])
+    nbytes = mq.mq_ffn_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device=DEV)
+    A = dev(c["A"])
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+
+    def step():
+        mq.mq_ffn_i8_f32(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws, nbytes)
+
+    g = capture_graph(step, 3)
+    base = dev(c["A"])
+    for r, factor in enumerate((1.0, 0.5, -1.25, 1.0)):
+        A.copy_(base * factor)                       # eager work between the replays
+        step()
+        torch.cuda.synchronize()
+        want = Y.clone()
+        Y.fill_(float("nan"))
+        ws.fill_(0xA7 + r)                           # the workspace's contents must not matter either
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want), f"replay {r}"
+    sA = oracle.scale_from_amax(oracle.absmax(c["A"]), 8)
+    rows = np.r_[0:8, 4096:4104, 8184:8192]
+    o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+    _, o2 = oracle_ffn_rows(c, 8, rows, sA, s2)
+    assert np.array_equal(host(Y)[rows], o2["Y"])
+
+
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (300, 2048), (2000, 1024), (8192, 512), (70, 1030),
                                    (17000, 96)])
