@@ -263,6 +263,39 @@ def test_mq_linear_f32_decode_sizes(M, N, K, relu, fixed):
         assert host(am)[0] == np.abs(want).max()
 
 
+def test_decode_sized_products_random_shapes():
+    # seeded random shapes (rows <= 512, any width, K a multiple of 32 up to 1024): the in-kernel quantizer through
+    # mq_linear_f32, and the split-K / loader-wave kernels forced through the packed entry point, against the oracle
+    rng = np.random.default_rng(20241127)
+    qws = torch.empty(mq.mq_quantize_absmax_ws_bytes(), dtype=torch.uint8, device=DEV)
+    try:
+        for it in range(12):
+            M, N, K = int(rng.integers(1, 513)), int(rng.integers(1, 2500)), int(rng.integers(1, 33)) * 32
+            relu, fixed = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+            p = workloads.random_problem(1000 + it, M, N, K)
+            A = np.clip(p["A"], -2, 2) if fixed else p["A"]
+            o = oracle.linear(A, p["Wt"], 8, p["bias"], relu, sA=63.5 if fixed else None)
+            pw = mq.prepare_weight(dev(p["Wt"]), 8)
+            nb = mq.mq_linear_ws_bytes(8, M, K)
+            ws = torch.full((nb,), 0x77, dtype=torch.uint8, device=DEV)
+            Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+            am = torch.zeros(1, dtype=torch.float32, device=DEV)
+            sA = torch.full((1,), 63.5, dtype=torch.float32, device=DEV) if fixed else None
+            mq.mq_linear_f32(dev(A), M, K, sA, pw.packed, pw.scale, 8, N, dev(p["bias"]), relu, Y, am, ws, nb)
+            assert np.array_equal(host(Y), o["Y"]), (M, N, K, relu, fixed)
+            assert host(am)[0] == np.abs(o["Y"]).max()
+            q = torch.empty(mq.mq_packed_bytes(8, M, K), dtype=torch.uint8, device=DEV)
+            s = torch.empty(1, dtype=torch.float32, device=DEV)
+            mq.mq_quantize_absmax_pack_f32(dev(p["A"]), M, K, 8, q, s, qws, qws.numel())
+            o2 = oracle.linear(p["A"], p["Wt"], 8, p["bias"], relu)
+            for v in (10, 11, 12, 13):
+                mq.mq_set_gemm_variant(v)
+                mq.mq_gemm_dequant_packed(q, pw.packed, 8, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, None)
+                assert np.array_equal(host(Y), o2["Y"]), (M, N, K, relu, v)
+    finally:
+        mq.mq_set_gemm_variant(0)
+
+
 def test_mq_linear_f32_decode_sizes_special_values():
     # quant_int inside the product kernel: ties to even, clipping, infinities, NaN -> 0, an all-zero input
     M, N, K = 40, 48, 64
