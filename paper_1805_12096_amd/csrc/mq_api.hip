@@ -353,9 +353,10 @@ int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws,
   void* pw = base + a_bytes;
   float* Y = reinterpret_cast<float*>(base + a_bytes + w_bytes);
   float* scal = reinterpret_cast<float*>(base + a_bytes + w_bytes + round_up(M * N * sizeof(float), 256));
-  // operand bytes only need to be valid memory; give them a fixed non-trivial pattern and unit multipliers
-  int rc = check_hip(hipMemsetAsync(pa, 0x35, a_bytes, s));
-  if (rc == MQ_OK) rc = check_hip(hipMemsetAsync(pw, 0xC7, w_bytes, s));
+  // operand bytes only need to be valid memory; pseudo-random ones make the matrix units draw the power (and
+  // hold the clock) they do on real data, which constant bytes do not; unit multipliers
+  int rc = launch_fill_pattern(pa, a_bytes, 0x35u, s);
+  if (rc == MQ_OK) rc = launch_fill_pattern(pw, w_bytes, 0xC7u, s);
   const float ones[2] = {1.0f, 1.0f};
   if (rc == MQ_OK) rc = check_hip(hipMemcpyAsync(scal, ones, sizeof ones, hipMemcpyHostToDevice, s));
   if (rc != MQ_OK) return rc;

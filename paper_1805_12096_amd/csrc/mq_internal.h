@@ -145,6 +145,7 @@ int launch_gate_mix_layer_norm(const float* x, const float* f, const float* z, c
 int launch_cross_attention(const float* q, const float* K, const float* V, size_t M, size_t S, size_t d, int heads,
                            float* ctx, hipStream_t s, float* partial = nullptr);
 int launch_clear_words(unsigned* p, unsigned n, hipStream_t s);
+int launch_fill_pattern(void* p, size_t bytes, unsigned seed, hipStream_t s);     // pseudo-random bytes (timing runs)
 int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
                              hipStream_t s);
 int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);

@@ -23,6 +23,17 @@ __device__ __forceinline__ int wave_sum(int v) {
 }
 
 __global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
+// Pseudo-random bytes (a hash of the word index): operand contents for timing runs.  The matrix units draw more
+// power on varied operands than on constant ones and clock lower, so constant fill ranks tile variants wrongly.
+__global__ void k_fill_pattern(uint32_t* p, size_t nwords, uint32_t seed) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += stride) {
+    uint32_t x = (uint32_t)i * 2654435761u + seed;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13; x *= 3266489917u; x ^= x >> 16;
+    p[i] = x;
+  }
+}
+
 __global__ void k_clear_words(uint32_t* p, unsigned n) {
   for (unsigned i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
 }
@@ -476,6 +487,14 @@ int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, con
     if (vec) hipLaunchKernelGGL((k_quantize_pack<16, true, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
     else hipLaunchKernelGGL((k_quantize_pack<16, false, false>), dim3(grid), dim3(kThreads), 0, s, x, rows, cols, scale, p, ksplit, 0u, none);
   }
+  return check_hip(hipGetLastError());
+}
+
+int launch_fill_pattern(void* p, size_t bytes, unsigned seed, hipStream_t s) {
+  const size_t nwords = bytes / 4;
+  if (nwords == 0) return MQ_OK;
+  const unsigned grid = grid_for(nwords, 256 * 8, 2048);
+  hipLaunchKernelGGL(k_fill_pattern, dim3(grid), dim3(256), 0, s, static_cast<uint32_t*>(p), nwords, seed);
   return check_hip(hipGetLastError());
 }
 
