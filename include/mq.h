@@ -231,6 +231,16 @@ int mq_gemm_requant_fixed_packed(const void* packedA, const void* packedW, size_
                                  const float* sA, const float* sW, const float* bias, int relu,
                                  const float* s_out, void* packed_out, void* stream);
 
+/* The same for 16-bit operands (Section 4.2: 16-bit values with the fixed
+ * multiplier 2^10): both operands packed 16 bit, the result
+ * quant_int(relu?(A Bt / (sA sW) + bias), s_out[0]) saturated to +-32767 and
+ * written as packed 16-bit activations [M x N] (mq_packed_bytes(16, M, N)
+ * bytes: both byte planes and the row sums the next product needs; the row
+ * sums are cleared and accumulated here).  Two launches, no workspace. */
+int mq_gemm_requant_fixed_packed_i16(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                     const float* sA, const float* sW, const float* bias, int relu,
+                                     const float* s_out, void* packed_out, void* stream);
+
 /* ---- auto-tuning (Section 4.4) ------------------------------------------
  * The paper times alternative implementations per tensor shape over a fixed
  * number of runs and then uses the fastest for all following calls.  Here the

@@ -21,7 +21,8 @@ __all__ = [
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
     "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
-    "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_autotune_ws_bytes", "mq_autotune_gemm",
+    "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_gemm_requant_fixed_packed_i16",
+    "mq_autotune_ws_bytes", "mq_autotune_gemm",
     "mq_topk_ws_bytes", "mq_gemm_topk_packed",
     "mq_running_average_f32", "mq_concat2_f32", "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32",
     "mq_cross_attention_f32", "mq_aan_layer_ws_bytes", "mq_aan_layer_f32", "AanLayer", "aan_layer",
@@ -58,6 +59,7 @@ def exported_symbols():
             "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
+            "mq_gemm_requant_fixed_packed_i16",
             "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_topk_ws_bytes", "mq_gemm_topk_packed", "mq_running_average_f32", "mq_concat2_f32",
             "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32", "mq_cross_attention_f32",
             "mq_aan_layer_ws_bytes", "mq_aan_layer_f32"]
@@ -121,6 +123,7 @@ def load_library():
     lib.mq_gemm_requant_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp, vp, vp]
     lib.mq_gemm_requant_single_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp, vp, vp]
     lib.mq_gemm_requant_fixed_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, vp, vp]
+    lib.mq_gemm_requant_fixed_packed_i16.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, vp, vp]
     lib.mq_autotune_ws_bytes.restype = sz
     lib.mq_autotune_ws_bytes.argtypes = [ci, sz, sz, sz]
     lib.mq_autotune_gemm.argtypes = [ci, sz, sz, sz, ci, vp, sz, vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
@@ -316,6 +319,13 @@ def mq_gemm_requant_fixed_packed(packedA, packedW, M, N, K, sA, sW, bias, relu, 
     _check(load_library().mq_gemm_requant_fixed_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(bias),
                                                        int(relu), _p(s_out), _p(packed_out), _stream(stream)),
            "mq_gemm_requant_fixed_packed")
+
+
+def mq_gemm_requant_fixed_packed_i16(packedA, packedW, M, N, K, sA, sW, bias, relu, s_out, packed_out, stream=None):
+    _check(load_library().mq_gemm_requant_fixed_packed_i16(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW),
+                                                           _p(bias), int(relu), _p(s_out), _p(packed_out),
+                                                           _stream(stream)),
+           "mq_gemm_requant_fixed_packed_i16")
 
 
 def mq_autotune_ws_bytes(bits, M, N, K) -> int:

@@ -332,6 +332,23 @@ int mq_gemm_requant_fixed_packed(const void* packedA, const void* packedW, size_
   return launch_gemm_requant_fixed(a, s_out, packed_out, as_stream(stream));
 }
 
+int mq_gemm_requant_fixed_packed_i16(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                     const float* sA, const float* sW, const float* bias, int relu,
+                                     const float* s_out, void* packed_out, void* stream) {
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || s_out == nullptr ||
+      packed_out == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(s_out, 4) ||
+      !aligned(packed_out, 16))
+    return MQ_ERR_ALIGN;
+  if (bias != nullptr && !aligned(bias, 4)) return MQ_ERR_ALIGN;
+  GemmArgs a{};
+  a.qA = packedA; a.packedW = packedW; a.bits = 16; a.M = M; a.N = N; a.K = K;
+  a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
+  return launch_gemm_requant_fixed_i16(a, s_out, packed_out, as_stream(stream));
+}
+
 size_t mq_autotune_ws_bytes(int bits, size_t M, size_t N, size_t K) {
   if (!bits_ok(bits) || !dims_ok(M, N, K)) return 0;
   return round_up(PackedDims(bits, M, K).total_bytes(), 256) + round_up(PackedDims(bits, N, K).total_bytes(), 256) +

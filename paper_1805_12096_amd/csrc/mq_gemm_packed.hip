@@ -183,7 +183,10 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       const int pa = (pr == 0 || pr == 1) ? 0 : NPL - 1;          // hh, hl, lh, ll
       const int pb = (pr == 0 || pr == 2) ? 0 : NPL - 1;
       const int ai = pr == 0 ? 0 : (pr == 3 ? NACC - 1 : NACC - 2);
-      acc[mt][nt][ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][pa], F.b[nt][pb], acc[mt][nt][ai], 0, 0, 0);
+      // the re-quantizing epilogue wants four consecutive n of one row in a lane: parameter as operand `a`
+      acc[mt][nt][ai] = EPI == kPRequant
+                            ? __builtin_amdgcn_mfma_i32_32x32x32_i8(F.b[nt][pb], F.a[mt][pa], acc[mt][nt][ai], 0, 0, 0)
+                            : __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][pa], F.b[nt][pb], acc[mt][nt][ai], 0, 0, 0);
     }
   };
   // Multiply one slice out of `cur` while the reads of the next slice fill `nxt`:
@@ -266,7 +269,72 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   }
 
   MQ_STAMP(1);
-  if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast) {
+  if constexpr (EPI == kPRequant && BITS == 16) {
+    // 16-bit product re-quantized with a multiplier known in advance (the paper's 16-bit scheme, Section 4.2:
+    // one fixed multiplier): y = relu?(fma(float(sum), u, bias[n])), q = clamp(rne(y s), +-32767), written as the
+    // packed 16-bit activations of the next product -- high-byte plane, low-byte plane, and sum_n q per row
+    // (added up over the tile columns with one atomic per row and wave; the caller's launcher zeroes them).
+    // Operands were swapped: register r of lane l is (n, m) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32).
+    const int lj = lane % 32, lh = lane / 32;
+    const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+    const float s2 = *p.s_out;
+    const bool relu = p.relu != 0;
+    const bool has_bias = p.bias != nullptr;
+    const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
+    const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
+    const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
+    const PackedDims dO(16, p.M, p.N);
+    int32_t* rowsum_out = reinterpret_cast<int32_t*>(p.packed_out + dO.plane_bytes());
+    __syncthreads();                               // every wave is done reading the last stage
+    uint8_t* scratch = smem + wave * 2 * kFragBytes;     // one sub-tile's two planes
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+      const unsigned m = wm0 + mt * 32 + lj;
+      const bool m_ok = m < p.M;
+      const unsigned corr_m = 128u * (unsigned)rowsum[m_ok ? m : p.M - 1] - 16384u * p.K;
+      int rowacc = 0;
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint32_t hi = 0, lo = 0;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int r = 4 * q + t;
+            const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
+            const unsigned nc = n < p.N ? n : p.N - 1;
+            const unsigned v = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
+                               (unsigned)acc[mt][nt][NACC - 1][r] + corr_m + 128u * (unsigned)colsum[nc];
+            float y = fmaf((float)(int)v, u, has_bias ? p.bias[nc] : 0.0f);
+            if (relu) y = fmaxf(y, 0.0f);                       // NaN -> 0 like (y > 0) ? y : 0
+            const float rr = rintf(__fmul_rn(y, s2));
+            int qi;
+            asm("v_cvt_i32_f32 %0, %1" : "=v"(qi) : "v"(rr));   // saturates, NaN -> 0
+            qi = min(max(qi, -32767), 32767);
+            if (!(m_ok && n < p.N)) qi = 0;                     // padding is the value 0, as the quantizer writes it
+            rowacc += qi;
+            hi |= (uint32_t)((qi >> 8) & 0xFF) << (8 * t);
+            lo |= (uint32_t)((qi & 0xFF) ^ 0x80) << (8 * t);
+          }
+          const unsigned at = (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh;
+          *reinterpret_cast<uint32_t*>(scratch + at) = hi;
+          *reinterpret_cast<uint32_t*>(scratch + kFragBytes + at) = lo;
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the wave's own writes
+        const u4 vh = *reinterpret_cast<const u4*>(scratch + lane * 16);
+        const u4 vl = *reinterpret_cast<const u4*>(scratch + kFragBytes + lane * 16);
+        const unsigned mrow = wm0 + mt * 32, ncol = wn0 + nt * 32;
+        if (mrow < dO.Np && ncol < dO.Kp) {
+          uint8_t* dst = p.packed_out + dO.frag_offset(mrow / 32, ncol / 32) + lane * 16;
+          *reinterpret_cast<u4*>(dst) = vh;
+          *reinterpret_cast<u4*>(dst + kFragBytes) = vl;
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // the reads must finish before the next sub-tile overwrites
+      }
+      rowacc += __shfl_xor(rowacc, 32, 64);
+      if (lh == 0 && m_ok) atomicAdd(&rowsum_out[m], rowacc);
+    }
+  } else if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast) {
     static_assert(BITS == 8, "fused epilogues are 8 bit");
     constexpr bool COOP = EPI == kPCoop || EPI == kPCoopFast;
     constexpr bool FASTC = EPI == kPCoopFast;
@@ -692,6 +760,19 @@ int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* pac
   b.s_out = const_cast<float*>(s_fixed);
   b.packed_out = packed_out;
   return launch_pp_variant<8, kPRequant>(b, fused_variant(a), s);
+}
+
+// 16-bit product re-quantized with a fixed multiplier into packed 16-bit activations (planes + row sums).
+// The row sums are accumulated with atomics: they are zeroed here by a small launch first.
+int launch_gemm_requant_fixed_i16(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s) {
+  const PackedDims dO(16, a.M, a.N);
+  int rc = launch_clear_words(reinterpret_cast<unsigned*>(static_cast<uint8_t*>(packed_out) + dO.plane_bytes()),
+                              (unsigned)dO.Np, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs b = a;
+  b.s_out = const_cast<float*>(s_fixed);
+  b.packed_out = packed_out;
+  return launch_pp<16, 128, 128, 4, 2, 4, kPRequant>(b, s);
 }
 
 int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {

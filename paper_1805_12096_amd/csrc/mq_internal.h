@@ -149,6 +149,7 @@ int launch_fill_pattern(void* p, size_t bytes, unsigned seed, hipStream_t s);   
 int launch_gemm_requant_coop(const GemmArgs& a, float* s_out, void* packed_out, unsigned* barrier,
                              hipStream_t s);
 int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
+int launch_gemm_requant_fixed_i16(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
 // Tiled 8-bit product with two extra waves per workgroup that only load (mq_gemm_prod.hip); variants 11 .. 13.
 int launch_gemm_prod(const GemmArgs& a, Epilogue epi, int which, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.

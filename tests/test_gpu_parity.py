@@ -967,6 +967,35 @@ def test_greedy_shortlist_ties_and_frequent_plus_translations_shape():
 
 # ---------------------------------- fixed multipliers (the paper's scheme) and auto-tuning
 
+@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (300, 256, 520), (130, 96, 1000)])
+def test_ffn_int16_with_the_fixed_multiplier(M, d, f):
+    # the paper's 16-bit scheme (Section 4.2): every tensor multiplied by 2^10; the first product writes the
+    # second one's input as packed 16-bit activations (byte planes + row sums) from its epilogue
+    c = workloads.ffn(4, M, d, f, 0.03, 16, seed_extra=M + d + 7 * f)
+    S = np.float32(1024.0)
+    o1 = oracle.linear(c["A"], c["W1t"], 16, c["b1"], True, sA=S, sW=S)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 16, c["b2"], False, sA=S, sW=S)
+    assert o1["overflow_count"] == 0 and o2["overflow_count"] == 0
+    sc = torch.full((1,), 1024.0, dtype=torch.float32, device=DEV)
+    p1 = mq.prepare_weight(dev(c["W1t"]), 16, scale=sc)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 16, scale=sc)
+    qA = torch.empty(mq.mq_packed_bytes(16, M, d), dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_pack_f32(dev(c["A"]), M, d, 16, sc, qA)
+    for _ in range(2):                                            # the row sums are cleared by the call itself
+        qH = torch.full((mq.mq_packed_bytes(16, M, f),), 0x5D, dtype=torch.uint8, device=DEV)
+        mq.mq_gemm_requant_fixed_packed_i16(qA, p1.packed, M, f, d, sc, sc, dev(c["b1"]), True, sc, qH)
+        # identical bytes to the quantizer's packing of the oracle's intermediate (planes, padding, row sums)
+        ref = torch.empty_like(qH)
+        mq.mq_quantize_pack_f32(dev(o1["Y"]), M, f, 16, sc, ref)
+        assert torch.equal(qH, ref)
+        q = torch.empty((M, f), dtype=torch.int16, device=DEV)
+        mq.mq_unpack_weight(qH, 16, M, f, q)
+        assert np.array_equal(host(q), o2["qA"])
+        Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+        mq.mq_gemm_dequant_packed(qH, p2.packed, 16, M, d, f, sc, sc, dev(c["b2"]), False, Y, None)
+        assert np.array_equal(host(Y), o2["Y"])
+
+
 def test_ffn_with_fixed_multipliers_single_pass():
     # Section 4.2: 8-bit inputs clipped to [-2, 2] and scaled by 127/2; no abs-max anywhere.  The
     # intermediate is quantized in the epilogue of the product that creates it.
