@@ -42,7 +42,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 #define MQ_CASE(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | 0x0F70); break;
     MQ_CASE(0) MQ_CASE(1) MQ_CASE(2) MQ_CASE(3) MQ_CASE(4) MQ_CASE(5) MQ_CASE(6) MQ_CASE(7) MQ_CASE(8)
     MQ_CASE(9) MQ_CASE(10) MQ_CASE(11) MQ_CASE(12) MQ_CASE(13) MQ_CASE(14) MQ_CASE(15) MQ_CASE(16)
-    MQ_CASE(18) MQ_CASE(20) MQ_CASE(24)
+    MQ_CASE(17) MQ_CASE(18) MQ_CASE(19) MQ_CASE(20) MQ_CASE(21) MQ_CASE(22) MQ_CASE(23) MQ_CASE(24) MQ_CASE(26)
 #undef MQ_CASE
     default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
   }
@@ -113,13 +113,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       src[j] = p.packedW + dW.frag_offset(blk, 0) + (size_t)((i - FA) % FPB) * kFragBytes + lane * 16;
     }
   }
+  // this wave's j-th load of stage kt
+  auto issue_frag = [&](unsigned kt, int j) {
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src[j] + (size_t)kt * (FPB * kFragBytes)),
+        (__attribute__((address_space(3))) void*)(smem + (kt % S) * STAGE + (wave * L + j) * kFragBytes), 16, 0, 0);
+  };
   auto issue = [&](unsigned kt) {
-    uint8_t* dst = smem + (kt % S) * STAGE + wave * L * kFragBytes;
 #pragma unroll
-    for (int j = 0; j < L; ++j)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src[j] + (size_t)kt * (FPB * kFragBytes)),
-          (__attribute__((address_space(3))) void*)(dst + j * kFragBytes), 16, 0, 0);
+    for (int j = 0; j < L; ++j) issue_frag(kt, j);
   };
   // One load of a stage, without a branch: past the last stage the same instruction re-reads stage 0
   // into a per-wave dummy slot behind the stages, so that every K step issues exactly L loads and the
@@ -201,11 +203,38 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  // As `slice`, with loads [j0, j1) of stage kt_load issued one at a time, evenly spaced between the MFMAs: a burst
+  // of them queues in the address unit (64 bytes per clock) and holds the wave's MFMAs up behind it.
+  auto slice_ld = [&](const Frags& cur, Frags& nxt, const uint8_t* next_stage, int next_ks, unsigned kt_load, int j0, int j1) {
+    const int nl = j1 - j0;
+    const int every = nl > 0 && NM / nl > 0 ? NM / nl : 1;
+    int issued = 0;
+#pragma unroll
+    for (int i = 0; i < (NM > R ? NM : R); ++i) {
+      if (i < NM) mfma_one(cur, i);
+      if (i < R) read_one(nxt, next_stage, next_ks, i);
+      if (i < NM && (i + 1) % every == 0 && issued < nl) {
+        issue_frag(kt_load, j0 + issued);
+        ++issued;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (; issued < nl; ++issued) issue_frag(kt_load, j0 + issued);
+  };
 
   if constexpr (PF) {
+    if (KT >= (unsigned)(S - 1)) {
 #pragma unroll
-    for (int st = 0; st < S - 1; ++st)
-      if ((unsigned)st < KT) issue(st);
+      for (int st = 0; st < S - 2; ++st) issue(st);
+      // stage S - 2: the first half here, the second behind slice 0 of step 0, as in every later step
+#pragma unroll
+      for (int j = 0; j < L / 2; ++j) issue_frag(S - 2, j);
+    } else {
+#pragma unroll
+      for (int st = 0; st < S - 1; ++st)
+        if ((unsigned)st < KT) issue(st);
+    }
   } else {
 #pragma unroll
     for (int st = 0; st < S - 1; ++st)
@@ -214,29 +243,40 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   }
   if constexpr (PF) {
     Frags f0, f1;
-    if ((unsigned)(S - 2) < KT) wait_vmcnt((S - 2) * L);
+    const bool longk = KT >= (unsigned)(S - 1);
+    if (longk) wait_vmcnt((S - 3) * L + L / 2);      // everything but stage 0 may still be in flight
     else wait_vmcnt(0);
     block_barrier();
     MQ_STAMP(2);                  // first stage landed
 #pragma unroll
     for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
-
-    for (unsigned kt = 0; kt < KT; ++kt) {
+    // One K step: slice 0 of stage kt (slice 1's fragments stream in behind it), the wait for stage kt + 1 and the
+    // barrier, slice 1 (slice 0 of stage kt + 1 streams in; after the last stage that reads a finished slot again and
+    // the result is unused).  Stage kt + S - 1 goes into the slot of stage kt - 1, free once every wave is past this
+    // step's barrier: its first half is issued behind slice 1 (LD1), its second half behind slice 0 of the next step
+    // (LD0), so S - 3 whole stages stay in flight across the wait.  The loop is peeled by what a step issues (all,
+    // the last half stage, nothing) so that each body is straight-line code.
+    auto step = [&](unsigned kt, auto ld0, auto ld1, auto drain) {
       const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
       const uint8_t* nxt = smem + ((kt + 1) % S) * STAGE + lane * 16;
-      // slice 0 of stage kt; slice 1's fragments stream in behind it
-      slice(f0, f1, cur, 1);
-      // stage kt + 1 must have landed for everybody before its first fragments are
-      // read; stages kt + 2 .. kt + S - 2 may stay in flight (none in the tail)
-      if (kt + S - 2 < KT) wait_vmcnt((S - 3) * L);
-      else wait_vmcnt(0);
+      if constexpr (decltype(ld0)::value) slice_ld(f0, f1, cur, 1, kt + S - 2, L / 2, L);
+      else slice(f0, f1, cur, 1);
+      if constexpr (decltype(drain)::value) wait_vmcnt(0);
+      else wait_vmcnt((S - 3) * L);
       block_barrier();
-      // every wave is past slice 0 of stage kt, so stage kt - 1's slot is free
-      if (kt + S - 1 < KT) issue(kt + S - 1);
-      // slice 1 of stage kt; slice 0 of stage kt + 1 streams in behind it (after
-      // the last stage this reads a finished slot again and the result is unused)
-      slice(f1, f0, nxt, 0);
+      if constexpr (decltype(ld1)::value) slice_ld(f1, f0, nxt, 0, kt + S - 1, 0, L / 2);
+      else slice(f1, f0, nxt, 0);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    unsigned kt = 0;
+    if (longk) {
+      const unsigned KM = KT - (unsigned)(S - 1);
+      for (; kt < KM; ++kt) step(kt, T{}, T{}, F{});
+      step(kt, T{}, F{}, F{});
+      ++kt;
     }
+    for (; kt < KT; ++kt) step(kt, F{}, F{}, T{});
   } else {
     // Register-lean variant for tiles whose accumulators leave no room for a second fragment
     // set: fragments are read right before use; with two waves per SIMD the other wave's MFMAs
