@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   const uint8_t* src_lane = p.packedW + lane_off;
   // GATHER: this workgroup's candidate rows, 16 per stage, are fetched into LDS once, before any
   // direct-to-LDS load is in flight (later ordinary loads would have to drain the pipeline)
-  int32_t* rows_lds = reinterpret_cast<int32_t*>(smem + S * STAGE);
+  int32_t* rows_lds = reinterpret_cast<int32_t*>(smem + S * STAGE + kWaves * kFragBytes);
   if (GATHER) {
     for (unsigned i = threadIdx.x; i < nlocal * 16; i += kWaves * 64) {
       const unsigned pos = (first + (i / 16) * stride) * 16 + i % 16;
@@ -122,7 +122,13 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     }
     __syncthreads();
   }
-  auto issue = [&](unsigned s) {
+  // One load per wave for stage s.  Past the workgroup's last unit the same instruction fetches unit 0 again into a
+  // per-wave slot behind the stages that nobody reads: every stage then issues exactly one load, the number of loads
+  // in flight at a given point is a constant, and the waits need neither a branch nor a table.  Needs nlocal > 0.
+  auto issue = [&](unsigned s_any) {
+    const bool real = s_any < nlocal;
+    const unsigned s = real ? s_any : 0;
+    uint8_t* dst = real ? smem + (s % S) * STAGE + wave * kFragBytes : smem + S * STAGE + wave * kFragBytes;
     const uint8_t* src;
     if (GATHER) {
       const unsigned r = (unsigned)rows_lds[s * 16 + lane % 16];
@@ -132,8 +138,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
       src = src_lane + operand16_uniform_offset(dW, (size_t)first + (size_t)s * stride, my_group);
     }
     __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)src,
-        (__attribute__((address_space(3))) void*)(smem + (s % S) * STAGE + wave * kFragBytes), 16, 0, 0);
+        (const __attribute__((address_space(1))) void*)src, (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
   };
   // The first two stages go out first (their memory latency is the longest wait of the kernel), then the
   // hidden-state operands of this wave's sentence tiles (tile t = wave + 8 i covers sentences 16 t ..
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   constexpr int kEarly = 2;
 #pragma unroll
   for (int s = 0; s < kEarly; ++s)
-    if ((unsigned)s < nlocal) issue(s);
+    if (nlocal > 0) issue(s);
   v4i hid[TPW][KG];
   const size_t tiles_avail = dA.nblocks * 2;
   // 16-sentence tiles this wave really owns (a slot beyond them would only repeat a tile): TPW or TPW - 1
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   }
 #pragma unroll
   for (int s = kEarly; s < S - 1; ++s)
-    if ((unsigned)s < nlocal) issue(s);
+    if (nlocal > 0) issue(s);
 
   // running maxima, one per accumulator register: (sum << 8) | (255 - stage).  Real sums exceed
   // -2^23, so a key whose sum field is -2^23 means "no candidate yet".
@@ -213,11 +218,11 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   };
 
   // Before stage s is multiplied, stages s and s + 1 must have landed (s + 1 is read from LDS into
-  // registers while s is multiplied).  Loads issued so far: stages 0 .. min(nlocal, s + S - 1) - 1.
-  auto land = [&](unsigned s) {
-    const unsigned issued = nlocal < s + S - 1 ? nlocal : s + S - 1;
-    const unsigned need = s + 2 < nlocal ? s + 2 : nlocal;
-    wait_vmcnt_n((int)(issued - need));
+  // registers while s is multiplied): of the loads issued so far the oldest s + 2 are needed, `newest` may be
+  // outstanding.  With a load in every stage S - 1 + s have been issued (newest = S - 3); without, S - 1
+  // (newest = S - 3 - s).
+  auto land = [&](int newest) {
+    wait_vmcnt_n(newest);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -232,26 +237,26 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   // maxima are updated from `prev` (the sums of the stage before) and the next unit is read from LDS
   // into `enext`.  The update's VALU work is cut into slices that sit between the MFMA groups, so it
   // runs while the matrix pipeline is busy instead of after it; the scheduling fences keep that order.
-  auto stage = [&](auto nt_tag, unsigned s, v4i (&cur)[TPW], const v4i (&prev)[TPW], const v4i (&e)[KG],
-                   v4i (&enext)[KG]) {
+  auto stage = [&](auto nt_tag, auto refill_tag, int newest, unsigned s, v4i (&cur)[TPW], const v4i (&prev)[TPW],
+                   const v4i (&e)[KG], v4i (&enext)[KG]) {
     constexpr int NT = decltype(nt_tag)::value;
-    land(s);
+    land(newest);
 #ifdef MQ_TS
     if (threadIdx.x == MQ_TS_TID && s < 12)
-      reinterpret_cast<unsigned long long*>(smem + S * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s] = wall_clock64();
+      reinterpret_cast<unsigned long long*>(smem + (S + 1) * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s] = wall_clock64();
 #endif
     // everybody is past stage s - 1 (and has its copy of stage s in registers), so slot s - 1 can be refilled
-    if (s + S - 1 < nlocal) issue(s + S - 1);
+    if constexpr (decltype(refill_tag)::value) issue(s + S - 1);
     // the next unit's LDS reads are spread between the MFMA groups: eight reads in a row would fill the
     // LDS queue (all eight waves read at the same time) and hold this wave's MFMAs back behind them
-    const bool more = s + 1 < nlocal;
+    // (after the last unit they read a finished slot again and the result is unused)
     const uint8_t* nx = smem + ((s + 1) % S) * STAGE + lane * 16;
     const int prev_tag = 256 - (int)s;          // 255 - (s - 1); unused garbage for s == 0 (prev holds "none")
     constexpr int ITEMS = NT * 4, PER = (ITEMS + KG - 1) / KG;
     const v4i zero = {0, 0, 0, 0};
 #pragma unroll
     for (int g = 0; g < KG; ++g) {
-      if (more) enext[g] = as_v4i(*reinterpret_cast<const u4*>(nx + g * kFragBytes));
+      enext[g] = as_v4i(*reinterpret_cast<const u4*>(nx + g * kFragBytes));
 #pragma unroll
       for (int i = 0; i < NT; ++i)
         cur[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(e[g], hid[i][g], g == 0 ? zero : cur[i], 0, 0, 0);
@@ -277,8 +282,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   if (nlocal > 0) {
     // stage 0 has to be in registers before the loop, and so have the operands: everything but the
     // stages issued after the operands may still be outstanding
-    const unsigned issued = nlocal < (unsigned)(S - 1) ? nlocal : (unsigned)(S - 1);
-    wait_vmcnt_n(issued > (unsigned)kEarly ? (int)(issued - kEarly) : 0);
+    wait_vmcnt_n(S - 1 - kEarly);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -294,17 +298,27 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
       asm volatile("" : "+v"(hid[i][g]));
       if ((unsigned)g >= kgroups) hid[i][g] = v4i{0, 0, 0, 0};
     }
-  if (ntl == TPW) {
-    for (unsigned s = 0; s < nlocal; s += 2) {
-      stage(std::integral_constant<int, TPW>{}, s, acc0, acc1, e0, e1);
-      if (s + 1 < nlocal) stage(std::integral_constant<int, TPW>{}, s + 1, acc1, acc0, e1, e0);
+  auto run = [&](auto nt_tag) {
+    if (nlocal <= (unsigned)(S - 1)) {
+      // The usual case (36 000 rows over 256 workgroups are 9 units each): the prologue has issued everything.
+      // Unrolled, so that each stage waits with its own constant and nothing is issued inside the loop.
+#pragma unroll
+      for (int s = 0; s < S - 1; ++s) {
+        if ((unsigned)s >= nlocal) break;
+        const int newest = S - 3 - s > 0 ? S - 3 - s : 0;
+        if (s % 2 == 0) stage(nt_tag, std::false_type{}, newest, (unsigned)s, acc0, acc1, e0, e1);
+        else stage(nt_tag, std::false_type{}, newest, (unsigned)s, acc1, acc0, e1, e0);
+      }
+    } else {
+      for (unsigned s = 0; s < nlocal; s += 2) {
+        stage(nt_tag, std::true_type{}, S - 3, s, acc0, acc1, e0, e1);
+        if (s + 1 < nlocal) stage(nt_tag, std::true_type{}, S - 3, s + 1, acc1, acc0, e1, e0);
+      }
     }
-  } else {
-    for (unsigned s = 0; s < nlocal; s += 2) {
-      stage(std::integral_constant<int, TPW - 1>{}, s, acc0, acc1, e0, e1);
-      if (s + 1 < nlocal) stage(std::integral_constant<int, TPW - 1>{}, s + 1, acc1, acc0, e1, e0);
-    }
-  }
+  };
+  if (ntl == TPW) run(std::integral_constant<int, TPW>{});
+  else run(std::integral_constant<int, TPW - 1>{});
+  wait_vmcnt_n(0);      // the refills past the last unit are still landing in their slots
   MQ_ASTAMP(14);
   // the last stage's sums are still pending; only a workgroup's last unit can reach past N, where
   // the rows are padding and must not compete (needs at least two workgroups, which the launcher
@@ -417,7 +431,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   if (threadIdx.x == MQ_TS_TID)
     for (unsigned s = 0; s < nlocal && s < 12; ++s)
       (p.partial + (1u << 20) / 8 * 2)[blockIdx.x * 16 + 2 + s] =
-          reinterpret_cast<unsigned long long*>(smem + S * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s];
+          reinterpret_cast<unsigned long long*>(smem + (S + 1) * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s];
 #endif
   MQ_ASTAMP(15);
 }
@@ -522,7 +536,7 @@ __global__ __launch_bounds__(256) void k_topk_reduce(const unsigned long long* _
 
 template <int TPW, bool GATHER, int BEAM = 1>
 int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
-  constexpr size_t smem = (size_t)kStages * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0)
+  constexpr size_t smem = (size_t)(kStages + 1) * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0)
 #ifdef MQ_TS
                           + 256
 #endif

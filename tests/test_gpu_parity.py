@@ -338,7 +338,9 @@ def gpu_greedy(Hd, E, pw=None):
     return host(tok), host(val)
 
 
-@pytest.mark.parametrize("M,V,d", [(1, 1, 1), (3, 17, 8), (12, 777, 64), (33, 4100, 96), (300, 3000, 512), (130, 129, 512)])
+# 70 000 words are more units per workgroup than the pipeline holds stages: the loop that refills slots
+@pytest.mark.parametrize("M,V,d", [(1, 1, 1), (3, 17, 8), (12, 777, 64), (33, 4100, 96), (300, 3000, 512), (130, 129, 512),
+                                   (20, 70000, 64), (40, 150001, 32)])
 def test_greedy_output_layer_small(M, V, d):
     c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V)
     o = oracle.greedy_output_layer(c["Hd"], c["E"])
@@ -1062,7 +1064,7 @@ def gpu_topk(Hd, E, k, shortlist=None):
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 @pytest.mark.parametrize("M,V,d", [(1, 4, 1), (12, 777, 64), (33, 4100, 96), (300, 36000, 512), (130, 9000, 192),
-                                   (600, 5000, 128)])
+                                   (600, 5000, 128), (12, 70000, 64)])
 def test_beam_output_layer_topk(M, V, d, k):
     # Table 2's b = 2 / b = 4 rows: the k best words per row, exact, with log-probabilities within 1e-4
     # (binary32 logits of magnitude <= ~30 here; the normaliser sums V terms in binary32).  M = 600 goes
