@@ -543,6 +543,25 @@ def test_gemm_packed_full_range_all_variants(dtype, M, N, K):
         mq.mq_set_gemm_variant(0)
 
 
+@pytest.mark.parametrize("dtype", [np.int8, np.int16])
+@pytest.mark.parametrize("K", [129, 192, 256, 320, 384, 448, 576, 640])
+def test_gemm_packed_pipeline_boundaries_all_variants(dtype, K):
+    # 3 to 10 K steps of 64: around every variant's ring depth (3, 4, 6 or 8 stages), where the main loop changes from
+    # "everything issued by the prologue" to one peeled step to the steady loop
+    M, N = 150, 140
+    rng = np.random.default_rng(K * 7919 + (8 if dtype == np.int8 else 16))
+    lim = 127 if dtype == np.int8 else 32767
+    qA = rng.integers(-lim, lim + 1, size=(M, K)).astype(dtype)
+    qB = rng.integers(-lim, lim + 1, size=(N, K)).astype(dtype)
+    want = oracle.dot_int(qA, qB)
+    try:
+        for v in PACKED_VARIANTS[8 if dtype == np.int8 else 16]:
+            mq.mq_set_gemm_variant(v)
+            assert np.array_equal(gpu_dot_int_packed(qA, qB), want), f"variant {v}"
+    finally:
+        mq.mq_set_gemm_variant(0)
+
+
 def test_gemm_packed_one_hot_layout():
     # one non-zero per operand: checks where the direct-to-LDS copy puts each lane's bytes
     for dtype in (np.int8, np.int16):
