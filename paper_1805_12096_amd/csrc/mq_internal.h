@@ -152,6 +152,8 @@ int launch_gemm_requant_fixed(const GemmArgs& a, const float* s_fixed, void* pac
 int launch_gemm_requant_fixed_i16(const GemmArgs& a, const float* s_fixed, void* packed_out, hipStream_t s);
 // Tiled 8-bit product with two extra waves per workgroup that only load (mq_gemm_prod.hip); variants 11 .. 13.
 int launch_gemm_prod(const GemmArgs& a, Epilogue epi, int which, hipStream_t s);
+// Variant 14 of the packed 8-bit products (mq_gemm_ks.hip): 128 x 128 tile, K split over two groups of four waves.
+int launch_gemm_ks(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
 int tuned_variant(int bits, size_t M, size_t N, size_t K);
 void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant);

@@ -288,7 +288,7 @@ def test_decode_sized_products_random_shapes():
             s = torch.empty(1, dtype=torch.float32, device=DEV)
             mq.mq_quantize_absmax_pack_f32(dev(p["A"]), M, K, 8, q, s, qws, qws.numel())
             o2 = oracle.linear(p["A"], p["Wt"], 8, p["bias"], relu)
-            for v in (10, 11, 12, 13):
+            for v in (10, 11, 12, 13, 14):
                 mq.mq_set_gemm_variant(v)
                 mq.mq_gemm_dequant_packed(q, pw.packed, 8, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, None)
                 assert np.array_equal(host(Y), o2["Y"]), (M, N, K, relu, v)
@@ -522,7 +522,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13], 16: [0, 1, 2, 3, 4, 5, 6]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14], 16: [0, 1, 2, 3, 4, 5, 6]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
@@ -1052,7 +1052,7 @@ def test_autotune_freezes_a_variant_and_results_stay_identical():
     nbytes = mq.mq_autotune_ws_bytes(8, M, N, K)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     best, us = mq.mq_autotune_gemm(8, M, N, K, 20, ws, nbytes)
-    assert 1 <= best <= 13 and us > 0
+    assert 1 <= best <= 14 and us > 0
     pw = mq.prepare_weight(dev(p["Wt"]), 8)
     pa, s = gpu_quantize_pack(p["A"], 8)
     Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
