@@ -279,31 +279,56 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     for (; kt < KT; ++kt) step(kt, F{}, F{}, T{});
   } else {
     // Register-lean variant for tiles whose accumulators leave no room for a second fragment
-    // set: fragments are read right before use; with two waves per SIMD the other wave's MFMAs
-    // cover the LDS latency.  One barrier per K step, as in the simple pipeline.
+    // set: fragments are read right before use (the compiler moves a slice's reads up behind the last MFMAs of
+    // the slice before as their registers fall free); with two waves per SIMD the other wave's MFMAs
+    // cover the rest of the LDS latency.  One barrier per K step.  Every step issues L loads (real or dummy), so
+    // S - 2 steps' worth may always stay in flight.
     Frags f;
-    constexpr int EVERY = (2 * NM) / L > 0 ? (2 * NM) / L : 1;     // MFMAs between two loads
+    // The step's barrier sits inside slice 1, before its last TAIL MFMAs: by then every fragment of stage kt has
+    // been read (the wait on the LDS counter makes sure), so the slot is free for everybody and stage kt + 1 is
+    // checked in; the first fragments of stage kt + 1 are read behind those last MFMAs instead of in a gap after
+    // the barrier, where all waves of the workgroup would read at the same time with the matrix pipeline idle.
+    constexpr int TAIL = NM / 2 > 0 ? NM / 2 : 1;
+    constexpr int SPAN = 2 * NM - TAIL;                           // MFMAs before the barrier: all loads go there
+    constexpr int EVERY2 = SPAN / L > 0 ? SPAN / L : 1;
+    wait_vmcnt((S - 2) * L);
+    block_barrier();
+#pragma unroll
+    for (int r = 0; r < R; ++r) read_one(f, smem + lane * 16, 0, r);
     for (unsigned kt = 0; kt < KT; ++kt) {
-      // every step issues L loads (real or dummy), so S - 2 steps' worth may always stay in flight
-      wait_vmcnt((S - 2) * L);
-      block_barrier();
       const uint8_t* cur = smem + (kt % S) * STAGE + lane * 16;
+      const uint8_t* nxt = smem + ((kt + 1) % S) * STAGE + lane * 16;
       int issued = 0;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int i = 0; i < NM; ++i) {
+        mfma_one(f, i);
+        if (i % EVERY2 == EVERY2 - 1 && issued < L) {
+          issue_one(kt + S - 1, issued);
+          ++issued;
+        }
+      }
 #pragma unroll
-        for (int r = 0; r < R; ++r) read_one(f, cur, ks, r);
+      for (int r = 0; r < R; ++r) read_one(f, cur, 1, r);
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-          mfma_one(f, i);
-          if ((ks * NM + i) % EVERY == EVERY - 1 && issued < L) {
-            issue_one(kt + S - 1, issued);
-            ++issued;
-          }
+      for (int i = 0; i < NM - TAIL; ++i) {
+        mfma_one(f, i);
+        if ((NM + i) % EVERY2 == EVERY2 - 1 && issued < L) {
+          issue_one(kt + S - 1, issued);
+          ++issued;
         }
       }
 #pragma unroll
       for (; issued < L; ++issued) issue_one(kt + S - 1, issued);
+      // stage kt + 1 has landed (the newest (S - 2) L loads are stage kt + 2 .. kt + S - 1) and nobody reads stage kt
+      // any more: every read of it has returned
+      __builtin_amdgcn_s_waitcnt(0xC07F);                         // lgkmcnt(0)
+      wait_vmcnt((S - 2) * L);
+      block_barrier();
+#pragma unroll
+      for (int i = NM - TAIL; i < NM; ++i) mfma_one(f, i);
+      // after the last stage this reads a slot nobody writes any more; the result is unused
+#pragma unroll
+      for (int r = 0; r < R; ++r) read_one(f, nxt, 0, r);
     }
     wait_vmcnt(0);     // dummy loads of the tail must not outlive the stages' reuse in the epilogue
   }
