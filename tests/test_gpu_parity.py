@@ -960,7 +960,8 @@ def gpu_greedy_shortlist(Hd, E, shortlist):
 
 
 @pytest.mark.parametrize("M,V,d,L", [(1, 1, 1, 1), (12, 777, 64, 1), (12, 777, 64, 15), (33, 4100, 96, 1000),
-                                     (300, 36000, 512, 4321), (300, 36000, 512, 36000), (130, 9000, 192, 8999)])
+                                     (300, 36000, 512, 4321), (300, 36000, 512, 36000), (130, 9000, 192, 8999),
+                                     (20, 150001, 32, 70000)])       # a list longer than the ring: slots refilled
 def test_greedy_shortlist(M, V, d, L):
     c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + L)
     rng = np.random.default_rng(L + V)
@@ -1112,10 +1113,11 @@ def test_beam_output_layer_ties_and_crowded_lanes():
 
 
 @pytest.mark.parametrize("k", [2, 4])
-def test_beam_output_layer_with_shortlist(k):
-    c = workloads.config3(M=64, V=9000, d=128, seed_extra=77)
+@pytest.mark.parametrize("V,L", [(9000, 1234), (120000, 60000)])     # the longer list refills the ring's slots
+def test_beam_output_layer_with_shortlist(k, V, L):
+    c = workloads.config3(M=64, V=V, d=128 if V < 10000 else 32, seed_extra=77)
     rng = np.random.default_rng(5)
-    sl = np.sort(rng.choice(9000, size=1234, replace=False)).astype(np.int32)
+    sl = np.sort(rng.choice(V, size=L, replace=False)).astype(np.int32)
     qE = c["E"][sl]
     # the short list is scored with the whole embedding's multiplier: quantize the whole, then gather
     full = oracle.greedy_output_layer(c["Hd"], c["E"])
