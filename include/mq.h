@@ -72,10 +72,12 @@ int mq_last_hip_error(void);
 /* Tuning knob for measurements in the spirit of the paper's auto-tuner (Section
  * 4.4: alternative implementations are timed per shape and the fastest is
  * kept).  variant 0 (default) lets the library choose the tile configuration of
- * the product kernels from the problem shape; 1..4 force one configuration for
- * every following product of this process (results are identical, only speed
- * changes; a variant that does not exist for the operand width makes the
- * product calls return MQ_ERR_UNSUPPORTED).  Not thread safe. */
+ * the product kernels from the problem shape; 1..14 (8 bit) or 1..6 (16 bit)
+ * force one configuration for every following product of this process (results
+ * are identical, only speed changes; a variant that does not exist for the
+ * operand width makes the product calls return MQ_ERR_UNSUPPORTED; the fused
+ * epilogues of the FFN block keep to the tile shapes they support).  Not thread
+ * safe. */
 int mq_set_gemm_variant(int variant);
 
 /* ---- quant_int (Section 4.2) -------------------------------------------- */
