@@ -65,9 +65,12 @@ __device__ __forceinline__ void tile_coords(unsigned tiles_m, unsigned tiles_n, 
 // along M, j along N.  wave_m0 / wave_n0 are the wave's first row / column.
 // 16-bit sums are recombined here from the three partial accumulators:
 //   acc = 2^16 hh + 2^8 mid + ll + 128 (rowsum[m] + colsum[n]) - 16384 K  (mod 2^32).
+// bias_pre (optional): this lane's TN biases (0 where there is none), fetched by the caller before its main
+// loop so that the epilogue does not start with a memory round trip.
 template <int BITS, int TM, int TN, int NACC, int EPI, int NWAVES>
 __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const Params& p, unsigned wave_m0,
-                                               unsigned wave_n0, const int32_t* rowsum, const int32_t* colsum) {
+                                               unsigned wave_n0, const int32_t* rowsum, const int32_t* colsum,
+                                               const float* bias_pre = nullptr) {
   const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
   const int lj = lane % 32, lh = lane / 32;
   float u = 0.f, local_amax = 0.f;
@@ -102,7 +105,10 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
       const unsigned n = wave_n0 + nt * 32 + lj;
       float bias = 0.f;
       unsigned corr_n = 0;
-      if (EPI == kEpiDequant && p.bias != nullptr) bias = p.bias[n];
+      if (EPI == kEpiDequant) {
+        if (bias_pre != nullptr) bias = bias_pre[nt];
+        else if (p.bias != nullptr) bias = p.bias[n];
+      }
       if (BITS == 16) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
 #pragma unroll
       for (int mt = 0; mt < TM; ++mt)
@@ -116,7 +122,10 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
       const bool n_ok = n < p.N;
       float bias = 0.f;
       unsigned corr_n = 0;
-      if (EPI == kEpiDequant && p.bias != nullptr && n_ok) bias = p.bias[n];
+      if (EPI == kEpiDequant) {
+        if (bias_pre != nullptr) bias = bias_pre[nt];
+        else if (p.bias != nullptr && n_ok) bias = p.bias[n];
+      }
       if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
 #pragma unroll
       for (int mt = 0; mt < TM; ++mt)

@@ -74,6 +74,15 @@ __global__ __launch_bounds__(512) void k_gemm_ks(const Params p) {
         (__attribute__((address_space(3))) void*)(smem + (pt % S) * STAGE + (wave * FPB + j) * kFragBytes), 16, 0, 0);
   };
 
+  // the dequantizing epilogue's biases: one per lane and column block, in registers across the main loop
+  float bias_pre[TN];
+  if constexpr (EPI == kEpiDequant) {
+#pragma unroll
+    for (int nt = 0; nt < TN; ++nt) {
+      const unsigned n = n0 + (wn * TN + nt) * 32 + lane % 32;
+      bias_pre[nt] = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
+    }
+  }
   v16i acc[TM][TN][1];
 #pragma unroll
   for (int a = 0; a < TM; ++a)
@@ -202,7 +211,8 @@ __global__ __launch_bounds__(512) void k_gemm_ks(const Params p) {
   // group 1 passes through the epilogue with a tile origin past the matrix: it stores nothing and takes part
   // in the epilogue's barrier
   const unsigned wave_m0 = grp == 0 ? m0 + wm * TM * 32 : p.M;
-  store_epilogue<8, TM, TN, 1, EPI, NW>(acc, p, wave_m0, n0 + wn * TN * 32, nullptr, nullptr);
+  store_epilogue<8, TM, TN, 1, EPI, NW>(acc, p, wave_m0, n0 + wn * TN * 32, nullptr, nullptr,
+                                        EPI == kEpiDequant ? bias_pre : nullptr);
 }
 
 template <int S, int EPI>

@@ -95,6 +95,24 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   float u_early = 0.f;
   if constexpr (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast)
     u_early = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+  // the tile's biases go to LDS before the main loop: fetched from global memory in the epilogue they are a full
+  // memory round trip that nothing hides
+  __shared__ float sbias[BN];
+  float bias_early = 0.f;
+  constexpr bool kBiasLds = BITS == 8 && (EPI == kPAmax || EPI == kPRequant || EPI == kPCoop || EPI == kPCoopFast);
+  if constexpr (kBiasLds) {
+    static_assert(NW * 64 >= BN, "one thread per column of the tile");
+    if (tid < BN && p.bias != nullptr && n0 + tid < p.N) bias_early = p.bias[n0 + tid];
+  }
+  // the dequantizing epilogue's biases: one per lane and column block, in registers across the main loop
+  float bias_pre[TN];
+  if constexpr (EPI == kPDequant) {
+#pragma unroll
+    for (int nt = 0; nt < TN; ++nt) {
+      const unsigned n = n0 + (wn * TN + nt) * 32 + lane % 32;
+      bias_pre[nt] = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.f;
+    }
+  }
 
   // Source of this wave's j-th load of a stage: fragment i = wave * L + j of the
   // stage; fragments [0, FA) are A's, the rest the parameter's.  Row blocks past
@@ -240,6 +258,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     for (int st = 0; st < S - 1; ++st)
 #pragma unroll
       for (int j = 0; j < L; ++j) issue_one(st, j);
+  }
+  if constexpr (kBiasLds) {
+    if (tid < BN) sbias[tid] = bias_early;      // visible to everybody after the barrier below
   }
   if constexpr (PF) {
     Frags f0, f1;
@@ -411,14 +432,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     // a tile with no row or column past the end needs no masking anywhere below
     const bool interior = FASTC || (m0 + BM <= p.M && n0 + BN <= p.N);
     constexpr bool SWAPPED = EPI != kPAmax;
-    // bias[n] without a branch (a branch per element makes every load wait for the one before): the
-    // index is clamped into the vector, and without a bias some readable address stands in
-    const bool has_bias = p.bias != nullptr;
-    auto bias_at = [&](unsigned n) -> float {
-      const float* src = has_bias ? p.bias + (n < p.N ? n : p.N - 1) : p.sA;
-      const float b = *src;
-      return has_bias ? b : 0.f;
-    };
+    // bias[n] of this tile (0 without a bias vector or past the last column): in LDS since before the main loop
+    auto bias_at = [&](unsigned n) -> float { return sbias[n - n0]; };
     // swapped layout: the 16 registers of a sub-tile are 16 columns n; their biases are fetched once
     float biasv[SWAPPED ? TN : 1][16];
     if constexpr (SWAPPED) {
@@ -659,7 +674,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
     const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
     store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
-        acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum);
+        acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum, EPI == kPDequant ? bias_pre : nullptr);
     MQ_STAMP(5);
   }
 }
