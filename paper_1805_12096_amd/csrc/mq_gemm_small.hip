@@ -49,6 +49,18 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
   }
   const uint8_t* w_src = p.packedW + dW.frag_offset(tile_n, 0) + lane * 16;
 
+  // The epilogue's constants are asked for before the operands: loaded where they are used, they are a memory
+  // round trip that nothing hides.  Every element a thread finishes has e % 64 == lane, so they share the
+  // column n and the bias.
+  const int lj = lane % 32, lh = lane / 32;
+  const unsigned n = tile_n * 32 + lj;
+  const bool n_ok = n < p.N;
+  float u = 0.f, bias = 0.f, local_amax = 0.f;
+  if (dequant) {
+    u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+    if (p.bias != nullptr && n_ok) bias = p.bias[n];
+  }
+
   v16i acc[TMW][NACC];
 #pragma unroll
   for (int mt = 0; mt < TMW; ++mt)
@@ -101,16 +113,7 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small(const Params p, const in
     }
   __syncthreads();
 
-  // Every thread adds up KS partial sums for TMW * 1024 / (KS * 64) elements.  Its elements all have
-  // e % 64 == lane, so they share the column n and the bias.
-  const int lj = lane % 32, lh = lane / 32;
-  const unsigned n = tile_n * 32 + lj;
-  const bool n_ok = n < p.N;
-  float u = 0.f, bias = 0.f, local_amax = 0.f;
-  if (dequant) {
-    u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
-    if (p.bias != nullptr && n_ok) bias = p.bias[n];
-  }
+  // Every thread adds up KS partial sums for TMW * 1024 / (KS * 64) elements.
   constexpr int PER_THREAD = TMW * 1024 / (KS * 64);
   static_assert(PER_THREAD >= 1 && PER_THREAD * KS * 64 == TMW * 1024, "elements must divide over the threads");
 #pragma unroll
@@ -285,6 +288,15 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
 #pragma unroll
     for (int i = 0; i < 16; ++i) fa[i] = *reinterpret_cast<const float4*>(base + (size_t)a_row[i] * ld);
   };
+  // the epilogue's constants first (see k_gemm_small): a thread's elements lie in column block
+  // c = (i KS 64) / 1024 of the tile, all at column lj of it
+  const float sW_pre = *p.sW;
+  float bias_pre[TNW];
+#pragma unroll
+  for (int c = 0; c < TNW; ++c) {
+    const unsigned n = (tile_n * TNW + c) * 32 + lj;
+    bias_pre[c] = (p.bias != nullptr && n < p.N) ? p.bias[n] : 0.0f;
+  }
   if (kb_begin < kb_end) fetch(kb_begin);        // the first round is on its way while the multiplier is formed
 
   float s;
@@ -339,9 +351,10 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
     for (int r = 0; r < 16; ++r) mine[(c * 16 + r) * 64 + lane] = acc[c][r];
   __syncthreads();
 
-  const float u = __fdiv_rn(1.0f, __fmul_rn(s, *p.sW));
+  const float u = __fdiv_rn(1.0f, __fmul_rn(s, sW_pre));
   float local_amax = 0.f;
   constexpr int PER_THREAD = TNW * 1024 / (KS * 64);
+  static_assert(1024 % (KS * 64) == 0, "a thread's i-th element lies in a column block known at compile time");
   static_assert(PER_THREAD >= 1 && PER_THREAD * KS * 64 == TNW * 1024, "elements must divide over the threads");
 #pragma unroll
   for (int i = 0; i < PER_THREAD; ++i) {
@@ -353,7 +366,7 @@ __global__ __launch_bounds__(KS * 64) void k_gemm_small_f32(const SmallF32Params
     const unsigned n = (tile_n * TNW + c) * 32 + lj;
     const unsigned m = tile_m * 32 + 8 * (r / 4) + 4 * lh + r % 4;
     if (n < p.N && m < p.M) {
-      float y = fmaf((float)(int)v, u, p.bias != nullptr ? p.bias[n] : 0.0f);
+      float y = fmaf((float)(int)v, u, bias_pre[(i * KS * 64) / 1024]);
       if (p.relu) y = (y > 0.0f) ? y : 0.0f;
       p.Y[(size_t)m * p.N + n] = y;
       local_amax = fmaxf(local_amax, fabsf(y));
