@@ -576,6 +576,26 @@ def test_gemm_packed_one_hot_layout():
             assert np.array_equal(gpu_dot_int_packed(qA, qB), want), (dtype, m, n, k)
 
 
+@pytest.mark.parametrize("M,N,K,relu", [(37, 53, 64, True), (300, 200, 320, False), (513, 258, 448, True),
+                                        (1000, 130, 2048, False), (129, 512, 4100, True)])
+def test_linear_pipeline_packed_k_split_over_wave_groups(M, N, K, relu):
+    # variant 14: an odd number of 64-element K steps leaves the second wave group's last step empty; the
+    # dequantizing epilogue with bias, ReLU and the abs-max by-product runs on the first group only
+    p = workloads.random_problem(M + N + K + 14, M, N, K)
+    o = oracle.linear(p["A"], p["Wt"], 8, p["bias"], relu)
+    pw = mq.prepare_weight(dev(p["Wt"]), 8)
+    pa, s = gpu_quantize_pack(p["A"], 8)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    try:
+        mq.mq_set_gemm_variant(14)
+        mq.mq_gemm_dequant_packed(pa, pw.packed, 8, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, am)
+    finally:
+        mq.mq_set_gemm_variant(0)
+    assert np.array_equal(host(Y), o["Y"])
+    assert host(am)[0] == np.abs(o["Y"]).max()
+
+
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("M,N,K,relu", [(37, 53, 129, True), (300, 512, 512, True), (520, 300, 1024, False)])
 def test_linear_pipeline_packed(bits, M, N, K, relu):
