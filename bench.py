@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file on the default workload
 # (profiles/ffn_int8_hbm_counters.txt: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after calibration on a known copy).
 MEASURED_TRAFFIC = {
-    "gemm1 single pass: bias+relu -> max|H| -> quant_int(H)": 29.8e6,
+    "gemm1 single pass: bias+relu -> max|H| -> quant_int(H)": 29.7e6,
     "(two-pass) gemm1 pass 1: bias+relu -> max|H|": 12.8e6,
-    "(two-pass) gemm1 pass 2: bias+relu -> quant_int(H)": 29.7e6,
+    "(two-pass) gemm1 pass 2: bias+relu -> quant_int(H)": 29.6e6,
     "gemm2+bias": 41.4e6,
     "absmax+quant_int(A) [2 launches]": 21.2e6,
 }
