@@ -1,15 +1,15 @@
 // dot'_int on packed 8-bit operands with the loading taken off the multiplying waves
 // (arxiv 1805.12096, Section 4.3: the product of two quantized tensors, both contiguous along K).
 //
-// In the tiled kernel of mq_gemm_packed.hip every wave issues its share of a stage's direct-to-LDS loads
-// right after the barrier of a K step.  The address unit of a compute unit takes 64 bytes per clock, so the
-// 16 KB of a 128 x 128 stage occupy it for 256 clocks -- as long as the step's matrix instructions take --
-// and while the loads queue there, the waves that issued them cannot issue anything else: the two phases run
-// one after the other instead of side by side (measured per wave and K step: 280 clocks in the issue, 150 in
-// the wait, 160 at the barrier, 500 multiplying).  Here two extra waves per workgroup do nothing but load:
-// they wait for a stage to land, meet the others at the step's barrier, and issue the stage that reuses the
-// slot everybody has just left; the multiplying waves only read fragments and multiply.  Two loaders,
-// because a wave can have at most 63 loads outstanding and a deep pipeline needs more than that in flight.
+// In the tiled kernel of mq_gemm_packed.hip the waves that multiply also issue the stage's direct-to-LDS loads.
+// The address unit of a compute unit takes 64 bytes per clock, so the 16 KB of a 128 x 128 stage occupy it for
+// 256 clocks -- as long as the step's matrix instructions take -- and a wave whose load waits in that queue cannot
+// issue anything else meanwhile.  Here two extra waves per workgroup do nothing but load: they wait for a stage to
+// land, meet the others at the step's barrier, and issue the stage that reuses the slot everybody has just left;
+// the multiplying waves only read fragments and multiply.  Two loaders, because a wave can have at most 63 loads
+// outstanding and a deep pipeline needs more than that in flight.  (Measured against the tiled kernel when that
+// one still issued a stage's loads as one burst after the barrier: 1-2 % faster; the tiled kernel has since
+// learned to space its loads between its MFMAs, and the auto-tuner decides between the two per shape.)
 //
 // Same stages, same fragment order, same single barrier per K step and the same epilogue as the tiled kernel.
 #include "mq_gemm_common.h"
