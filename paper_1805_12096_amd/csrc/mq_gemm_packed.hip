@@ -7,11 +7,12 @@
 // pipeline affordable: S stages of LDS, S - 1 of them in flight, which is what
 // it takes to cover HBM latency with one or two waves per SIMD.
 //
-// Synchronisation per K step (one barrier):
-//   wait until this wave's loads of stage kt have landed (vmcnt counts the
+// Synchronisation per K step (one barrier, between the step's two 32-element slices):
+//   wait until this wave's loads of stage kt + 1 have landed (vmcnt counts the
 //   younger stages that may still be in flight), barrier (now everybody's have,
-//   and everybody is done reading stage kt - 1), issue the loads that overwrite
-//   stage kt - 1's slot, multiply stage kt.
+//   and everybody is done reading stage kt - 1).  The loads that overwrite stage
+//   kt - 1's slot are issued one at a time between the MFMAs of the following two
+//   slices; fragments are read from LDS one slice ahead of the MFMAs that use them.
 // The compiler does not track LDS written by these loads, so the waits are
 // explicit and the barrier is fenced against compile-time motion by hand.
 #include <type_traits>
