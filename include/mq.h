@@ -352,6 +352,23 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
                   const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* The same block for callers that run it again and again on one workspace (a decode loop, a captured graph).
+ * The grid-wide agreements of the single-pass kernels need a few words of the workspace to be zero when a
+ * kernel starts; mq_ffn_i8_f32 zeroes them with a small launch of its own on every call.  Here the caller
+ * zeroes them ONCE with mq_ffn_ws_prepare and every mq_ffn_i8_f32_prepared call leaves them zero again (the
+ * quantizing kernel and the first product clear each other's words on their way), which takes that launch out
+ * of the block: three launches instead of four where the single-pass kernels apply.  Results are bit-identical
+ * to mq_ffn_i8_f32.  Between prepare and the calls, and from call to call, the caller must not write to the
+ * workspace or use it for anything else; sizes (M, d, f) must be those the workspace was prepared for; calls
+ * sharing a workspace must not overlap (same rule as for mq_ffn_i8_f32).  After a call that failed, or whose
+ * result carries the NaN of a timed-out agreement, prepare again.  mq_ffn_i8_f32 may be mixed in freely: it
+ * also leaves the words zero.  Arguments as for mq_ffn_i8_f32; mq_ffn_ws_prepare: ws of at least
+ * mq_ffn_ws_bytes(M, d, f) bytes, 256-byte aligned. */
+int mq_ffn_ws_prepare(void* ws, size_t ws_bytes, size_t M, size_t d, size_t f, void* stream);
+int mq_ffn_i8_f32_prepared(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                           const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* The same block in 16 bit (Transformer-big style): quant_int(A), product +
  * b1 + ReLU into a binary32 H kept in ws with max|H| as a by-product of the
  * epilogue, quant_int(H) straight into the packed layout with the multiplier

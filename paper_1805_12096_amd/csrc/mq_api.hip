@@ -532,9 +532,12 @@ size_t mq_ffn_ws_bytes(size_t M, size_t d, size_t f) {
   return FfnWs(M, d, f).total;
 }
 
-int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
-                  const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
-                  void* ws, size_t ws_bytes, void* stream) {
+namespace {
+// The int8 FFN block.  prepared: the caller guarantees that the agreement words of the workspace are zero (see
+// mq_ffn_ws_prepare), so no launch clears them; either way a call that took the single-pass kernels leaves them zero.
+int ffn_i8_run(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+               const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+               void* ws, size_t ws_bytes, void* stream, bool prepared) {
   if (A == nullptr || packedW1 == nullptr || sW1 == nullptr || packedW2 == nullptr || sW2 == nullptr ||
       Y == nullptr || ws == nullptr)
     return MQ_ERR_NULL;
@@ -555,16 +558,25 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   void* qH = base + L.off_qH;
   // a1 + a2: abs-max and quant_int of the input: for a million elements or more the kernel that reads A once
   // (1.9 us less per block for config 2 than the two-launch form, measured on one device in alternation)
-  unsigned* barrier = reinterpret_cast<unsigned*>(base + L.off_bar);     // cleared by the first kernel below
+  // two agreement areas: the first product's (G) and the quantizer's (Q)
+  unsigned* G = reinterpret_cast<unsigned*>(base + L.off_bar);
+  unsigned* Q = G + kBarrierWords;
   int rc = MQ_ERR_UNSUPPORTED;
+  bool q_used = false;
   if (g_ffn_single_pass && M * d >= ((size_t)1 << 20)) {
-    // one kernel reads A once and agrees on max|A| across the grid; a tiny launch clears its agreement words
-    // and the first product's
-    rc = launch_clear_words(barrier, 2 * kBarrierWords, s);
-    if (rc != MQ_OK) return rc;
-    rc = launch_absmax_quantize_pack_fused(A, M, d, 8, barrier + kBarrierWords, sA, qA, s);
+    // one kernel reads A once and agrees on max|A| across the grid.  Its agreement words and the first product's
+    // are cleared by a tiny launch -- or, with a prepared workspace, its own are zero already and it zeroes the
+    // first product's on its way (which in turn zeroes the quantizer's for the next call)
+    if (!prepared) {
+      rc = launch_clear_words(G, 2 * kBarrierWords, s);
+      if (rc != MQ_OK) return rc;
+      rc = launch_absmax_quantize_pack_fused(A, M, d, 8, Q, sA, qA, s);
+    } else {
+      rc = launch_absmax_quantize_pack_fused(A, M, d, 8, Q, sA, qA, s, G, kBarrierWords);
+    }
+    q_used = rc == MQ_OK;
   }
-  if (rc == MQ_ERR_UNSUPPORTED) rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s, barrier, kBarrierWords);
+  if (rc == MQ_ERR_UNSUPPORTED) rc = launch_absmax_quantize_pack(A, M, d, 8, part1, sA, qA, s, G, kBarrierWords);
   if (rc != MQ_OK) return rc;
   // a4 + a5, first pass: only the abs-max of relu(A W1 + b1) leaves the chip
   GemmArgs g1{};
@@ -572,8 +584,18 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1;
   // when the first product's result is at most one tile per resident workgroup, one launch does both
   // passes with the sums held in registers across a grid-wide barrier
-  rc = g_ffn_single_pass ? launch_gemm_requant_coop(g1, sH, qH, barrier, s) : MQ_ERR_UNSUPPORTED;
+  if (q_used) {
+    g1.clear_words = Q;        // the quantizer is done with them: left zero for the next call
+    g1.nclear = kBarrierWords;
+  }
+  rc = g_ffn_single_pass ? launch_gemm_requant_coop(g1, sH, qH, G, s) : MQ_ERR_UNSUPPORTED;
+  g1.clear_words = nullptr;
+  g1.nclear = 0;
   if (rc == MQ_ERR_UNSUPPORTED) {
+    if (q_used) {              // nobody else zeroes the quantizer's words on this path
+      rc = launch_clear_words(Q, kBarrierWords, s);
+      if (rc != MQ_OK) return rc;
+    }
     rc = launch_gemm_amax_partial(g1, part2, s);
     if (rc != MQ_OK) return rc;
     // second pass: the same sums again, quantized with the multiplier now known, stored as packed int8
@@ -585,6 +607,29 @@ int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* pack
   g2.qA = qH; g2.packedW = packedW2; g2.bits = 8; g2.M = M; g2.N = d; g2.K = f;
   g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
   return launch_gemm_packed(g2, kEpiDequant, s);
+}
+}  // namespace
+
+int mq_ffn_i8_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                  const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                  void* ws, size_t ws_bytes, void* stream) {
+  return ffn_i8_run(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_bytes, stream, false);
+}
+
+int mq_ffn_ws_prepare(void* ws, size_t ws_bytes, size_t M, size_t d, size_t f, void* stream) {
+  if (ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(M, f, d)) return MQ_ERR_SHAPE;
+  if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
+  const FfnWs L(M, d, f);
+  if (ws_bytes < L.total) return MQ_ERR_WORKSPACE;
+  return launch_clear_words(reinterpret_cast<unsigned*>(static_cast<uint8_t*>(ws) + L.off_bar), 2 * kBarrierWords,
+                            as_stream(stream));
+}
+
+int mq_ffn_i8_f32_prepared(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
+                           const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
+                           void* ws, size_t ws_bytes, void* stream) {
+  return ffn_i8_run(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_bytes, stream, true);
 }
 
 namespace mq {

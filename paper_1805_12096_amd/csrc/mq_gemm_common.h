@@ -31,6 +31,8 @@ struct Params {
   uint8_t* packed_out;      // output written as packed 8-bit activations [M x N]
   unsigned* barrier;        // kBarrierWords words of the single-pass epilogue's grid-wide barrier, zero at start
   unsigned long long barrier_ticks;   // longest wait there, in ticks of the 100 MHz wall clock
+  unsigned* clear_words;    // single-pass epilogue: nclear words that workgroup 0 zeroes at its start (or null)
+  unsigned nclear;
 };
 
 __device__ __forceinline__ v4i as_v4i(u4 v) { return __builtin_bit_cast(v4i, v); }

@@ -87,6 +87,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 #define MQ_STAMP(i) do { } while (0)
 #endif
   MQ_STAMP(0);
+  if constexpr (EPI == kPCoop || EPI == kPCoopFast) {
+    // the agreement words of the kernel that ran before this one (a caller that keeps them clean between calls
+    // instead of clearing them with a launch of their own): nobody uses them while this kernel runs
+    if (p.clear_words != nullptr && blockIdx.x == 0)
+      for (unsigned i = tid; i < p.nclear; i += NW * 64) p.clear_words[i] = 0u;
+  }
   unsigned tile_m, tile_n;
   tile_coords(p.tiles_m, p.tiles_n, BM >= 1024 ? 1u : 1024u / BM, tile_m, tile_n);
   const unsigned m0 = tile_m * BM, n0 = tile_n * BN;
@@ -796,6 +802,8 @@ int launch_coop(const GemmArgs& a, hipStream_t s) {
   p.packed_out = static_cast<uint8_t*>(a.packed_out);
   p.barrier = a.barrier;
   p.barrier_ticks = barrier_timeout_ticks();
+  p.clear_words = a.clear_words;
+  p.nclear = a.nclear;
   if (a.barrier == nullptr) return MQ_ERR_NULL;
   // ReLU and no partial tile: the kernel whose re-quantization is one addition per element
   const bool fast = a.relu != 0 && a.M % BM == 0 && a.N % BN == 0;

@@ -79,6 +79,9 @@ struct GemmArgs {
   float* s_out;
   void* packed_out;
   unsigned* barrier;
+  // single-pass product only: words (of some OTHER kernel's grid-wide agreement) that workgroup 0 zeroes at its start
+  unsigned* clear_words;
+  unsigned nclear;
 };
 int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
 void set_forced_variant(int v);
@@ -111,8 +114,10 @@ int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bi
                                 float* scale_out, void* packed, hipStream_t s, unsigned* clear = nullptr,
                                 unsigned nclear = 0);
 int launch_absmax_partials(const float* x, size_t n, float* partials, unsigned* count, hipStream_t s);
+// clear_words / nclear (optional): words of another kernel's agreement that workgroup 0 zeroes at its start.
 int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
-                                      float* scale_out, void* packed, hipStream_t s);
+                                      float* scale_out, void* packed, hipStream_t s, unsigned* clear_words = nullptr,
+                                      unsigned nclear = 0);
 int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,
                                   unsigned npartials, float* scale_out, void* packed, hipStream_t s);
 // Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same

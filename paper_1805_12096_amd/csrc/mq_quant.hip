@@ -377,8 +377,13 @@ template <int BITS, bool VEC, int NI>
 __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __restrict__ x, size_t rows, size_t cols,
                                                               uint8_t* __restrict__ packed, unsigned ksplit,
                                                               unsigned* barrier, unsigned long long ticks,
-                                                              float* __restrict__ scale_out) {
+                                                              float* __restrict__ scale_out, unsigned* clear_words,
+                                                              unsigned nclear) {
   constexpr int kW = 512 / kWave;
+  // words a LATER kernel's agreement wants zero (not the ones used below): a caller that keeps its agreement
+  // areas clean from call to call has this kernel and the next one clear each other's
+  if (clear_words != nullptr && blockIdx.x == 0)
+    for (unsigned i = threadIdx.x; i < nclear; i += 512) clear_words[i] = 0u;
   const PackedDims d(BITS, rows, cols);
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int sub = lane % 8;                       // which 4 floats of a 32-element fragment row
@@ -530,7 +535,7 @@ int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int 
 namespace {
 template <int BITS, bool VEC, int NI>
 int launch_fused_one(const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
-                     unsigned* barrier, float* scale_out, hipStream_t s) {
+                     unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear) {
   auto kern = k_absmax_quantize_pack<BITS, VEC, NI>;
   static int max_blocks = -1;       // workgroups the device can hold at once, asked once
   if (max_blocks < 0) {
@@ -543,18 +548,18 @@ int launch_fused_one(const float* x, size_t rows, size_t cols, uint8_t* packed, 
   }
   if (grid > (unsigned)max_blocks) return MQ_ERR_UNSUPPORTED;     // the grid-wide wait needs every workgroup resident
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, s, x, rows, cols, packed, ksplit, barrier, barrier_timeout_ticks(),
-                     scale_out);
+                     scale_out, clear_words, nclear);
   return check_hip(hipGetLastError());
 }
 
 template <int BITS, bool VEC>
 int launch_fused_ni(int ni, const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
-                    unsigned* barrier, float* scale_out, hipStream_t s) {
+                    unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear) {
   switch (ni) {
-    case 1: return launch_fused_one<BITS, VEC, 1>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
-    case 2: return launch_fused_one<BITS, VEC, 2>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
-    case 4: return launch_fused_one<BITS, VEC, 4>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
-    default: return launch_fused_one<BITS, VEC, 8>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s);
+    case 1: return launch_fused_one<BITS, VEC, 1>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+    case 2: return launch_fused_one<BITS, VEC, 2>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+    case 4: return launch_fused_one<BITS, VEC, 4>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+    default: return launch_fused_one<BITS, VEC, 8>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
   }
 }
 }  // namespace
@@ -564,7 +569,8 @@ int launch_fused_ni(int ni, const float* x, size_t rows, size_t cols, uint8_t* p
 // wave): MQ_ERR_UNSUPPORTED otherwise, nothing launched.  The kBarrierWords words at `barrier` must be
 // zero when the kernel starts.  scale_out[0] receives the multiplier (NaN if the grid-wide wait failed).
 int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
-                                      float* scale_out, void* packed, hipStream_t s) {
+                                      float* scale_out, void* packed, hipStream_t s, unsigned* clear_words,
+                                      unsigned nclear) {
   const PackedDims d(bits, rows, cols);
   const size_t row_groups = d.Np / 8;
   const size_t max_waves = (size_t)kBarrierSlots * (512 / kWave);
@@ -582,11 +588,11 @@ int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, 
   uint8_t* p = static_cast<uint8_t*>(packed);
   const bool vec = cols % 4 == 0;
   if (bits == 8) {
-    return vec ? launch_fused_ni<8, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s)
-               : launch_fused_ni<8, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s);
+    return vec ? launch_fused_ni<8, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear)
+               : launch_fused_ni<8, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
   }
-  return vec ? launch_fused_ni<16, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s)
-             : launch_fused_ni<16, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s);
+  return vec ? launch_fused_ni<16, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear)
+             : launch_fused_ni<16, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
 }
 
 // abs-max + quant_int into the packed layout in two launches, no atomics, no fill:

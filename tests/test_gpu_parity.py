@@ -815,6 +815,80 @@ def test_ffn_block_replayed_as_a_graph_of_several_steps():
     assert np.array_equal(host(Y)[rows], o2["Y"])
 
 
+@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (320, 512, 2048), (2048, 512, 2048), (2048, 512, 16384),
+                                   (2100, 512, 300), (8192, 512, 2048)])
+def test_ffn_block_on_a_prepared_workspace(M, d, f):
+    # mq_ffn_ws_prepare once, then calls that leave the agreement words as they found them: repeated calls with
+    # changing inputs, the plain entry point mixed in, both switch positions of the single-pass kernels.  The
+    # sizes cover: nothing single-pass (small), single-pass product only, both single-pass kernels (the last
+    # ones), and a first product too large for one launch behind a single-pass quantizer (f = 16384).
+    c = workloads.ffn(2, M, d, f, 0.04, 8, seed_extra=M + d + f + 5)
+    p1 = mq.prepare_weight(dev(c["W1t"]), 8)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 8)
+    b1, b2 = dev(c["b1"]), dev(c["b2"])
+    nbytes = mq.mq_ffn_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x5B, dtype=torch.uint8, device=DEV)
+    ws_plain = torch.full((nbytes,), 0x11, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+    W = torch.empty((M, d), dtype=torch.float32, device=DEV)
+    base = dev(c["A"])
+    A = base.clone()
+    mq.mq_ffn_ws_prepare(ws, nbytes, M, d, f)
+    try:
+        for r, (factor, kind) in enumerate([(1.0, "p"), (0.5, "p"), (-2.0, "plain"), (3.0, "p"), (1.0, "off"), (0.25, "p"),
+                                            (1.0, "p")]):
+            A.copy_(base * factor)
+            mq.mq_ffn_i8_f32(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, W, ws_plain, nbytes)
+            Y.fill_(float("nan"))
+            if kind == "plain":        # the plain entry point on the prepared workspace: leaves it prepared
+                mq.mq_ffn_i8_f32(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws, nbytes)
+            else:
+                mq.mq_set_ffn_single_pass(0 if kind == "off" else 1)
+                mq.mq_ffn_i8_f32_prepared(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws, nbytes)
+                mq.mq_set_ffn_single_pass(1)
+            torch.cuda.synchronize()
+            assert torch.equal(Y, W), f"call {r} ({kind})"
+    finally:
+        mq.mq_set_ffn_single_pass(1)
+    if M * f <= 1 << 22:           # the last call ran on the unscaled input: pin it to the oracle
+        o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+        s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+        o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
+        assert np.array_equal(host(Y), o2["Y"])
+
+
+def test_ffn_block_on_a_prepared_workspace_replayed_as_a_graph():
+    c = workloads.config2()
+    M, d = c["A"].shape
+    f = c["W1t"].shape[0]
+    p1 = mq.prepare_weight(dev(c["W1t"]), 8)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 8)
+    b1, b2 = dev(c["b1"]), dev(c["b2"])
+    nbytes = mq.mq_ffn_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device=DEV)
+    ws_plain = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device=DEV)
+    A = dev(c["A"])
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+    mq.mq_ffn_ws_prepare(ws, nbytes, M, d, f)
+
+    def step():
+        mq.mq_ffn_i8_f32_prepared(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws, nbytes)
+
+    g = capture_graph(step, 3)          # three consecutive blocks per replay: each relies on what the one before left
+    base = dev(c["A"])
+    for r, factor in enumerate((1.0, 0.5, -1.25, 1.0)):
+        A.copy_(base * factor)           # eager work between the replays
+        mq.mq_ffn_i8_f32(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws_plain, nbytes)
+        torch.cuda.synchronize()
+        want = Y.clone()
+        Y.fill_(float("nan"))
+        g.replay()
+        if r == 1:
+            step()                       # an eager prepared call between replays
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want), f"replay {r}"
+
+
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (300, 2048), (2000, 1024), (8192, 512), (70, 1030),
                                    (17000, 96)])
