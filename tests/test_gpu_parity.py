@@ -1025,6 +1025,38 @@ def test_single_pass_barrier_timeout_is_loud_and_recoverable():
     assert np.array_equal(gpu_ffn_fused(c), o2["Y"])
 
 
+def test_prepared_workspace_after_a_timed_out_agreement():
+    # The same failure on a prepared workspace: the call that gave up is loud (NaN) and may leave the agreement words
+    # in any state; after mq_ffn_ws_prepare the calls are right again.  (M d >= 2^20, so both single-pass kernels run.)
+    M, d, f = 2048, 512, 640
+    c = workloads.ffn(2, M, d, f, 0.04, 8, seed_extra=78)
+    o1 = oracle.linear(c["A"], c["W1t"], 8, c["b1"], True)
+    s2 = oracle.scale_from_amax(oracle.absmax(o1["Y"]), 8)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 8, c["b2"], False, sA=s2)
+    p1 = mq.prepare_weight(dev(c["W1t"]), 8)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 8)
+    A, b1, b2 = dev(c["A"]), dev(c["b1"]), dev(c["b2"])
+    nbytes = mq.mq_ffn_ws_bytes(M, d, f)
+    ws = torch.full((nbytes,), 0x77, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
+
+    def call():
+        mq.mq_ffn_i8_f32_prepared(A, M, d, f, p1.packed, p1.scale, b1, p2.packed, p2.scale, b2, Y, ws, nbytes)
+        torch.cuda.synchronize()
+        return host(Y)
+
+    mq.mq_ffn_ws_prepare(ws, nbytes, M, d, f)
+    assert np.array_equal(call(), o2["Y"])
+    try:
+        mq.mq_set_barrier_timeout_us(0)
+        assert np.all(np.isnan(call()))
+    finally:
+        mq.mq_set_barrier_timeout_us(500000)
+    mq.mq_ffn_ws_prepare(ws, nbytes, M, d, f)
+    assert np.array_equal(call(), o2["Y"])
+    assert np.array_equal(call(), o2["Y"])
+
+
 def test_single_pass_requantizing_product_refuses_what_does_not_fit():
     M, N, K = 4352, 4096, 64           # 272 tiles of 256 x 256
     pa = torch.zeros(mq.mq_packed_bytes(8, M, K), dtype=torch.uint8, device=DEV)
