@@ -114,6 +114,7 @@ def main():
         return g.replay
 
     STEPS_PER_GRAPH = 10
+    SPIN_UP_MS = 40.0
 
     def time_steps(fn, steps, warm):
         """Microseconds per step over EXACTLY `steps` steps after `warm` untimed ones.  Steps are replayed as HIP
@@ -121,6 +122,14 @@ def main():
         several microseconds of its own, which a loop over batches would not pay once per batch."""
         one = graphed(fn, 1)
         many = graphed(fn, STEPS_PER_GRAPH) if steps >= STEPS_PER_GRAPH and not args.no_graph else None
+        # The device needs some tens of milliseconds of steady work to settle at its working clock after the idle
+        # gaps of set-up (the first of two identical measurements in a process came out 5 % slower): the step runs
+        # untimed for SPIN_UP_MS before the warm-up steps.
+        t_spin = time.perf_counter()
+        while (time.perf_counter() - t_spin) * 1e3 < SPIN_UP_MS:
+            for _ in range(8):
+                (many or one)()
+            torch.cuda.synchronize()
         for _ in range(warm):
             one()
         torch.cuda.synchronize()
