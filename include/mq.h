@@ -248,7 +248,9 @@ int mq_gemm_requant_fixed_packed_i16(const void* packedA, const void* packedW, s
  * number of runs and then uses the fastest for all following calls.  Here the
  * alternatives are the tile configurations of the packed product kernels.
  * mq_autotune_gemm times every configuration valid for `bits` on an [M x K] x
- * [N x K] problem (`runs` launches each, on dummy operands inside ws), records
+ * [N x K] problem (`runs` launches each, in two rounds of which the faster counts,
+ * after about 30 ms of untimed launches that bring an idle device to its working
+ * clock; on dummy operands inside ws), records
  * the fastest in a process-wide table keyed by (bits, M, N, K) -- which all
  * packed products of that shape consult from then on, unless
  * mq_set_gemm_variant forces a configuration -- and reports it.  Results of the
