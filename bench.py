@@ -382,9 +382,13 @@ def main():
 
         qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
         qws = torch.empty(QWS, dtype=torch.uint8, device=dev)
+        # the output layer's quantizer runs on a workspace of its own, prepared once (one kernel per call, which
+        # leaves its agreement words zero); the other workloads below use the entry point that takes any workspace
+        qws_out = torch.empty(QWS, dtype=torch.uint8, device=dev)
+        mq.mq_quantize_absmax_ws_prepare(qws_out, QWS)
 
         def out_step():
-            mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, QWS)
+            mq.mq_quantize_absmax_pack_f32_prepared(Hd, M, d, 8, qp, s, qws_out, QWS)
             mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
 
         out_step()
@@ -400,14 +404,14 @@ def main():
 
         def cold_round():
             for q_ in pes:
-                mq.mq_quantize_absmax_pack_f32(Hd, M, d, 8, qp, s, qws, QWS)
+                mq.mq_quantize_absmax_pack_f32_prepared(Hd, M, d, 8, qp, s, qws_out, QWS)
                 mq.mq_gemm_argmax_packed(qp, q_.packed, M, V, d, s, q_.scale, tok, val, ws, nws)
 
         us3c = time_events(graphed(cold_round), max(5, args.steps // 10), 2) / len(pes)
         del pes
         alg3 = V * d + 4 * M * d + 8 * M
         extras["output_layer_argmax"] = {
-            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, abs-max + quant_int + fused arg-max",
+            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, abs-max + quant_int (one kernel on a prepared workspace) + fused arg-max",
             "us_per_step_warm": round(us3, 2), "tokens_per_s_warm": round(M / us3 * 1e6, 0),
             "GBps_alg_warm": round(alg3 / us3 / 1e3, 1),
             "us_per_step_cold": round(us3c, 2), "tokens_per_s_cold": round(M / us3c * 1e6, 0),

@@ -130,6 +130,16 @@ size_t mq_quantize_absmax_ws_bytes(void);
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
                                 float* scale_out, void* ws, size_t ws_bytes, void* stream);
 
+/* The same for callers that keep the workspace to themselves (a decode loop, a captured graph): the agreement
+ * words of the kernel that reads x once are zeroed ONCE by mq_quantize_absmax_ws_prepare and left zero by every
+ * mq_quantize_absmax_pack_f32_prepared call (the last workgroup done with them zeroes them), so no call spends
+ * a launch on clearing them and the one-kernel form is used for every tensor that fits it, small ones included.
+ * Results are identical to mq_quantize_absmax_pack_f32.  Nobody else may write to the workspace between the
+ * calls, and calls sharing a workspace must not overlap.  Arguments as above. */
+int mq_quantize_absmax_ws_prepare(void* ws, size_t ws_bytes, void* stream);
+int mq_quantize_absmax_pack_f32_prepared(const float* x, size_t rows, size_t cols, int bits, void* packed,
+                                         float* scale_out, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- memoized quant_int(B^T) (Section 4.3) ------------------------------ */
 
 /* Bytes of the packed parameter for an [N x K] Wt; 0 if bits is invalid or a

@@ -20,7 +20,7 @@ __all__ = [
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
     "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
-    "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
+    "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_gemm_requant_fixed_packed_i16",
     "mq_autotune_ws_bytes", "mq_autotune_gemm",
     "mq_topk_ws_bytes", "mq_gemm_topk_packed",
@@ -57,7 +57,7 @@ def exported_symbols():
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
             "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
-            "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_gemm_amax_ws_bytes",
+            "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
             "mq_gemm_requant_fixed_packed_i16",
             "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_topk_ws_bytes", "mq_gemm_topk_packed", "mq_running_average_f32", "mq_concat2_f32",
@@ -117,6 +117,8 @@ def load_library():
     lib.mq_quantize_absmax_ws_bytes.restype = sz
     lib.mq_quantize_absmax_ws_bytes.argtypes = []
     lib.mq_quantize_absmax_pack_f32.argtypes = [vp, sz, sz, ci, vp, vp, vp, sz, vp]
+    lib.mq_quantize_absmax_pack_f32_prepared.argtypes = [vp, sz, sz, ci, vp, vp, vp, sz, vp]
+    lib.mq_quantize_absmax_ws_prepare.argtypes = [vp, sz, vp]
     lib.mq_gemm_amax_ws_bytes.restype = sz
     lib.mq_gemm_amax_ws_bytes.argtypes = [sz, sz]
     lib.mq_gemm_amax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, ci, vp, sz, vp]
@@ -291,6 +293,17 @@ def mq_quantize_absmax_ws_bytes() -> int:
 def mq_quantize_absmax_pack_f32(x, rows, cols, bits, packed, scale_out, ws, ws_bytes, stream=None):
     _check(load_library().mq_quantize_absmax_pack_f32(_p(x), rows, cols, bits, _p(packed), _p(scale_out), _p(ws),
                                                       ws_bytes, _stream(stream)), "mq_quantize_absmax_pack_f32")
+
+
+def mq_quantize_absmax_ws_prepare(ws, ws_bytes, stream=None):
+    _check(load_library().mq_quantize_absmax_ws_prepare(_p(ws), ws_bytes, _stream(stream)),
+           "mq_quantize_absmax_ws_prepare")
+
+
+def mq_quantize_absmax_pack_f32_prepared(x, rows, cols, bits, packed, scale_out, ws, ws_bytes, stream=None):
+    _check(load_library().mq_quantize_absmax_pack_f32_prepared(_p(x), rows, cols, bits, _p(packed), _p(scale_out),
+                                                               _p(ws), ws_bytes, _stream(stream)),
+           "mq_quantize_absmax_pack_f32_prepared")
 
 
 def mq_gemm_amax_ws_bytes(M, N) -> int:

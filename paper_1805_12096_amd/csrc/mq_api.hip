@@ -144,9 +144,35 @@ int mq_set_quantize_single_pass(int enable) {
   return MQ_OK;
 }
 
-size_t mq_quantize_absmax_ws_bytes(void) {      // one workspace serves both forms
-  const size_t partials = kAbsmaxPartials * sizeof(float), barrier = round_up(kBarrierWords * sizeof(unsigned), 256);
-  return partials > barrier ? partials : barrier;
+size_t mq_quantize_absmax_ws_bytes(void) {      // agreement words, then partial maxima: one workspace serves every form
+  return round_up(kBarrierWords * sizeof(unsigned), 256) + kAbsmaxPartials * sizeof(float);
+}
+
+int mq_quantize_absmax_ws_prepare(void* ws, size_t ws_bytes, void* stream) {
+  if (ws == nullptr) return MQ_ERR_NULL;
+  if (!aligned(ws, 16)) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_quantize_absmax_ws_bytes()) return MQ_ERR_WORKSPACE;
+  return launch_clear_words(static_cast<unsigned*>(ws), kBarrierWords, as_stream(stream));
+}
+
+int mq_quantize_absmax_pack_f32_prepared(const float* x, size_t rows, size_t cols, int bits, void* packed,
+                                         float* scale_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!bits_ok(bits)) return MQ_ERR_DTYPE;
+  if (x == nullptr || scale_out == nullptr || packed == nullptr || ws == nullptr) return MQ_ERR_NULL;
+  if (!dims_ok(1, rows, cols)) return MQ_ERR_SHAPE;
+  if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(scale_out, 4) || !aligned(ws, 16)) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_quantize_absmax_ws_bytes()) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  // Whatever fits the registers of one resident grid takes the kernel that reads x once; it finds its agreement
+  // words zero and leaves them zero.  Without a clearing launch in front of it that kernel also wins for small
+  // tensors, where the plain entry point prefers two tiny kernels.
+  if (g_quantize_single_pass != 0) {
+    const int rc = launch_absmax_quantize_pack_fused(x, rows, cols, bits, static_cast<unsigned*>(ws), scale_out, packed,
+                                                     s, nullptr, 0, 1);
+    if (rc != MQ_ERR_UNSUPPORTED) return rc;
+  }
+  float* partials = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + round_up(kBarrierWords * sizeof(unsigned), 256));
+  return launch_absmax_quantize_pack(x, rows, cols, bits, partials, scale_out, packed, s);
 }
 
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,

@@ -31,7 +31,9 @@ constexpr unsigned kBarrierSlots = 256;
 // blockIdx.x % kBarrierCopies: loads of one cache line from the whole chip are served one after the other
 // (about 12 ns each), so 256 pollers on one copy would take 3 us per round, 32 take 0.4 us.
 constexpr unsigned kBarrierCopies = 8;
-static_assert(kBarrierSlots % 64 == 0 && kBarrierCopies * kBarrierSlots + 1 <= kBarrierWords, "barrier layout");
+static_assert(kBarrierSlots % 64 == 0 && kBarrierCopies * kBarrierSlots + 2 <= kBarrierWords, "barrier layout");
+// Word behind the sticky one: counts the workgroups that are done with the area (see grid_max_retire).
+constexpr unsigned kBarrierDoneWord = kBarrierCopies * kBarrierSlots + 1;
 
 // Maximum of an unsigned value over the 64 lanes, the same in every lane: inside rows of 16 lanes by
 // data-parallel-primitive moves (swap neighbours, swap pairs, mirror the half rows, mirror the rows),
@@ -85,6 +87,16 @@ __device__ __forceinline__ float grid_max_collect(unsigned* barrier, unsigned lo
     __builtin_amdgcn_s_sleep(2);
   }
   return __uint_as_float(wave_max_u32(best) - 1u);
+}
+
+// For kernels that leave the area as they found it, all zero, so that the next launch needs no clearing launch
+// before it.  One thread of every workgroup calls this once, after its workgroup's collect (and, for the workgroup
+// that publishes the multiplier, after its look at the sticky word); the value returned to the LAST caller of the
+// grid is gridDim.x - 1: by then no workgroup will read or write the area again, and that workgroup zeroes all
+// kBarrierWords words.  This is the one read-modify-write on a shared word in the protocol; it is not on the
+// path of anybody's wait.
+__device__ __forceinline__ unsigned grid_max_retire(unsigned* barrier) {
+  return atomicAdd(barrier + kBarrierDoneWord, 1u);
 }
 
 // True if some workgroup of this launch gave up waiting (to be read after the caller's own collect).

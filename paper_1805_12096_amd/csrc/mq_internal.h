@@ -115,9 +115,10 @@ int launch_absmax_quantize_pack(const float* x, size_t rows, size_t cols, int bi
                                 unsigned nclear = 0);
 int launch_absmax_partials(const float* x, size_t n, float* partials, unsigned* count, hipStream_t s);
 // clear_words / nclear (optional): words of another kernel's agreement that workgroup 0 zeroes at its start.
+// self_clean: the kernel leaves its own kBarrierWords words at `barrier` all zero (the last workgroup done zeroes them).
 int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
                                       float* scale_out, void* packed, hipStream_t s, unsigned* clear_words = nullptr,
-                                      unsigned nclear = 0);
+                                      unsigned nclear = 0, int self_clean = 0);
 int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int bits, const float* partials,
                                   unsigned npartials, float* scale_out, void* packed, hipStream_t s);
 // Fused FFN pieces (8 bit): product + bias + ReLU reduced to per-tile abs-max partials, and the same

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __res
                                                               uint8_t* __restrict__ packed, unsigned ksplit,
                                                               unsigned* barrier, unsigned long long ticks,
                                                               float* __restrict__ scale_out, unsigned* clear_words,
-                                                              unsigned nclear) {
+                                                              unsigned nclear, int self_clean) {
   constexpr int kW = 512 / kWave;
   // words a LATER kernel's agreement wants zero (not the ones used below): a caller that keeps its agreement
   // areas clean from call to call has this kernel and the next one clear each other's
@@ -435,6 +435,10 @@ __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __res
   }
   __syncthreads();
   const float amax = red[0];
+  // self_clean: the agreement area is left all zero.  Every workgroup but the first is done with it here (its
+  // count goes out now and is looked at after the stores); the first still has to look at the sticky word.
+  unsigned retired_before = 0u;
+  if (self_clean && blockIdx.x != 0 && threadIdx.x == 0) retired_before = grid_max_retire(barrier);
   const float lim = BITS == 8 ? 127.0f : 32767.0f;
   const float s = (amax > 0.0f) ? __fdiv_rn(lim, amax) : 1.0f;
   if (active) {
@@ -467,7 +471,17 @@ __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __res
       if (sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = grid_max_failed(barrier) ? __builtin_nanf("") : s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *scale_out = grid_max_failed(barrier) ? __builtin_nanf("") : s;
+    if (self_clean) retired_before = grid_max_retire(barrier);
+  }
+  if (self_clean) {
+    __shared__ unsigned last;
+    if (threadIdx.x == 0) last = retired_before == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (last != 0u)
+      for (unsigned i = threadIdx.x; i < kBarrierWords; i += 512) barrier[i] = 0u;
+  }
 }
 
 }  // namespace
@@ -535,7 +549,8 @@ int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int 
 namespace {
 template <int BITS, bool VEC, int NI>
 int launch_fused_one(const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
-                     unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear) {
+                     unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear,
+                     int self_clean) {
   auto kern = k_absmax_quantize_pack<BITS, VEC, NI>;
   static int max_blocks = -1;       // workgroups the device can hold at once, asked once
   if (max_blocks < 0) {
@@ -548,18 +563,19 @@ int launch_fused_one(const float* x, size_t rows, size_t cols, uint8_t* packed, 
   }
   if (grid > (unsigned)max_blocks) return MQ_ERR_UNSUPPORTED;     // the grid-wide wait needs every workgroup resident
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), 0, s, x, rows, cols, packed, ksplit, barrier, barrier_timeout_ticks(),
-                     scale_out, clear_words, nclear);
+                     scale_out, clear_words, nclear, self_clean);
   return check_hip(hipGetLastError());
 }
 
 template <int BITS, bool VEC>
 int launch_fused_ni(int ni, const float* x, size_t rows, size_t cols, uint8_t* packed, unsigned ksplit, unsigned grid,
-                    unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear) {
+                    unsigned* barrier, float* scale_out, hipStream_t s, unsigned* clear_words, unsigned nclear,
+                    int self_clean) {
   switch (ni) {
-    case 1: return launch_fused_one<BITS, VEC, 1>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
-    case 2: return launch_fused_one<BITS, VEC, 2>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
-    case 4: return launch_fused_one<BITS, VEC, 4>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
-    default: return launch_fused_one<BITS, VEC, 8>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+    case 1: return launch_fused_one<BITS, VEC, 1>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
+    case 2: return launch_fused_one<BITS, VEC, 2>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
+    case 4: return launch_fused_one<BITS, VEC, 4>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
+    default: return launch_fused_one<BITS, VEC, 8>(x, rows, cols, packed, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
   }
 }
 }  // namespace
@@ -570,7 +586,7 @@ int launch_fused_ni(int ni, const float* x, size_t rows, size_t cols, uint8_t* p
 // zero when the kernel starts.  scale_out[0] receives the multiplier (NaN if the grid-wide wait failed).
 int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, int bits, unsigned* barrier,
                                       float* scale_out, void* packed, hipStream_t s, unsigned* clear_words,
-                                      unsigned nclear) {
+                                      unsigned nclear, int self_clean) {
   const PackedDims d(bits, rows, cols);
   const size_t row_groups = d.Np / 8;
   const size_t max_waves = (size_t)kBarrierSlots * (512 / kWave);
@@ -588,11 +604,11 @@ int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, 
   uint8_t* p = static_cast<uint8_t*>(packed);
   const bool vec = cols % 4 == 0;
   if (bits == 8) {
-    return vec ? launch_fused_ni<8, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear)
-               : launch_fused_ni<8, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+    return vec ? launch_fused_ni<8, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean)
+               : launch_fused_ni<8, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
   }
-  return vec ? launch_fused_ni<16, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear)
-             : launch_fused_ni<16, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear);
+  return vec ? launch_fused_ni<16, true>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean)
+             : launch_fused_ni<16, false>(ni, x, rows, cols, p, ksplit, grid, barrier, scale_out, s, clear_words, nclear, self_clean);
 }
 
 // abs-max + quant_int into the packed layout in two launches, no atomics, no fill:

@@ -919,6 +919,55 @@ def test_quantize_absmax_pack(bits, shape):
         assert torch.equal(o, outs[0])
 
 
+@pytest.mark.parametrize("bits", [8, 16])
+@pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (300, 2048), (2000, 1024), (8192, 512), (70, 1030),
+                                   (17000, 96)])
+def test_quantize_absmax_pack_on_a_prepared_workspace(bits, shape):
+    # the workspace's agreement words are zeroed once; every call leaves them zero (the kernel that reads x once
+    # cleans up after itself, the two-pass form never touches them): five calls in a row with changing inputs,
+    # with the one-kernel form switched off in between, then three replays of a graph of two calls
+    rng = np.random.default_rng(shape[0] * 7 + shape[1] + bits)
+    base = rng.standard_normal(shape, dtype=np.float32) * np.float32(0.3)
+    nb = mq.mq_quantize_absmax_ws_bytes()
+    ws = torch.full((nb,), 0x6D, dtype=torch.uint8, device=DEV)
+    ws_plain = torch.full((nb,), 0x6D, dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_absmax_ws_prepare(ws, nb)
+    x = dev(base)
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    s_plain = torch.empty(1, dtype=torch.float32, device=DEV)
+    packed = torch.empty(mq.mq_packed_bytes(bits, *shape), dtype=torch.uint8, device=DEV)
+    packed_plain = torch.empty_like(packed)
+
+    def call():
+        mq.mq_quantize_absmax_pack_f32_prepared(x, shape[0], shape[1], bits, packed, s, ws, nb)
+
+    def check(tag):
+        mq.mq_quantize_absmax_pack_f32(x, shape[0], shape[1], bits, packed_plain, s_plain, ws_plain, nb)
+        torch.cuda.synchronize()
+        assert torch.equal(s, s_plain) and torch.equal(packed, packed_plain), tag
+
+    try:
+        for r, (factor, single) in enumerate([(1.0, 1), (0.5, 1), (-3.0, 0), (2.0, 1), (1.0, 1)]):
+            x.copy_(dev(base) * factor)
+            packed.fill_(0x5A)
+            mq.mq_set_quantize_single_pass(single)
+            call()
+            mq.mq_set_quantize_single_pass(1)
+            check(f"call {r}")
+    finally:
+        mq.mq_set_quantize_single_pass(1)
+    oq, os_ = oracle.quant_int_absmax(base, bits)
+    q = torch.empty(shape, dtype=QT[bits], device=DEV)
+    mq.mq_unpack_weight(packed, bits, shape[0], shape[1], q)
+    assert host(s)[0] == os_ and np.array_equal(host(q), oq)
+    g = capture_graph(call, 2)
+    for r, factor in enumerate((0.75, -1.5, 1.0)):
+        x.copy_(dev(base) * factor)
+        packed.fill_(0x33)
+        g.replay()
+        check(f"replay {r}")
+
+
 def test_quantize_absmax_pack_skips_nan_and_handles_zero_tensor():
     x = np.zeros((40, 70), dtype=np.float32)
     nb = mq.mq_quantize_absmax_ws_bytes()
