@@ -968,6 +968,33 @@ def test_quantize_absmax_pack_on_a_prepared_workspace(bits, shape):
         check(f"replay {r}")
 
 
+def test_prepared_quantizer_cleans_up_after_a_timed_out_agreement():
+    # every workgroup gives up at once: the multiplier is NaN, all kernels end, and since the workgroups still count
+    # themselves out the last one leaves the agreement words zero: the next call is right without preparing again
+    shape = (2000, 1024)
+    rng = np.random.default_rng(99)
+    xh = rng.standard_normal(shape, dtype=np.float32)
+    oq, os_ = oracle.quant_int_absmax(xh, 8)
+    nb = mq.mq_quantize_absmax_ws_bytes()
+    ws = torch.full((nb,), 0x42, dtype=torch.uint8, device=DEV)
+    mq.mq_quantize_absmax_ws_prepare(ws, nb)
+    x = dev(xh)
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    packed = torch.empty(mq.mq_packed_bytes(8, *shape), dtype=torch.uint8, device=DEV)
+    try:
+        mq.mq_set_barrier_timeout_us(0)
+        mq.mq_quantize_absmax_pack_f32_prepared(x, shape[0], shape[1], 8, packed, s, ws, nb)
+        assert np.isnan(host(s)[0])
+    finally:
+        mq.mq_set_barrier_timeout_us(500000)
+    assert not ws[: 4 * (8 * 256 + 64)].any().item()
+    for _ in range(2):
+        mq.mq_quantize_absmax_pack_f32_prepared(x, shape[0], shape[1], 8, packed, s, ws, nb)
+        q = torch.empty(shape, dtype=torch.int8, device=DEV)
+        mq.mq_unpack_weight(packed, 8, shape[0], shape[1], q)
+        assert host(s)[0] == os_ and np.array_equal(host(q), oq)
+
+
 def test_quantize_absmax_pack_skips_nan_and_handles_zero_tensor():
     x = np.zeros((40, 70), dtype=np.float32)
     nb = mq.mq_quantize_absmax_ws_bytes()
