@@ -135,7 +135,8 @@ int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bi
  * mq_quantize_absmax_pack_f32_prepared call (the last workgroup done with them zeroes them), so no call spends
  * a launch on clearing them and the one-kernel form is used for every tensor that fits it, small ones included.
  * Results are identical to mq_quantize_absmax_pack_f32.  Nobody else may write to the workspace between the
- * calls, and calls sharing a workspace must not overlap.  Arguments as above. */
+ * calls, and calls sharing a workspace must not overlap.  A call whose agreement timed out (multiplier NaN)
+ * still leaves the words zero.  Arguments as above. */
 int mq_quantize_absmax_ws_prepare(void* ws, size_t ws_bytes, void* stream);
 int mq_quantize_absmax_pack_f32_prepared(const float* x, size_t rows, size_t cols, int bits, void* packed,
                                          float* scale_out, void* ws, size_t ws_bytes, void* stream);
