@@ -615,7 +615,8 @@ int ffn_i8_run(const float* A, size_t M, size_t d, size_t f, const void* packedW
   unsigned* Q = G + kBarrierWords;
   int rc = MQ_ERR_UNSUPPORTED;
   bool q_used = false;
-  if (g_ffn_single_pass && M * d >= ((size_t)1 << 20)) {
+  // (with a clearing launch in front of it that kernel only pays from a million elements on; without, always)
+  if (g_ffn_single_pass && (prepared || M * d >= ((size_t)1 << 20))) {
     // one kernel reads A once and agrees on max|A| across the grid.  Its agreement words and the first product's
     // are cleared by a tiny launch -- or, with a prepared workspace, its own are zero already and it zeroes the
     // first product's on its way (which in turn zeroes the quantizer's for the next call)
