@@ -37,6 +37,36 @@
  *     the abs-max and quantizes to 0.
  *   - Integer sums are exact modulo 2^32 (two's complement wrap), independent of
  *     tiling.  With 8-bit operands no sum can wrap for K <= 133 144.
+ *
+ * Single-pass kernels (grid-wide agreement inside one launch)
+ *   A per-tensor multiplier Qmax / max|x| needs the maximum over the whole tensor
+ *   before the first element can be converted.  Where the tensor fits the registers
+ *   of one resident grid, some calls do both in ONE launch: every workgroup
+ *   publishes its maximum in a slot of the workspace, waits until all slots are
+ *   filled and converts from registers.  These are mq_gemm_requant_single_packed,
+ *   mq_ffn_i8_f32 / mq_ffn_i8_f32_prepared (first product and input quantizer),
+ *   mq_quantize_absmax_pack_f32 (from 2^20 elements) and its _prepared form.
+ *   What they need and what they do when they do not get it:
+ *   - The agreement area is 2112 words of the workspace: eight copies of 256 slots
+ *     (one per workgroup; eight so that pollers spread over cache lines), one sticky
+ *     failure word, one count of workgroups that are done.  It must be all zero when
+ *     the kernel starts; the plain entry points clear it with a small launch, the
+ *     _prepared ones keep it zero from call to call.
+ *   - The launcher only takes this path if the grid fits the device when the device
+ *     is EMPTY (occupancy x compute units >= workgroups, and at most 256 workgroups;
+ *     mq_single_pass_fits is that test).  It cannot know what else is running.  These
+ *     calls therefore need the GPU to themselves while they run: no kernel of another
+ *     stream or process resident at the same time, and never two single-pass calls
+ *     in flight at once (not even on separate workspaces).  Otherwise some workgroups
+ *     may not become resident while the others wait for them.
+ *   - The wait is bounded (mq_set_barrier_timeout_us, default 0.5 s).  A workgroup
+ *     that gives up raises the sticky word; the multiplier the call publishes
+ *     (scale_out, or the internal one of the FFN block) is then NaN and so is every
+ *     float computed from it; the status of the call is still MQ_OK, because nothing
+ *     is known on the host.  Check the multiplier (or the output) for NaN where
+ *     co-residency cannot be excluded, or switch the single-pass kernels off
+ *     (mq_set_ffn_single_pass(0), mq_set_quantize_single_pass(0)): the two-pass forms
+ *     give the same bits and wait for nothing.
  */
 #ifndef MQ_H_
 #define MQ_H_
@@ -124,7 +154,10 @@ int mq_quantize_pack_f32(const float* x, size_t rows, size_t cols, int bits, con
  * the two-pass form, (2) the single-pass form whenever the tensor fits, (1) is
  * the default choice by size.
  * ws: device, 16-byte aligned, mq_quantize_absmax_ws_bytes(), contents
- * irrelevant on entry. */
+ * irrelevant on entry.  Layout: the agreement area first, the partial maxima of
+ * the two-pass form behind it; the call leaves the agreement area as the
+ * _prepared form below wants it (all zero) whenever it touched it, so the two
+ * entry points may share a workspace. */
 int mq_set_quantize_single_pass(int enable);
 size_t mq_quantize_absmax_ws_bytes(void);
 int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bits, void* packed,
@@ -219,16 +252,22 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
 /* The same result in ONE pass over the operands, for results small enough that
  * every 256 x 256 tile is resident on the chip at once (at most one tile per
  * compute unit; MQ_ERR_UNSUPPORTED beyond that, nothing computed): each tile
- * keeps its sums in registers while all workgroups agree on max|y| through
- * two words of ws, then quantizes and stores.  Two launches (clearing the two
- * words, the product).  The wait for the other workgroups is bounded (0.5 s);
+ * keeps its sums in registers while all workgroups agree on max|y| through the
+ * agreement area at the start of ws (2112 words, see "Single-pass kernels" at
+ * the top), then quantizes and stores.  Two launches (clearing the area, the
+ * product).  The wait for the other workgroups is bounded (0.5 s);
  * should it ever expire, scale_out[0] is set to NaN so that nothing computed
- * from it can pass for a result.  Arguments and results as
- * mq_gemm_requant_packed; ws is written here.
+ * from it can pass for a result.  Needs the GPU to itself (see the top).
+ * Arguments and results as mq_gemm_requant_packed; ws is written here.
+ * mq_single_pass_fits(M, N, resident) is the launcher's size test on its own
+ * (no device needed): 1 if an [M x N] result has at most min(resident, 256)
+ * tiles of 256 x 256, where `resident` is the number of workgroups of the kernel
+ * the device holds at once (occupancy x compute units; 256 on MI355X).
  * mq_set_barrier_timeout_us changes the bound on the wait (default 500000, at
  * most 10^7; 0 makes every waiter give up at once, which is how the tests
  * reach the failure path without a kernel that hangs). */
 int mq_set_barrier_timeout_us(unsigned us);
+int mq_single_pass_fits(size_t M, size_t N, size_t resident);
 int mq_gemm_requant_single_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
                                   const float* sA, const float* sW, const float* bias, int relu,
                                   void* ws, size_t ws_bytes, float* scale_out, void* packed_out,
@@ -309,8 +348,10 @@ int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, si
  * themselves, no compacted copy is made):
  *   tok[m] = the listed row with the largest sum (the smallest id on ties),
  *   maxlogit[m] as in mq_gemm_argmax.
- * Ids outside [0, N) are undefined behaviour.  Same limits and workspace as
- * mq_gemm_argmax_packed. */
+ * The list is the caller's contract; it is not validated on the host (it lives in device memory).  An id outside
+ * [0, N) never reads outside the embedding: the kernel scores row 0 (for a negative id) or row N - 1 in its
+ * place, and if that candidate wins, tok[m] is the id as listed.  A list that is not ascending only changes
+ * which of several equal sums wins.  Same limits and workspace as mq_gemm_argmax_packed. */
 int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int32_t* shortlist,
                              size_t shortlist_len, size_t M, size_t N, size_t K,
                              const float* sA, const float* sW, int32_t* tok, float* maxlogit,

@@ -189,10 +189,14 @@ int mq_quantize_absmax_pack_f32(const float* x, size_t rows, size_t cols, int bi
     // that reads x once; larger tensors take the two-pass form below
     int rc = launch_clear_words(static_cast<unsigned*>(ws), kBarrierWords, s);
     if (rc != MQ_OK) return rc;
-    rc = launch_absmax_quantize_pack_fused(x, rows, cols, bits, static_cast<unsigned*>(ws), scale_out, packed, s);
+    // (self-cleaning like the prepared form: a prepared workspace handed to this entry point stays prepared)
+    rc = launch_absmax_quantize_pack_fused(x, rows, cols, bits, static_cast<unsigned*>(ws), scale_out, packed, s, nullptr,
+                                           0, 1);
     if (rc != MQ_ERR_UNSUPPORTED) return rc;
   }
-  return launch_absmax_quantize_pack(x, rows, cols, bits, static_cast<float*>(ws), scale_out, packed, s);
+  // the partial maxima live behind the agreement words, as in the prepared form: this path never touches those
+  float* partials = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + round_up(kBarrierWords * sizeof(unsigned), 256));
+  return launch_absmax_quantize_pack(x, rows, cols, bits, partials, scale_out, packed, s);
 }
 
 size_t mq_packed_bytes(int bits, size_t N, size_t K) {
@@ -323,6 +327,10 @@ int mq_gemm_requant_packed(const void* packedA, const void* packedW, size_t M, s
   a.qA = packedA; a.packedW = packedW; a.bits = 8; a.M = M; a.N = N; a.K = K;
   a.sA = sA; a.sW = sW; a.bias = bias; a.relu = relu != 0;
   return launch_gemm_requant(a, static_cast<const float*>(ws), scale_out, packed_out, as_stream(stream));
+}
+
+int mq_single_pass_fits(size_t M, size_t N, size_t resident) {
+  return single_pass_fits(M, N, resident) ? 1 : 0;
 }
 
 int mq_gemm_requant_single_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,

@@ -79,14 +79,6 @@ __device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, 
 // output product restricted to a subset of the vocabulary).  A unit is then 16 consecutive shortlist
 // positions; since every lane of a direct-to-LDS load supplies its own address, gathering the 16
 // rows costs nothing extra.  Indices are candidate positions; the reduce kernel maps them back.
-#ifdef MQ_TS
-#ifndef MQ_TS_TID
-#define MQ_TS_TID 0
-#endif
-#define MQ_ASTAMP(i) do { if (threadIdx.x == MQ_TS_TID) (p.partial + (1u << 20) / 8 * 2)[blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define MQ_ASTAMP(i) do { } while (0)
-#endif
 
 // BEAM > 1 (beam search, Table 2's b = 2 and b = 4 rows): every accumulator register keeps its BEAM best
 // keys instead of one (sorted insertion: BEAM max / min pairs per candidate), and every sentence tile keeps
@@ -100,7 +92,6 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
 
   const int lane = threadIdx.x % 64;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-  MQ_ASTAMP(0);
   const PackedDims dA(8, p.M, p.K), dW(8, p.N, p.K);
   const unsigned kgroups = (unsigned)(dW.kfrags / 2);          // real K groups (<= KG)
   const unsigned nunits = GATHER ? (p.L + 15) / 16 : (unsigned)(dW.nblocks * 2);   // 16-candidate units
@@ -118,7 +109,10 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   if (GATHER) {
     for (unsigned i = threadIdx.x; i < nlocal * 16; i += kWaves * 64) {
       const unsigned pos = (first + (i / 16) * stride) * 16 + i % 16;
-      rows_lds[i] = pos < p.L ? p.shortlist[pos] : p.shortlist[0];   // positions past the end are masked later
+      // positions past the end are masked later; an id outside [0, N) reads the nearest row instead of memory
+      // outside the embedding (the token reported for it is the id as listed)
+      const int id = pos < p.L ? p.shortlist[pos] : p.shortlist[0];
+      rows_lds[i] = min(max(id, 0), (int)p.N - 1);
     }
     __syncthreads();
   }
@@ -241,10 +235,6 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
                    const v4i (&e)[KG], v4i (&enext)[KG]) {
     constexpr int NT = decltype(nt_tag)::value;
     land(newest);
-#ifdef MQ_TS
-    if (threadIdx.x == MQ_TS_TID && s < 12)
-      reinterpret_cast<unsigned long long*>(smem + (S + 1) * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s] = wall_clock64();
-#endif
     // everybody is past stage s - 1 (and has its copy of stage s in registers), so slot s - 1 can be refilled
     if constexpr (decltype(refill_tag)::value) issue(s + S - 1);
     // the next unit's LDS reads are spread between the MFMA groups: eight reads in a row would fill the
@@ -319,7 +309,6 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
   if (ntl == TPW) run(std::integral_constant<int, TPW>{});
   else run(std::integral_constant<int, TPW - 1>{});
   wait_vmcnt_n(0);      // the refills past the last unit are still landing in their slots
-  MQ_ASTAMP(14);
   // the last stage's sums are still pending; only a workgroup's last unit can reach past N, where
   // the rows are padding and must not compete (needs at least two workgroups, which the launcher
   // guarantees whenever there is more than one unit)
@@ -427,13 +416,6 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     const unsigned m = (wave + kWaves * i) * 16 + lane % 16;
     if (lane < 16 && m < p.M) p.partial[(size_t)m * gridDim.x + blockIdx.x] = key;
   }
-#ifdef MQ_TS
-  if (threadIdx.x == MQ_TS_TID)
-    for (unsigned s = 0; s < nlocal && s < 12; ++s)
-      (p.partial + (1u << 20) / 8 * 2)[blockIdx.x * 16 + 2 + s] =
-          reinterpret_cast<unsigned long long*>(smem + (S + 1) * STAGE + (GATHER ? 255 * 16 * 4 : 0))[s];
-#endif
-  MQ_ASTAMP(15);
 }
 
 // One wave per sentence: maximum over the per-workgroup keys, then decode.
@@ -536,11 +518,7 @@ __global__ __launch_bounds__(256) void k_topk_reduce(const unsigned long long* _
 
 template <int TPW, bool GATHER, int BEAM = 1>
 int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
-  constexpr size_t smem = (size_t)(kStages + 1) * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0)
-#ifdef MQ_TS
-                          + 256
-#endif
-      ;
+  constexpr size_t smem = (size_t)(kStages + 1) * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0);
   auto kern = k_argmax_stream<TPW, GATHER, BEAM>;
   static bool attr_done = false;
   if (!attr_done) {

@@ -77,16 +77,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
   const int lane = tid % 64;
   const int wave = tid / 64;
   const int wm = wave / WN, wn = wave % WN;
-#ifdef MQ_TS
-  // instrumented builds only: wall-clock stamps per workgroup, behind the barrier words (single-pass kernel)
-  // or behind the max|y| word (dequantizing kernel called with a large enough buffer there)
-#define MQ_STAMP(i) do { if (tid == 0) { \
-    if (EPI == kPCoop || EPI == kPCoopFast) reinterpret_cast<unsigned long long*>(p.barrier + kBarrierWords)[blockIdx.x * 8 + (i)] = wall_clock64(); \
-    else if (EPI == kPDequant && p.out_amax != nullptr) reinterpret_cast<unsigned long long*>(p.out_amax)[8 + blockIdx.x * 8 + (i)] = wall_clock64(); } } while (0)
-#else
-#define MQ_STAMP(i) do { } while (0)
-#endif
-  MQ_STAMP(0);
   if constexpr (EPI == kPCoop || EPI == kPCoopFast) {
     // the agreement words of the kernel that ran before this one (a caller that keeps them clean between calls
     // instead of clearing them with a launch of their own): nobody uses them while this kernel runs
@@ -275,7 +265,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     if (longk) wait_vmcnt((S - 3) * L + L / 2);      // everything but stage 0 may still be in flight
     else wait_vmcnt(0);
     block_barrier();
-    MQ_STAMP(2);                  // first stage landed
 #pragma unroll
     for (int r = 0; r < R; ++r) read_one(f0, smem + lane * 16, 0, r);
     // One K step: slice 0 of stage kt (slice 1's fragments stream in behind it), the wait for stage kt + 1 and the
@@ -361,7 +350,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     wait_vmcnt(0);     // dummy loads of the tail must not outlive the stages' reuse in the epilogue
   }
 
-  MQ_STAMP(1);
   if constexpr (EPI == kPRequant && BITS == 16) {
     // 16-bit product re-quantized with a multiplier known in advance (the paper's 16-bit scheme, Section 4.2:
     // one fixed multiplier): y = relu?(fma(float(sum), u, bias[n])), q = clamp(rne(y s), +-32767), written as the
@@ -449,10 +437,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) biasv[nt][j] = bias_at(wn0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4);
     }
-#ifdef MQ_TS
-    if (u == 12345.f) return;
-    MQ_STAMP(6);
-#endif
 
     // ---- max|y| of this block, y = relu?(fma((float)acc, u, bias[n])) as in the storing epilogue.
     // For one column n the value y is a monotonic function of the integer sum (both
@@ -521,10 +505,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
         else if (interior) reduce_rows(std::true_type{}, std::false_type{});
         else reduce_rows(std::false_type{}, std::false_type{});
       }
-#ifdef MQ_TS
-      if (local == 12345.f) return;
-      MQ_STAMP(7);
-#endif
       local = __uint_as_float(wave_max_u32(__float_as_uint(local)));   // local >= 0: bit patterns order like floats
       if (lane == 0) red[wave] = local;
       __syncthreads();
@@ -556,14 +536,11 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
           float m = red[0];
 #pragma unroll
           for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
-          MQ_STAMP(2);
           grid_max_publish(p.barrier, m);
         }
         sums_to_y();
         if (wave == 0) {
-          MQ_STAMP(3);
           const float amax = grid_max_collect(p.barrier, p.barrier_ticks);
-          MQ_STAMP(4);
           if (lane == 0) red[0] = amax;
         }
         __syncthreads();
@@ -670,7 +647,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
         if (interior) store_tiles(std::true_type{});
         else store_tiles(std::false_type{});
       }
-      MQ_STAMP(5);
       if constexpr (COOP) {
         if (blockIdx.x == 0 && tid == 0) {
           *p.s_out = grid_max_failed(p.barrier) ? __builtin_nanf("") : s2;
@@ -682,7 +658,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
     store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
         acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum, EPI == kPDequant ? bias_pre : nullptr);
-    MQ_STAMP(5);
   }
 }
 
@@ -822,7 +797,8 @@ int launch_coop(const GemmArgs& a, hipStream_t s) {
     max_blocks = per_cu * cus;
   }
   // the grid-wide barrier needs every workgroup resident at the same time (and has a slot)
-  if (tiles_m * tiles_n > (size_t)max_blocks || tiles_m * tiles_n > kBarrierSlots) return MQ_ERR_UNSUPPORTED;
+  static_assert(BM == 256 && BN == 256 && kBarrierSlots == 256, "single_pass_fits assumes this tile and slot count");
+  if (!single_pass_fits(a.M, a.N, (size_t)max_blocks)) return MQ_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * 64), smem, s, p);
   return check_hip(hipGetLastError());
 }

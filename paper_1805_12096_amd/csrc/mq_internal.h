@@ -129,6 +129,13 @@ int launch_gemm_requant(const GemmArgs& a, const float* partials, float* s_out, 
 // Words of the grid-wide barrier of the single-pass kernels: eight copies of one slot per workgroup
 // (at most 256) and a sticky failure word, rounded up.
 constexpr unsigned kBarrierWords = 8 * 256 + 64;
+// Size test of the single-pass re-quantizing product: one 256 x 256 tile per workgroup, every workgroup resident
+// on an otherwise empty device (`resident` = occupancy x compute units) and holding one of the 256 slots.
+inline bool single_pass_fits(size_t M, size_t N, size_t resident) {
+  if (M == 0 || N == 0) return false;
+  const size_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  return tiles <= resident && tiles <= 256;
+}
 unsigned long long barrier_timeout_ticks();
 void set_barrier_timeout_ticks(unsigned long long ticks);
 size_t topk_stream_ws_bytes(size_t M, int k);

@@ -146,6 +146,114 @@ def test_decoder_layer_matches_oracle(shape, use_ffn, use_gate):
     assert_chained_close(host(y), want_y, "layer output", 0.10)
 
 
+def gpu_quant8(xd):
+    """abs-max, multiplier and quant_int (8 bit) of a device tensor; returns (integers, multiplier) on the host."""
+    rows, cols = xd.shape
+    s = torch.empty(1, dtype=torch.float32, device=DEV)
+    mq.mq_absmax_f32(xd, xd.numel(), s)
+    mq.mq_scale_from_amax(s, 8, s)
+    q = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    mq.mq_quantize_f32(xd, rows, cols, 8, s, q, None)
+    return host(q), host(s)[0]
+
+
+def assert_few_flips(xd, want_f32, what):
+    """quant_int of a GPU glue result against quant_int of the oracle's value of the same tensor: the multipliers
+    agree to a few ulps (the tensor's maximum is itself a glue result: a layer normalisation's binary32 sums leave
+    it a few ulps from the binary64 value; 1e-6 relative is allowed), no integer differs by more than one, and only
+    a handful differ at all (a binary32 glue result a few ulps from the binary64 one crosses a rounding boundary
+    with probability ~ |x s| 2^-21 ~ 2e-5; 1e-4 of the elements are allowed)."""
+    q, s = gpu_quant8(xd)
+    oq, os_ = oracle.quant_int_absmax(want_f32, 8)
+    assert abs(float(s) - float(os_)) <= 1e-6 * float(os_), what
+    dq = q.astype(np.int32) - oq.astype(np.int32)
+    assert np.abs(dq).max() <= 1, f"{what}: an integer differs by {np.abs(dq).max()}"
+    allowed = max(3, int(1e-4 * dq.size))
+    assert np.count_nonzero(dq) <= allowed, f"{what}: {np.count_nonzero(dq)} of {dq.size} integers flipped (allowed {allowed})"
+
+
+def gpu_linear_f32(A, W, bias, relu):
+    M, K = A.shape
+    N = W.N
+    nb = mq.mq_linear_ws_bytes(8, M, K)
+    ws = torch.empty(nb, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    mq.mq_linear_f32(A, M, K, None, W.packed, W.scale, 8, N, bias, relu, Y, None, ws, nb)
+    return Y
+
+
+@pytest.mark.parametrize("shape", [dict(M=300, d=512, ffn=2048, aan_ffn=2048, S=25, heads=8),
+                                   dict(M=130, d=512, ffn=2048, aan_ffn=512, S=25, heads=8),
+                                   dict(M=24, d=48, ffn=40, aan_ffn=72, S=3, heads=4)])
+def test_decoder_layer_stage_by_stage(shape):
+    # The envelope of test_decoder_layer_matches_oracle is wide because one flipped integer moves a whole row of the
+    # next product.  Here every stage is checked on the ORACLE's input for that stage, so nothing accumulates:
+    #   glue stages: 2e-5 against the binary64 value, and quant_int of the GPU's result differs from quant_int of the
+    #     oracle's in at most a handful of integers, each by one;
+    #   products (quant_int -> dot'_int -> dequantize + bias): bit-identical;
+    # and the one-call layer must give the bits of the same stages called one by one on the GPU.
+    from test_oracle_glue_pins import hand_composed_layer
+    M, d, heads, t = shape["M"], shape["d"], shape["heads"], 20
+    c = workloads.config5_chained(M=M, layers=1, d=d, ffn=shape["ffn"], aan_ffn=shape["aan_ffn"], S=shape["S"], V=8,
+                                  t=t, seed_extra=shape["M"] + 1)
+    P, (K, V) = c["layers"][0], c["KV"][0]
+    x, gp = c["x0"], c["g_prev"][0]
+    r = hand_composed_layer(x, gp, t, P, K, V, heads)
+    W = {}
+    for name in ("aan_ffn1", "aan_ffn2", "aan_gate", "ctx_q", "ctx_o", "ffn1", "ffn2"):
+        W[name] = mq.prepare_weight(dev(P[name]["Wt"]), 8)
+        W[name].bias = dev(P[name]["bias"])
+    ln = {n_: (dev(P[n_]["gamma"]), dev(P[n_]["beta"])) for n_ in ("ln1", "ln2", "ln3")}
+    xd, gpd, Kd, Vd = dev(x), dev(gp), dev(K), dev(V)
+
+    def f32buf(cols=d):
+        return torch.empty((M, cols), dtype=torch.float32, device=DEV)
+
+    def stages(src):
+        """The layer's stages one call at a time; src(name, gpu_value) picks each stage's input."""
+        o = {}
+        o["g"] = f32buf()
+        mq.mq_running_average_f32(gpd, xd, M * d, t, o["g"])
+        o["h1"] = gpu_linear_f32(src("g", o["g"]), W["aan_ffn1"], W["aan_ffn1"].bias, True)
+        o["f"] = gpu_linear_f32(src("h1", o["h1"]), W["aan_ffn2"], W["aan_ffn2"].bias, False)
+        fin = src("f", o["f"])
+        cat = f32buf(2 * d)
+        mq.mq_concat2_f32(xd, d, fin, d, M, cat)
+        o["z"] = gpu_linear_f32(cat, W["aan_gate"], W["aan_gate"].bias, False)
+        o["y1"] = f32buf()
+        mq.mq_gate_mix_layer_norm_f32(xd, fin, src("z", o["z"]), ln["ln1"][0], ln["ln1"][1], M, d, glue.LN_EPS, o["y1"])
+        y1 = src("y1", o["y1"])
+        o["q"] = gpu_linear_f32(y1, W["ctx_q"], W["ctx_q"].bias, False)
+        o["ctx"] = f32buf()
+        mq.mq_cross_attention_f32(src("q", o["q"]), Kd, Vd, M, shape["S"], d, heads, o["ctx"])
+        o["o"] = gpu_linear_f32(src("ctx", o["ctx"]), W["ctx_o"], W["ctx_o"].bias, False)
+        o["y2"] = f32buf()
+        mq.mq_add_layer_norm_f32(src("o", o["o"]), y1, ln["ln2"][0], ln["ln2"][1], M, d, glue.LN_EPS, o["y2"])
+        y2 = src("y2", o["y2"])
+        o["h2"] = gpu_linear_f32(y2, W["ffn1"], W["ffn1"].bias, True)
+        o["ff"] = gpu_linear_f32(src("h2", o["h2"]), W["ffn2"], W["ffn2"].bias, False)
+        o["y3"] = f32buf()
+        mq.mq_add_layer_norm_f32(src("ff", o["ff"]), y2, ln["ln3"][0], ln["ln3"][1], M, d, glue.LN_EPS, o["y3"])
+        return o
+
+    # every stage on the oracle's value of its input
+    forced = stages(lambda name, gpu_value: dev(r[name]))
+    torch.cuda.synchronize()
+    for name in ("h1", "f", "z", "q", "o", "h2", "ff"):
+        assert np.array_equal(host(forced[name]), r[name]), f"product {name} on the oracle's input"
+    assert close(host(forced["g"]), r["g"], 1e-6)
+    for name in ("y1", "ctx", "y2", "y3"):
+        assert close(host(forced[name]), r[name]), f"glue {name} on the oracle's input"
+    for name in ("g", "y1", "ctx", "y2"):              # the glue results that enter quant_int
+        assert_few_flips(forced[name], r[name], name)
+    # the one-call layer against the same stages chained on the GPU's own values
+    own = stages(lambda name, gpu_value: gpu_value)
+    layer = prepare_layer(P, d, shape["ffn"], shape["aan_ffn"])
+    y, g = run_layer(layer, xd, gpd, t, Kd, Vd, heads)
+    torch.cuda.synchronize()
+    assert torch.equal(g, own["g"]) and torch.equal(y, own["y3"])
+
+
 def test_decoder_layer_and_output_layer_replayed_as_a_graph():
     # the launch configuration of bench.py's chained decode step: layers and the greedy output layer in one HIP
     # graph.  Every replay (other inputs, refilled workspaces, eager work in between) must give the eager bits.

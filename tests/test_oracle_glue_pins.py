@@ -120,6 +120,101 @@ def test_decoder_layer_variants_reduce_to_their_parts():
     assert np.allclose(zrow.mean(axis=1), 0, atol=1e-5) and np.allclose(zrow.var(axis=1), 1, atol=1e-3)
 
 
+def hand_composed_layer(x, gp, t, P, K, V, heads, use_ffn=True, use_gate=True):
+    """The decoder layer of reading R16 / R17 written out step by step from the single operations (each pinned above
+    or in test_oracle_pins.py); returns every intermediate."""
+    from oracle import linear
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    r = {}
+    r["g"] = f32(glue.running_average(gp, x, t))
+    r["f"] = r["g"]
+    if use_ffn:
+        r["h1"] = linear(r["g"], P["aan_ffn1"]["Wt"], 8, P["aan_ffn1"]["bias"], True)["Y"]
+        r["f"] = linear(r["h1"], P["aan_ffn2"]["Wt"], 8, P["aan_ffn2"]["bias"])["Y"]
+    if use_gate:
+        r["cat"] = np.concatenate([f32(x), f32(r["f"])], axis=1)             # the layer input first, then the averaged path
+        r["z"] = linear(r["cat"], P["aan_gate"]["Wt"], 8, P["aan_gate"]["bias"])["Y"]
+        h = glue.gate_mix(x, r["f"], r["z"])
+    else:
+        h = r["f"].astype(np.float64)
+    r["y1"] = f32(glue.add_layer_norm(h, x, P["ln1"]["gamma"], P["ln1"]["beta"]))
+    r["q"] = linear(r["y1"], P["ctx_q"]["Wt"], 8, P["ctx_q"]["bias"])["Y"]
+    r["ctx"] = f32(glue.cross_attention(r["q"], K, V, heads))
+    r["o"] = linear(r["ctx"], P["ctx_o"]["Wt"], 8, P["ctx_o"]["bias"])["Y"]
+    r["y2"] = f32(glue.add_layer_norm(r["o"], r["y1"], P["ln2"]["gamma"], P["ln2"]["beta"]))
+    r["h2"] = linear(r["y2"], P["ffn1"]["Wt"], 8, P["ffn1"]["bias"], True)["Y"]
+    r["ff"] = linear(r["h2"], P["ffn2"]["Wt"], 8, P["ffn2"]["bias"])["Y"]
+    r["y3"] = f32(glue.add_layer_norm(r["ff"], r["y2"], P["ln3"]["gamma"], P["ln3"]["beta"]))
+    return r
+
+
+@pytest.mark.parametrize("use_ffn,use_gate", [(True, True), (False, True), (True, False), (False, False)])
+def test_decoder_layer_equals_the_hand_composition_of_its_parts(use_ffn, use_gate):
+    c = workloads.config5_chained(M=7, layers=1, d=32, ffn=64, aan_ffn=48, S=4, V=50, t=5, seed_extra=3)
+    P, (K, V) = c["layers"][0], c["KV"][0]
+    x, gp = c["x0"], c["g_prev"][0]
+    y, g = glue.aan_decoder_layer(x, gp, 5, P, K, V, heads=4, use_ffn=use_ffn, use_gate=use_gate)
+    r = hand_composed_layer(x, gp, 5, P, K, V, 4, use_ffn, use_gate)
+    assert np.array_equal(g, r["g"]) and np.array_equal(y, r["y3"])
+
+
+def planted_gate_case():
+    """A layer whose inputs tell the pieces of the gate apart: every sentence has x[0] >= 0.5, the running average's
+    first entry is positive too, and the averaging network's output has f[0] ~ -100 (planted in its last bias)."""
+    c = workloads.config5_chained(M=9, layers=1, d=32, ffn=64, aan_ffn=48, S=4, V=50, t=5, seed_extra=11)
+    P, (K, V) = c["layers"][0], c["KV"][0]
+    x, gp = c["x0"].copy(), c["g_prev"][0].copy()
+    x[:, 0] = np.abs(x[:, 0]) + np.float32(0.5)
+    gp[:, 0] = np.abs(gp[:, 0]) + np.float32(0.5)
+    P = {k: dict(v) for k, v in P.items()}
+    b = P["aan_ffn2"]["bias"].copy()
+    b[0] = -100.0
+    P["aan_ffn2"]["bias"] = b
+    return c, P, K, V, x, gp
+
+
+def test_gate_halves_first_columns_gate_the_input_last_columns_the_averaged_path():
+    # gate weights zero, biases saturating: z = bias.  (+50 | -50) opens the input's gate only: h = x, the layer is
+    # LN(x + x) ..., which is the "-ffn -gate" layer at position 1 (there g = x).  (-50 | +50) opens the averaged
+    # path's gate only: h = f, which is the "-gate" layer.  Exact: sigmoid(+-50) is 1 and 2e-22 in binary64.
+    c, P, K, V, x, gp = planted_gate_case()
+    d = 32
+    Pz = dict(P)
+    for first, second, same_as in ((50.0, -50.0, "x"), (-50.0, 50.0, "f")):
+        Pz["aan_gate"] = {"Wt": np.zeros((2 * d, 2 * d), dtype=np.float32),
+                          "bias": np.r_[np.full(d, first), np.full(d, second)].astype(np.float32)}
+        y, _ = glue.aan_decoder_layer(x, gp, 5, Pz, K, V, heads=4)
+        if same_as == "x":
+            want, _ = glue.aan_decoder_layer(x, gp, 1, Pz, K, V, heads=4, use_ffn=False, use_gate=False)
+        else:
+            want, _ = glue.aan_decoder_layer(x, gp, 5, Pz, K, V, heads=4, use_gate=False)
+        assert np.array_equal(y, want), same_as
+    other, _ = glue.aan_decoder_layer(x, gp, 5, Pz, K, V, heads=4, use_ffn=False, use_gate=False)
+    assert not np.allclose(y, other, atol=1e-3)          # h = f is not h = g
+
+
+def test_gate_input_is_the_layer_input_followed_by_the_network_output():
+    # The gate product reads [x ; f].  Weights on ONE input column, +1000 into every z1 and -1000 into every z2:
+    # on column 0 (x[0] >= 0.5 in every sentence) the input's gate saturates open and the other one shut: h = x;
+    # on column d (f[0] ~ -100) it is the other way round: h = f.  With the halves of the input swapped, or with
+    # the running average g (g[0] > 0) in the place of f, each case would give the other case's result.
+    c, P, K, V, x, gp = planted_gate_case()
+    d = 32
+    f0 = hand_composed_layer(x, gp, 5, P, K, V, 4)["f"][:, 0]
+    assert np.all(f0 < -50) and np.all(glue.running_average(gp, x, 5)[:, 0] > 0)
+    want_x, _ = glue.aan_decoder_layer(x, gp, 1, P, K, V, heads=4, use_ffn=False, use_gate=False)     # h = x
+    want_f, _ = glue.aan_decoder_layer(x, gp, 5, P, K, V, heads=4, use_gate=False)                    # h = f
+    assert not np.allclose(want_x, want_f, atol=1e-3)
+    for col, want in ((0, want_x), (d, want_f)):
+        Wt = np.zeros((2 * d, 2 * d), dtype=np.float32)
+        Wt[:d, col] = 1000.0
+        Wt[d:, col] = -1000.0
+        Pg = dict(P)
+        Pg["aan_gate"] = {"Wt": Wt, "bias": np.zeros(2 * d, dtype=np.float32)}
+        y, _ = glue.aan_decoder_layer(x, gp, 5, Pg, K, V, heads=4)
+        assert np.array_equal(y, want), col
+
+
 def test_decode_step_chains_layers_and_picks_tokens():
     c = workloads.config5_chained(M=5, layers=2, d=32, ffn=64, aan_ffn=64, S=3, V=40, t=4)
     r = glue.decode_step(c["x0"], c["g_prev"], c["t"], c["layers"], c["KV"], c["E"], heads=4)
