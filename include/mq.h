@@ -86,7 +86,8 @@ typedef enum mq_status {
   MQ_ERR_ALIGN = 4,       /* a pointer is not aligned as required */
   MQ_ERR_WORKSPACE = 5,   /* workspace smaller than the *_ws_bytes query says */
   MQ_ERR_UNSUPPORTED = 6, /* valid arguments the library cannot serve */
-  MQ_ERR_HIP = 7          /* the HIP runtime refused a launch; see mq_last_hip_error */
+  MQ_ERR_HIP = 7,         /* the HIP runtime refused a launch; see mq_last_hip_error */
+  MQ_ERR_LIMIT = 8        /* a size is beyond what the library's static scratch array serves */
 } mq_status;
 
 /* Library version: major * 10000 + minor * 100 + patch. */
@@ -340,6 +341,20 @@ int mq_gemm_argmax(const void* qA, const void* packedW, size_t M, size_t N, size
 int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
                           const float* sA, const float* sW, int32_t* tok, float* maxlogit,
                           void* ws, size_t ws_bytes, void* stream);
+
+/* mq_gemm_argmax_packed for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The per-workgroup candidates
+ * (the `ws` of mq_gemm_argmax_packed) live in a static device array of the library instead: 768 KiB (384 rows x
+ * 256 workgroups x 8 bytes) per GPU the library runs on, held until the process ends.  The call allocates
+ * nothing and frees nothing, here or inside the runtime's allocator; inputs and outputs are still the caller's.
+ * Same arguments otherwise, same results bit for bit.
+ * Limits: K <= 512 and N <= 1044480 as for mq_gemm_argmax_packed (MQ_ERR_UNSUPPORTED beyond), M <= 24576 rows
+ * (MQ_ERR_LIMIT beyond: "a size is beyond what the library's static scratch array serves").
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams or
+ * threads) race and give undefined tokens; calls on one stream are ordered and safe.  Nothing in the array has
+ * to be zero on entry (every word that is read was written by the same call before). */
+int mq_gemm_argmax_packed_static(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                 const float* sA, const float* sW, int32_t* tok, float* maxlogit, void* stream);
 
 /* Short-listed output layer (Section 4.1 "Shortlist": the output product is
  * restricted to a subset of translation candidates).  shortlist: device int32

@@ -19,7 +19,7 @@ __all__ = [
     "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_gemm_requant_fixed_packed_i16",
     "mq_autotune_ws_bytes", "mq_autotune_gemm",
@@ -56,7 +56,7 @@ def exported_symbols():
             "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
-            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
+            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
             "mq_gemm_requant_fixed_packed_i16",
@@ -113,6 +113,7 @@ def load_library():
     lib.mq_argmax_ws_bytes.argtypes = [sz, sz]
     lib.mq_gemm_argmax.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_gemm_argmax_packed.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.mq_gemm_argmax_packed_static.argtypes = [vp, vp, sz, sz, sz, vp, vp, vp, vp, vp]
     lib.mq_gemm_argmax_shortlist.argtypes = [vp, vp, vp, sz, sz, sz, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_quantize_absmax_ws_bytes.restype = sz
     lib.mq_quantize_absmax_ws_bytes.argtypes = []
@@ -268,6 +269,12 @@ def mq_gemm_argmax_packed(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, 
     _check(load_library().mq_gemm_argmax_packed(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(tok),
                                                 _p(maxlogit), _p(ws), ws_bytes, _stream(stream)),
            "mq_gemm_argmax_packed")
+
+
+def mq_gemm_argmax_packed_static(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, stream=None):
+    _check(load_library().mq_gemm_argmax_packed_static(_p(packedA), _p(packedW), M, N, K, _p(sA), _p(sW), _p(tok),
+                                                       _p(maxlogit), _stream(stream)),
+           "mq_gemm_argmax_packed_static")
 
 
 def mq_gemm_argmax_shortlist(packedA, packedW, shortlist, shortlist_len, M, N, K, sA, sW, tok, maxlogit, ws, ws_bytes,

@@ -91,6 +91,7 @@ const char* mq_status_string(int status) {
     case MQ_ERR_WORKSPACE: return "workspace too small";
     case MQ_ERR_UNSUPPORTED: return "unsupported arguments";
     case MQ_ERR_HIP: return "HIP runtime error (see mq_last_hip_error)";
+    case MQ_ERR_LIMIT: return "a size is beyond what the library's static scratch array serves";
     default: return "unknown status";
   }
 }
@@ -494,6 +495,20 @@ int mq_gemm_argmax_packed(const void* packedA, const void* packedW, size_t M, si
   if (ws_bytes < mq_argmax_ws_bytes(M, N)) return MQ_ERR_WORKSPACE;
   if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
   return launch_argmax_stream(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ws, nullptr, 0, as_stream(stream));
+}
+
+int mq_gemm_argmax_packed_static(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                 const float* sA, const float* sW, int32_t* tok, float* maxlogit, void* stream) {
+  if (packedA == nullptr || packedW == nullptr || sA == nullptr || sW == nullptr || tok == nullptr ||
+      maxlogit == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, N, K)) return MQ_ERR_SHAPE;
+  if (!aligned(packedA, 16) || !aligned(packedW, 16) || !aligned(sA, 4) || !aligned(sW, 4) || !aligned(tok, 4) ||
+      !aligned(maxlogit, 4))
+    return MQ_ERR_ALIGN;
+  if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
+  if (M > argmax_static_max_rows()) return MQ_ERR_LIMIT;
+  return launch_argmax_stream_static(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, as_stream(stream));
 }
 
 int mq_gemm_argmax_shortlist(const void* packedA, const void* packedW, const int32_t* shortlist,

@@ -26,6 +26,7 @@
 //     small kernel reduces them and decodes.  No atomics, no initialisation.
 // 64-bit keys order by sum first and by smaller index second:
 //   key = (sum ^ 0x80000000) << 32 | (0xFFFFFFFF - n);  0 means "no candidate".
+#include <mutex>
 #include <type_traits>
 
 #include "mq_gemm_common.h"
@@ -543,7 +544,7 @@ bool argmax_stream_supported(size_t M, size_t N, size_t K) {
 
 int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
                          const float* sW, int32_t* tok, float* maxlogit, void* ws, const int32_t* shortlist,
-                         size_t shortlist_len, hipStream_t s) {
+                         size_t shortlist_len, hipStream_t s, unsigned max_grid) {
   if (!argmax_stream_supported(M, N, K)) return MQ_ERR_UNSUPPORTED;
   const PackedDims dW(8, N, K), dAll(8, M, K);
   static int cus = 0;               // compute units of the device, asked once
@@ -557,6 +558,7 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
   const size_t units = shortlist != nullptr ? (shortlist_len + 15) / 16 : dW.nblocks * 2;
   unsigned grid = (unsigned)(units < (size_t)cus ? units : (size_t)cus);
   if (grid > (unsigned)kMaxBlocks) grid = kMaxBlocks;
+  if (max_grid != 0 && grid > max_grid) grid = max_grid;       // the caller's partials array has that many columns
   if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
   // rows beyond what one workgroup's registers hold (3 tiles of 16 sentences per wave) go in further passes
   constexpr size_t kChunk = (size_t)kWaves * 3 * 16;
@@ -593,6 +595,41 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
     if (rc != MQ_OK) return rc;
   }
   return MQ_OK;
+}
+
+// ---- the same output layer for callers that cannot allocate: partial winners in a static device array ----
+// One pass of kStaticRows sentences against at most kStaticCols workgroups' candidates: 768 KiB per device, held
+// until the process ends.  Further passes (more rows) reuse it one after the other on the stream.
+namespace {
+constexpr size_t kStaticRows = (size_t)kWaves * 3 * 16;     // rows of one pass of the streaming kernel (384)
+constexpr unsigned kStaticCols = 256;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned long long scratch[kStaticRows * kStaticCols];
+std::mutex g_scratch_mutex;
+unsigned long long* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, asked once
+}  // namespace
+
+size_t argmax_static_max_rows() { return kStaticRows * 64; }
+
+int launch_argmax_stream_static(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                const float* sA, const float* sW, int32_t* tok, float* maxlogit, hipStream_t s) {
+  int dev = -1;
+  if (check_hip(hipGetDevice(&dev)) != MQ_OK) return MQ_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MQ_ERR_UNSUPPORTED;
+  unsigned long long* ptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+      // `scratch` itself is only a host-side handle: kernels get the address the runtime reports for this device
+      void* addr = nullptr;
+      const int rc = check_hip(hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)));
+      if (rc != MQ_OK || addr == nullptr) return MQ_ERR_HIP;
+      g_scratch_ptr[dev] = static_cast<unsigned long long*>(addr);
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // every key the reduce kernel reads was written by this call's streaming kernel: nothing has to start at zero
+  return launch_argmax_stream(packedA, packedW, M, N, K, sA, sW, tok, maxlogit, ptr, nullptr, 0, s, kStaticCols);
 }
 
 size_t topk_stream_ws_bytes(size_t M, int k) {

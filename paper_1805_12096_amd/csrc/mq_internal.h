@@ -175,8 +175,13 @@ int packed_variant_count(int bits);
 // Streaming arg-max product for decode-sized batches (both operands packed, 8 bit).
 size_t argmax_stream_ws_bytes(size_t M);
 bool argmax_stream_supported(size_t M, size_t N, size_t K);
+// max_grid: columns of the partials array at ws (0 = as many as argmax_stream_ws_bytes provides).
 int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
                          const float* sW, int32_t* tok, float* maxlogit, void* ws, const int32_t* shortlist,
-                         size_t shortlist_len, hipStream_t s);
+                         size_t shortlist_len, hipStream_t s, unsigned max_grid = 0);
+// The same with the partial winners in a static device array of the library (no workspace, no allocation).
+size_t argmax_static_max_rows();
+int launch_argmax_stream_static(const void* packedA, const void* packedW, size_t M, size_t N, size_t K,
+                                const float* sA, const float* sW, int32_t* tok, float* maxlogit, hipStream_t s);
 
 }  // namespace mq

@@ -131,6 +131,8 @@ def _rows():
                            (BIG, WSB), (None, X)],
         "mq_gemm_argmax_packed": [(G, P16), (G, P16), (4, N_), (4, N_), (4, N_), (G, P4), (G, P4), (G, P4), (G, P4),
                                   (G, WSP), (BIG, WSB), (None, X)],
+        "mq_gemm_argmax_packed_static": [(G, P16), (G, P16), (4, N_), (4, N_), (4, N_), (G, P4), (G, P4), (G, P4), (G, P4),
+                                         (None, X)],
         "mq_gemm_argmax_shortlist": [(G, P16), (G, P16), (G, P4), (2, N_), (4, N_), (4, N_), (4, N_), (G, P4), (G, P4),
                                      (G, P4), (G, P4), (G, WSP), (BIG, WSB), (None, X)],
         "mq_linear_f32": [(G, P16), (4, N_), (4, N_), (G, OPT), (G, P16), (G, P4), (8, BITS), (4, N_), (G, OPT), (0, X),
@@ -193,6 +195,9 @@ def test_bad_arguments_are_refused_before_any_launch(lib, name):
 def test_limits_of_single_entry_points(lib):
     # sizes a particular kernel cannot serve, still refused on the host
     assert lib.mq_gemm_argmax_packed(G, G, 4, 4, 1024, G, G, G, G, G, BIG, None) == UNSUP        # K beyond 512
+    assert lib.mq_gemm_argmax_packed_static(G, G, 4, 4, 1024, G, G, G, G, None) == UNSUP
+    assert lib.mq_gemm_argmax_packed_static(G, G, 24577, 4, 64, G, G, G, G, None) == LIMIT       # rows beyond the array
+    assert "static scratch" in mq.mq_status_string(LIMIT)
     assert lib.mq_gemm_argmax_shortlist(G, G, G, 9, 4, 4, 4, G, G, G, G, G, BIG, None) == SHAPE  # list longer than N
     assert lib.mq_gemm_topk_packed(G, G, None, 0, 4, 16, 4, G, G, 5, G, G, G, BIG, None) == SHAPE   # k beyond 4
     assert lib.mq_gemm_topk_packed(G, G, G, 1, 4, 16, 4, G, G, 2, G, G, G, BIG, None) == SHAPE      # list shorter than k
