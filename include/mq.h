@@ -103,7 +103,7 @@ int mq_last_hip_error(void);
 /* Tuning knob for measurements in the spirit of the paper's auto-tuner (Section
  * 4.4: alternative implementations are timed per shape and the fastest is
  * kept).  variant 0 (default) lets the library choose the tile configuration of
- * the product kernels from the problem shape; 1..14 (8 bit) or 1..6 (16 bit)
+ * the product kernels from the problem shape; 1..14 (8 bit) or 1..7 (16 bit)
  * force one configuration for every following product of this process (results
  * are identical, only speed changes; a variant that does not exist for the
  * operand width makes the product calls return MQ_ERR_UNSUPPORTED; the fused
@@ -311,6 +311,12 @@ int mq_gemm_requant_fixed_packed_i16(const void* packedA, const void* packedW, s
  * best_variant / best_us (host pointers, may be NULL) receive the choice and its
  * average microseconds.  Not thread safe; the table holds 256 shapes. */
 size_t mq_autotune_ws_bytes(int bits, size_t M, size_t N, size_t K);
+/* The times of the most recent mq_autotune_gemm run: us_by_variant (HOST float[n]) receives the microseconds per
+ * launch of variant v at index v (index 0 and variants that do not exist for the operand width: -1), winners and
+ * losers alike.  For 16 bit the candidates are six tile configurations of the decomposition onto four 8-bit matrix
+ * products (1..6) and the vector-ALU kernel built on the 16-bit dot instruction (7), the chip's counterpart of the
+ * instruction the paper's 16-bit kernel uses (Section 4.2). */
+int mq_autotune_report(float* us_by_variant, int n);
 int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws, size_t ws_bytes,
                      void* stream, int* best_variant, float* best_us);
 

@@ -22,7 +22,7 @@ __all__ = [
     "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_gemm_requant_fixed_packed_i16",
-    "mq_autotune_ws_bytes", "mq_autotune_gemm",
+    "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_autotune_report",
     "mq_topk_ws_bytes", "mq_gemm_topk_packed",
     "mq_running_average_f32", "mq_concat2_f32", "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32",
     "mq_cross_attention_f32", "mq_aan_layer_ws_bytes", "mq_aan_layer_f32", "AanLayer", "aan_layer",
@@ -60,7 +60,7 @@ def exported_symbols():
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
             "mq_gemm_requant_fixed_packed_i16",
-            "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_topk_ws_bytes", "mq_gemm_topk_packed", "mq_running_average_f32", "mq_concat2_f32",
+            "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_autotune_report", "mq_topk_ws_bytes", "mq_gemm_topk_packed", "mq_running_average_f32", "mq_concat2_f32",
             "mq_add_layer_norm_f32", "mq_gate_mix_layer_norm_f32", "mq_cross_attention_f32",
             "mq_aan_layer_ws_bytes", "mq_aan_layer_f32"]
 
@@ -130,6 +130,7 @@ def load_library():
     lib.mq_autotune_ws_bytes.restype = sz
     lib.mq_autotune_ws_bytes.argtypes = [ci, sz, sz, sz]
     lib.mq_autotune_gemm.argtypes = [ci, sz, sz, sz, ci, vp, sz, vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
+    lib.mq_autotune_report.argtypes = [ctypes.POINTER(ctypes.c_float), ci]
     lib.mq_set_ffn_single_pass.argtypes = [ci]
     lib.mq_set_quantize_single_pass.argtypes = [ci]
     lib.mq_set_barrier_timeout_us.argtypes = [ctypes.c_uint]
@@ -362,6 +363,13 @@ def mq_autotune_gemm(bits, M, N, K, runs, ws, ws_bytes, stream=None):
     _check(load_library().mq_autotune_gemm(bits, M, N, K, runs, _p(ws), ws_bytes, _stream(stream),
                                            ctypes.byref(best), ctypes.byref(us)), "mq_autotune_gemm")
     return int(best.value), float(us.value)
+
+
+def mq_autotune_report(n=16):
+    """Microseconds per launch of every variant in the last mq_autotune_gemm run: {variant: us}."""
+    buf = (ctypes.c_float * n)()
+    _check(load_library().mq_autotune_report(buf, n), "mq_autotune_report")
+    return {v: float(buf[v]) for v in range(1, n) if buf[v] >= 0.0}
 
 
 def mq_set_ffn_single_pass(enable) -> None:

@@ -384,6 +384,17 @@ int mq_gemm_requant_fixed_packed_i16(const void* packedA, const void* packedW, s
   return launch_gemm_requant_fixed_i16(a, s_out, packed_out, as_stream(stream));
 }
 
+// times of the last mq_autotune_gemm run, microseconds per launch by variant (index 0 unused; < 0: not available)
+static float g_autotune_us[32];
+static int g_autotune_count = 0;
+
+int mq_autotune_report(float* us_by_variant, int n) {
+  if (us_by_variant == nullptr) return MQ_ERR_NULL;
+  if (n <= 0) return MQ_ERR_SHAPE;
+  for (int v = 0; v < n; ++v) us_by_variant[v] = (v < g_autotune_count && v < 32) ? g_autotune_us[v] : -1.0f;
+  return MQ_OK;
+}
+
 size_t mq_autotune_ws_bytes(int bits, size_t M, size_t N, size_t K) {
   if (!bits_ok(bits) || !dims_ok(M, N, K)) return 0;
   return round_up(PackedDims(bits, M, K).total_bytes(), 256) + round_up(PackedDims(bits, N, K).total_bytes(), 256) +
@@ -464,6 +475,8 @@ int mq_autotune_gemm(int bits, size_t M, size_t N, size_t K, int runs, void* ws,
   float best_ms = 0.f;
   for (int v = 1; v <= nv && v < 32; ++v)
     if (best_of[v] >= 0.f && (best == 0 || best_of[v] < best_ms)) { best = v; best_ms = best_of[v]; }
+  g_autotune_count = nv + 1 < 32 ? nv + 1 : 32;
+  for (int v = 0; v < 32; ++v) g_autotune_us[v] = best_of[v] >= 0.f ? best_of[v] * 1000.0f / (float)runs : -1.0f;
   set_forced_variant(saved);
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);

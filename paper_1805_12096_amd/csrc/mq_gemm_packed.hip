@@ -737,7 +737,7 @@ size_t tiles_of(int variant, size_t M, size_t N) {
 }
 }  // namespace
 
-int packed_variant_count(int bits) { return bits == 8 ? 14 : 6; }
+int packed_variant_count(int bits) { return bits == 8 ? 14 : 7; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
@@ -858,6 +858,7 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     }
   }
   if ((a.bits == 8 && v == 10) || (a.bits == 16 && v == 6)) return launch_gemm_small(a, epi, s);
+  if (a.bits == 16 && v == 7) return launch_gemm_dot2(a, epi, s);                        // vector ALU instead of matrix cores
   if (a.bits == 8 && v >= 11 && v <= 13) return launch_gemm_prod(a, epi, v - 11, s);     // loading waves apart
   if (a.bits == 8 && v == 14) return launch_gemm_ks(a, epi, s);                          // K split over two wave groups
   if (a.bits == 8)

@@ -167,6 +167,8 @@ int launch_gemm_requant_fixed_i16(const GemmArgs& a, const float* s_fixed, void*
 int launch_gemm_prod(const GemmArgs& a, Epilogue epi, int which, hipStream_t s);
 // Variant 14 of the packed 8-bit products (mq_gemm_ks.hip): 128 x 128 tile, K split over two groups of four waves.
 int launch_gemm_ks(const GemmArgs& a, Epilogue epi, hipStream_t s);
+// 16-bit product on the vector ALU (v_dot2c_i32_i16), both operands packed; variant 7 of the packed 16-bit products.
+int launch_gemm_dot2(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
 int tuned_variant(int bits, size_t M, size_t N, size_t K);
 void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant);

@@ -152,7 +152,7 @@ def _rows():
     }
 
 
-QUERIES_AND_SETTERS = {"mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant", "mq_packed_bytes",
+QUERIES_AND_SETTERS = {"mq_version", "mq_autotune_report", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant", "mq_packed_bytes",
                        "mq_set_quantize_single_pass", "mq_quantize_absmax_ws_bytes", "mq_gemm_amax_ws_bytes",
                        "mq_set_barrier_timeout_us", "mq_single_pass_fits", "mq_autotune_ws_bytes", "mq_argmax_ws_bytes",
                        "mq_linear_ws_bytes", "mq_ffn_ws_bytes", "mq_set_ffn_single_pass", "mq_ffn_i16_ws_bytes",
@@ -205,6 +205,9 @@ def test_limits_of_single_entry_points(lib):
     assert lib.mq_cross_attention_f32(G, G, G, 4, 4, 8, 3, G, None) == SHAPE                        # 8 not divisible by 3
     assert lib.mq_autotune_gemm(8, 64, 64, 64, 0, G, BIG, None, None, None) == SHAPE                # no runs
     assert lib.mq_set_gemm_variant(99) == UNSUP and lib.mq_set_gemm_variant(0) == 0
+    assert lib.mq_autotune_report(None, 8) == NULL
+    buf = (ctypes.c_float * 8)()
+    assert lib.mq_autotune_report(buf, 0) == SHAPE and lib.mq_autotune_report(buf, 8) == 0 and buf[0] == -1.0
     assert lib.mq_set_barrier_timeout_us(20_000_000) == SHAPE and lib.mq_set_barrier_timeout_us(500_000) == 0
 
 

@@ -528,7 +528,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14], 16: [0, 1, 2, 3, 4, 5, 6]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14], 16: [0, 1, 2, 3, 4, 5, 6, 7]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
@@ -566,6 +566,34 @@ def test_gemm_packed_pipeline_boundaries_all_variants(dtype, K):
             assert np.array_equal(gpu_dot_int_packed(qA, qB), want), f"variant {v}"
     finally:
         mq.mq_set_gemm_variant(0)
+
+
+@pytest.mark.parametrize("M,N,K,relu", [(1, 1, 1, False), (37, 53, 64, True), (384, 512, 512, False), (130, 260, 1100, True)])
+def test_int16_vector_alu_product_matches_oracle(M, N, K, relu):
+    # variant 7 of the 16-bit packed products: the 16-bit dot instruction on the vector ALU instead of four 8-bit
+    # matrix products.  Raw sums on full-range integers (runs of the extreme values planted, so that a pair of
+    # products reaches 2 x 32767^2 and the sums wrap), then the dequantizing epilogue with bias, ReLU and the
+    # abs-max by-product.
+    rng = np.random.default_rng(M * 31 + N * 7 + K)
+    qA = rng.integers(-32767, 32768, size=(M, K)).astype(np.int16)
+    qB = rng.integers(-32767, 32768, size=(N, K)).astype(np.int16)
+    qA[0, : min(K, 6)] = -32767
+    qB[0, : min(K, 6)] = -32767
+    qA[-1, -1], qB[-1, -1] = 32767, -32767
+    p = workloads.random_problem(M + N + K + 7, M, N, K)
+    o = oracle.linear(p["A"], p["Wt"], 16, p["bias"], relu)
+    pw = mq.prepare_weight(dev(p["Wt"]), 16)
+    pa, s = gpu_quantize_pack(p["A"], 16)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    try:
+        mq.mq_set_gemm_variant(7)
+        assert np.array_equal(gpu_dot_int_packed(qA, qB), oracle.dot_int(qA, qB))
+        mq.mq_gemm_dequant_packed(pa, pw.packed, 16, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, am)
+    finally:
+        mq.mq_set_gemm_variant(0)
+    assert np.array_equal(host(Y), o["Y"])
+    assert host(am)[0] == np.abs(o["Y"]).max()
 
 
 def test_gemm_packed_one_hot_layout():
