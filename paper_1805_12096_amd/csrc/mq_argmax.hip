@@ -22,8 +22,12 @@
 //   * sums of 8-bit products over K <= 512 stay below 2^23, so (sum << 8 |
 //     255 - stage) is a 32-bit key whose integer maximum is the arg-max with
 //     the earliest stage winning ties: two VALU operations per candidate;
-//   * every workgroup writes one 64-bit (sum, index) key per sentence; a second
-//     small kernel reduces them and decodes.  No atomics, no initialisation.
+//   * every workgroup writes one 64-bit (sum, index) key per sentence, its own
+//     run of consecutive keys; a second small kernel reduces them and decodes.
+//     No atomics, no initialisation.  (Folding that reduction into this kernel
+//     was tried -- 64-bit atomic maxima per sentence with the last workgroup out
+//     decoding -- and took three times as long: the 76 800 atomics serialise on
+//     the few cache lines that hold the maxima.)
 // 64-bit keys order by sum first and by smaller index second:
 //   key = (sum ^ 0x80000000) << 32 | (0xFFFFFFFF - n);  0 means "no candidate".
 #include <mutex>
@@ -54,7 +58,7 @@ struct ArgmaxParams {
   const uint8_t* packedA;   // hidden states, packed 8 bit [M x K]
   const uint8_t* packedW;   // embedding, packed 8 bit [N x K]
   unsigned M, N, K;
-  unsigned long long* partial;   // [M][gridDim.x]
+  unsigned long long* partial;   // BEAM == 1: [gridDim.x][Mpad], Mpad = M rounded up to 16; beam search: [M][gridDim.x][BEAM]
   const int32_t* shortlist;      // optional: vocabulary rows to score, ascending; NULL = all N rows
   unsigned L;                    // candidates: shortlist length, or N
   // beam search (BEAM > 1): partial holds [M][gridDim.x][BEAM] keys, norm [M][gridDim.x] (max, sum) pairs of
@@ -415,31 +419,43 @@ __global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParam
     o = __shfl_xor(key, 32, 64);
     if (o > key) key = o;
     const unsigned m = (wave + kWaves * i) * 16 + lane % 16;
-    if (lane < 16 && m < p.M) p.partial[(size_t)m * gridDim.x + blockIdx.x] = key;
+    // this workgroup's keys are consecutive in memory: the 16 lanes of a sentence tile fill one 128-byte line
+    if (lane < 16 && m < p.M) p.partial[(size_t)blockIdx.x * (((size_t)p.M + 15) / 16 * 16) + m] = key;
   }
 }
 
-// One wave per sentence: maximum over the per-workgroup keys, then decode.
+// One workgroup per tile of 16 sentences: 16 groups of 16 lanes each take every 16th workgroup's keys of the tile (one
+// 128-byte line per group and load), the groups' maxima meet in LDS, and 16 lanes decode.
 __global__ __launch_bounds__(256) void k_argmax_reduce(const unsigned long long* __restrict__ partial, unsigned cols,
                                                        unsigned M, const float* __restrict__ sA,
                                                        const float* __restrict__ sW, int32_t* __restrict__ tok,
                                                        float* __restrict__ maxlogit,
                                                        const int32_t* __restrict__ shortlist) {
-  const int lane = threadIdx.x % 64;
-  const unsigned m = blockIdx.x * 4 + threadIdx.x / 64;
-  if (m >= M) return;
-  const unsigned long long* row = partial + (size_t)m * cols;
+  __shared__ unsigned long long red[16][16];
+  const unsigned mi = threadIdx.x % 16, gs = threadIdx.x / 16;
+  const unsigned m = blockIdx.x * 16 + mi;
+  const size_t Mpad = ((size_t)M + 15) / 16 * 16;
   unsigned long long key = 0ull;
-  for (unsigned g = lane; g < cols; g += 64) {
-    const unsigned long long k = row[g];
-    if (k > key) key = k;
+  if (m < M) {
+    const unsigned long long* col = partial + m;
+    unsigned g = gs;
+    for (; g + 48 < cols; g += 64) {              // four independent loads in flight per lane
+      const unsigned long long k0 = col[(size_t)g * Mpad], k1 = col[(size_t)(g + 16) * Mpad];
+      const unsigned long long k2 = col[(size_t)(g + 32) * Mpad], k3 = col[(size_t)(g + 48) * Mpad];
+      const unsigned long long a = k0 > k1 ? k0 : k1, b = k2 > k3 ? k2 : k3, c = a > b ? a : b;
+      if (c > key) key = c;
+    }
+    for (; g < cols; g += 16) {
+      const unsigned long long k = col[(size_t)g * Mpad];
+      if (k > key) key = k;
+    }
   }
+  red[gs][mi] = key;
+  __syncthreads();
+  if (gs == 0 && m < M) {
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const unsigned long long o = __shfl_xor(key, off, 64);
-    if (o > key) key = o;
-  }
-  if (lane == 0) {
+    for (int j = 1; j < 16; ++j)
+      if (red[j][mi] > key) key = red[j][mi];
     const float u = __fdiv_rn(1.0f, __fmul_rn(*sA, *sW));
     const int best = (int)((unsigned)(key >> 32) ^ 0x80000000u);
     const unsigned pos = 0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull);
@@ -534,7 +550,11 @@ int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
 
 }  // namespace
 
-size_t argmax_stream_ws_bytes(size_t M) { return (size_t)kMaxBlocks * M * sizeof(unsigned long long); }
+// one pass's keys: a run of (rows of the pass, rounded up to 16) keys per workgroup
+size_t argmax_stream_ws_bytes(size_t M) {
+  const size_t rows = M < (size_t)kWaves * 3 * 16 ? M : (size_t)kWaves * 3 * 16;
+  return (size_t)kMaxBlocks * round_up(rows, 16) * sizeof(unsigned long long);
+}
 
 // Limits: sums must fit 24 bits (127^2 K < 2^23); at most 255 stages per workgroup.  Any number of rows: 384 per pass.
 bool argmax_stream_supported(size_t M, size_t N, size_t K) {
@@ -589,7 +609,7 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
       }
     }
     if (rc != MQ_OK) return rc;
-    hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, p.partial, grid,
+    hipLaunchKernelGGL(k_argmax_reduce, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, s, p.partial, grid,
                        (unsigned)rows, sA, sW, tok + row0, maxlogit + row0, shortlist);
     rc = check_hip(hipGetLastError());
     if (rc != MQ_OK) return rc;

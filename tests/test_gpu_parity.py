@@ -1228,6 +1228,19 @@ def test_greedy_shortlist_ties_and_frequent_plus_translations_shape():
     assert np.all(np.isin(tok, sl))
 
 
+def test_greedy_shortlist_ids_outside_the_vocabulary_do_not_fault():
+    # an id outside [0, N) is the caller's mistake; the kernel scores the nearest row in its place instead of reading
+    # outside the embedding, and reports the id as listed if that candidate wins
+    c = workloads.config3(M=9, V=500, d=64, seed_extra=3)
+    bad = np.array([-7, 3, 17, 250, 100000], dtype=np.int32)
+    good_clamped = np.array([0, 3, 17, 250, 499])
+    o = oracle.greedy_output_layer(c["Hd"], c["E"], shortlist=np.unique(good_clamped))
+    tok_bad, val_bad = gpu_greedy_shortlist(c["Hd"], c["E"], bad)
+    assert np.array_equal(val_bad, o["maxlogit"])                       # rows 0 and 499 were scored in their place
+    back = {-7: 0, 100000: 499}
+    assert np.array_equal(np.array([back.get(int(t), int(t)) for t in tok_bad]), o["tok"])
+
+
 # ---------------------------------- fixed multipliers (the paper's scheme) and auto-tuning
 
 @pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (300, 256, 520), (130, 96, 1000)])
