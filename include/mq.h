@@ -447,7 +447,8 @@ int mq_ffn_i8_f32_prepared(const float* A, size_t M, size_t d, size_t f, const v
 /* The same block in 16 bit (Transformer-big style): quant_int(A), product +
  * b1 + ReLU into a binary32 H kept in ws with max|H| as a by-product of the
  * epilogue, quant_int(H) straight into the packed layout with the multiplier
- * formed in that kernel, second product + b2.  Five launches, no host
+ * formed in that kernel, second product + b2.  (The input is read once where
+ * it fits the one-kernel quantizer, see "Single-pass kernels" at the top.)  Five launches, no host
  * synchronisation; packedW1 / packedW2 from mq_prepare_weight(bits = 16).
  * Results are identical to the call-by-call chain.  Arguments as
  * mq_ffn_i8_f32; ws: mq_ffn_i16_ws_bytes(M, d, f) bytes (it holds H). */
@@ -455,6 +456,19 @@ size_t mq_ffn_i16_ws_bytes(size_t M, size_t d, size_t f);
 int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* packedW1, const float* sW1,
                    const float* b1, const void* packedW2, const float* sW2, const float* b2, float* Y,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* The 16-bit block with multipliers fixed in advance, the paper's own 16-bit scheme (Section 4.2: every tensor
+ * times 2^10, sums in 32 bits, so that no sum can wrap for the model's value range): quant_int(A, sA[0]), product +
+ * b1 + ReLU re-quantized with sH[0] in the producing epilogue (saturating at +-32767; the intermediate goes to
+ * memory once, as packed 16-bit values, never as floats), product + b2.  No abs-max pass anywhere.  Four launches.
+ * sA, sH: device float[1] multipliers of the input and of the intermediate; packedW1 / packedW2 prepared with
+ * bits = 16 and whatever multipliers sW1 / sW2 say (2^10 in the paper).  Results are those of
+ * mq_quantize_pack_f32 + mq_gemm_requant_fixed_packed_i16 + mq_gemm_dequant_packed bit for bit.
+ * ws: device, 256-byte aligned, mq_ffn_i16_fixed_ws_bytes(M, d, f) bytes, contents irrelevant. */
+size_t mq_ffn_i16_fixed_ws_bytes(size_t M, size_t d, size_t f);
+int mq_ffn_i16_fixed_f32(const float* A, size_t M, size_t d, size_t f, const float* sA, const void* packedW1,
+                         const float* sW1, const float* b1, const float* sH, const void* packedW2, const float* sW2,
+                         const float* b2, float* Y, void* ws, size_t ws_bytes, void* stream);
 
 /* Output layer for beam search with beam size > 1 (Table 2, the b = 2 and b = 4
  * rows): for every row of the packed hidden states the k <= 4 most probable

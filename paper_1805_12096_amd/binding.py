@@ -19,7 +19,7 @@ __all__ = [
     "mq_version", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant",
     "mq_absmax_f32", "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes",
     "mq_prepare_weight", "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant",
-    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
+    "mq_gemm_i32_packed", "mq_gemm_dequant_packed", "mq_argmax_ws_bytes", "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32", "mq_ffn_i16_fixed_ws_bytes", "mq_ffn_i16_fixed_f32",
     "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes", "mq_gemm_amax_packed",
     "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed", "mq_gemm_requant_fixed_packed_i16",
     "mq_autotune_ws_bytes", "mq_autotune_gemm", "mq_autotune_report",
@@ -56,7 +56,7 @@ def exported_symbols():
             "mq_scale_from_amax", "mq_quantize_f32", "mq_quantize_pack_f32", "mq_packed_bytes", "mq_prepare_weight",
             "mq_unpack_weight", "mq_gemm_i32", "mq_gemm_dequant", "mq_gemm_i32_packed",
             "mq_gemm_dequant_packed", "mq_argmax_ws_bytes",
-            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32",
+            "mq_gemm_argmax", "mq_gemm_argmax_packed", "mq_gemm_argmax_packed_static", "mq_gemm_argmax_shortlist", "mq_linear_ws_bytes", "mq_linear_f32", "mq_ffn_ws_bytes", "mq_ffn_i8_f32", "mq_ffn_ws_prepare", "mq_ffn_i8_f32_prepared", "mq_set_ffn_single_pass", "mq_gemm_requant_single_packed", "mq_single_pass_fits", "mq_set_barrier_timeout_us", "mq_set_quantize_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_f32", "mq_ffn_i16_fixed_ws_bytes", "mq_ffn_i16_fixed_f32",
             "mq_quantize_absmax_ws_bytes", "mq_quantize_absmax_pack_f32", "mq_quantize_absmax_ws_prepare", "mq_quantize_absmax_pack_f32_prepared", "mq_gemm_amax_ws_bytes",
             "mq_gemm_amax_packed", "mq_gemm_requant_packed", "mq_gemm_requant_fixed_packed",
             "mq_gemm_requant_fixed_packed_i16",
@@ -140,6 +140,9 @@ def load_library():
     lib.mq_ffn_i8_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_ffn_i8_f32_prepared.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_ffn_ws_prepare.argtypes = [vp, sz, sz, sz, sz, vp]
+    lib.mq_ffn_i16_fixed_ws_bytes.restype = sz
+    lib.mq_ffn_i16_fixed_ws_bytes.argtypes = [sz, sz, sz]
+    lib.mq_ffn_i16_fixed_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mq_ffn_i16_ws_bytes.restype = sz
     lib.mq_ffn_i16_ws_bytes.argtypes = [sz, sz, sz]
     lib.mq_ffn_i16_f32.argtypes = [vp, sz, sz, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -414,6 +417,16 @@ def mq_ffn_i16_ws_bytes(M, d, f) -> int:
 def mq_ffn_i16_f32(A, M, d, f, packedW1, sW1, b1, packedW2, sW2, b2, Y, ws, ws_bytes, stream=None):
     _check(load_library().mq_ffn_i16_f32(_p(A), M, d, f, _p(packedW1), _p(sW1), _p(b1), _p(packedW2), _p(sW2),
                                          _p(b2), _p(Y), _p(ws), ws_bytes, _stream(stream)), "mq_ffn_i16_f32")
+
+
+def mq_ffn_i16_fixed_ws_bytes(M, d, f) -> int:
+    return int(load_library().mq_ffn_i16_fixed_ws_bytes(M, d, f))
+
+
+def mq_ffn_i16_fixed_f32(A, M, d, f, sA, packedW1, sW1, b1, sH, packedW2, sW2, b2, Y, ws, ws_bytes, stream=None):
+    _check(load_library().mq_ffn_i16_fixed_f32(_p(A), M, d, f, _p(sA), _p(packedW1), _p(sW1), _p(b1), _p(sH),
+                                               _p(packedW2), _p(sW2), _p(b2), _p(Y), _p(ws), ws_bytes, _stream(stream)),
+           "mq_ffn_i16_fixed_f32")
 
 
 def mq_topk_ws_bytes(M, N, k) -> int:

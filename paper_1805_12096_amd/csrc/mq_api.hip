@@ -725,11 +725,12 @@ namespace mq {
 namespace {
 // Scratch layout of mq_ffn_i16_f32.
 struct Ffn16Ws {
-  size_t off_part, off_scal, off_qA, off_H, off_qH, total;
+  size_t off_part, off_scal, off_bar, off_qA, off_H, off_qH, total;
   Ffn16Ws(size_t M, size_t d, size_t f) {
     off_part = 0;
     off_scal = round_up(kAbsmaxPartials * sizeof(float), 256);
-    off_qA = off_scal + 256;
+    off_bar = off_scal + 256;                                        // agreement words of the one-kernel quantizer
+    off_qA = off_bar + round_up(kBarrierWords * sizeof(unsigned), 256);
     off_H = round_up(off_qA + PackedDims(16, M, d).total_bytes(), 256);
     off_qH = round_up(off_H + M * f * sizeof(float), 256);
     total = round_up(off_qH + PackedDims(16, M, f).total_bytes(), 256);
@@ -765,8 +766,20 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
   uint8_t* qA = base + L.off_qA;
   float* H = reinterpret_cast<float*>(base + L.off_H);
   uint8_t* qH = base + L.off_qH;
-  // a1 + a2 on the input; the same first kernel zeroes max|H|
-  int rc = launch_absmax_quantize_pack(A, M, d, 16, part, sA, qA, s, reinterpret_cast<unsigned*>(hmax), 1);
+  // a1 + a2 on the input.  Where the tensor fits the registers of one resident grid it is read once: a small launch
+  // clears the agreement words and max|H|, then one kernel finds max|A| across the grid and converts from registers;
+  // otherwise two passes (partial maxima, then the quantizer), the first of which zeroes max|H|.
+  unsigned* bar = reinterpret_cast<unsigned*>(base + L.off_bar);
+  static_assert(sizeof(float) * 3 <= 256, "max|H| sits right in front of the agreement words");
+  int rc = MQ_ERR_UNSUPPORTED;
+  if (g_ffn_single_pass && M * d >= ((size_t)1 << 20)) {
+    // hmax is the third float of the 256 bytes in front of `bar`: one clearing launch covers both
+    rc = launch_clear_words(reinterpret_cast<unsigned*>(hmax), (unsigned)((L.off_bar - L.off_scal) / 4 - 2 + kBarrierWords), s);
+    if (rc != MQ_OK) return rc;
+    rc = launch_absmax_quantize_pack_fused(A, M, d, 16, bar, sA, qA, s);
+  }
+  if (rc == MQ_ERR_UNSUPPORTED)
+    rc = launch_absmax_quantize_pack(A, M, d, 16, part, sA, qA, s, reinterpret_cast<unsigned*>(hmax), 1);
   if (rc != MQ_OK) return rc;
   // a4 + a5: H = relu(A W1 + b1) in binary32, max|H| as a by-product of the epilogue
   GemmArgs g1{};
@@ -781,6 +794,41 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
   GemmArgs g2{};
   g2.qA = qH;
   g2.packedW = packedW2; g2.bits = 16; g2.M = M; g2.N = d; g2.K = f;
+  g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
+  return launch_gemm_packed(g2, kEpiDequant, s);
+}
+
+size_t mq_ffn_i16_fixed_ws_bytes(size_t M, size_t d, size_t f) {
+  if (!dims_ok(M, f, d)) return 0;
+  return round_up(PackedDims(16, M, d).total_bytes(), 256) + round_up(PackedDims(16, M, f).total_bytes(), 256);
+}
+
+int mq_ffn_i16_fixed_f32(const float* A, size_t M, size_t d, size_t f, const float* sA, const void* packedW1,
+                         const float* sW1, const float* b1, const float* sH, const void* packedW2, const float* sW2,
+                         const float* b2, float* Y, void* ws, size_t ws_bytes, void* stream) {
+  if (A == nullptr || sA == nullptr || packedW1 == nullptr || sW1 == nullptr || sH == nullptr || packedW2 == nullptr ||
+      sW2 == nullptr || Y == nullptr || ws == nullptr)
+    return MQ_ERR_NULL;
+  if (!dims_ok(M, f, d)) return MQ_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(packedW1, 16) || !aligned(packedW2, 16) || !aligned(ws, 256) || !aligned(sA, 4) ||
+      !aligned(sW1, 4) || !aligned(sH, 4) || !aligned(sW2, 4) || !aligned(Y, 4))
+    return MQ_ERR_ALIGN;
+  if ((b1 != nullptr && !aligned(b1, 4)) || (b2 != nullptr && !aligned(b2, 4))) return MQ_ERR_ALIGN;
+  if (ws_bytes < mq_ffn_i16_fixed_ws_bytes(M, d, f)) return MQ_ERR_WORKSPACE;
+  hipStream_t s = as_stream(stream);
+  uint8_t* qA = static_cast<uint8_t*>(ws);
+  uint8_t* qH = qA + round_up(PackedDims(16, M, d).total_bytes(), 256);
+  // quant_int(A) with the given multiplier, product + b1 + ReLU re-quantized with the given multiplier in the
+  // epilogue (H goes to memory once, as packed 16-bit values), product + b2
+  int rc = launch_quantize_pack(A, M, d, 16, sA, qA, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs g1{};
+  g1.qA = qA; g1.packedW = packedW1; g1.bits = 16; g1.M = M; g1.N = f; g1.K = d;
+  g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1;
+  rc = launch_gemm_requant_fixed_i16(g1, sH, qH, s);
+  if (rc != MQ_OK) return rc;
+  GemmArgs g2{};
+  g2.qA = qH; g2.packedW = packedW2; g2.bits = 16; g2.M = M; g2.N = d; g2.K = f;
   g2.sA = sH; g2.sW = sW2; g2.bias = b2; g2.relu = 0; g2.Y = Y;
   return launch_gemm_packed(g2, kEpiDequant, s);
 }

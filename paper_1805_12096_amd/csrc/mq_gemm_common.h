@@ -69,10 +69,14 @@ __device__ __forceinline__ void tile_coords(unsigned tiles_m, unsigned tiles_n, 
 //   acc = 2^16 hh + 2^8 mid + ll + 128 (rowsum[m] + colsum[n]) - 16384 K  (mod 2^32).
 // bias_pre (optional): this lane's TN biases (0 where there is none), fetched by the caller before its main
 // loop so that the epilogue does not start with a memory round trip.
+// row_base / col_base: index of rowsum[0] / colsum[0] (a caller that has copied its tile's sums to LDS before its
+// main loop, for the same reason, passes the tile's origin; sums of rows and columns past the end must then be there
+// too, as zeros).
 template <int BITS, int TM, int TN, int NACC, int EPI, int NWAVES>
 __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const Params& p, unsigned wave_m0,
                                                unsigned wave_n0, const int32_t* rowsum, const int32_t* colsum,
-                                               const float* bias_pre = nullptr) {
+                                               const float* bias_pre = nullptr, unsigned row_base = 0,
+                                               unsigned col_base = 0) {
   const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
   const int lj = lane % 32, lh = lane / 32;
   float u = 0.f, local_amax = 0.f;
@@ -88,7 +92,7 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
       v = acc[mt][nt][0][r];
     } else {
       const unsigned t = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
-                         (unsigned)acc[mt][nt][NACC - 1][r] + 128u * (unsigned)rowsum[m] + corr_n;
+                         (unsigned)acc[mt][nt][NACC - 1][r] + 128u * (unsigned)rowsum[m - row_base] + corr_n;
       v = (int)t;
     }
     const size_t uni = (size_t)(wave_m0 + mt * 32 + 8 * (r / 4) + r % 4) * p.N + wave_n0 + nt * 32;
@@ -111,7 +115,7 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
         if (bias_pre != nullptr) bias = bias_pre[nt];
         else if (p.bias != nullptr) bias = p.bias[n];
       }
-      if (BITS == 16) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
+      if (BITS == 16) corr_n = 128u * (unsigned)colsum[n - col_base] - 16384u * p.K;
 #pragma unroll
       for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
@@ -128,7 +132,7 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
         if (bias_pre != nullptr) bias = bias_pre[nt];
         else if (p.bias != nullptr && n_ok) bias = p.bias[n];
       }
-      if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n] - 16384u * p.K;
+      if (BITS == 16 && n_ok) corr_n = 128u * (unsigned)colsum[n - col_base] - 16384u * p.K;
 #pragma unroll
       for (int mt = 0; mt < TM; ++mt)
 #pragma unroll

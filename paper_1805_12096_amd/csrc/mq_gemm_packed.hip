@@ -101,6 +101,20 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     static_assert(NW * 64 >= BN, "one thread per column of the tile");
     if (tid < BN && p.bias != nullptr && n0 + tid < p.N) bias_early = p.bias[n0 + tid];
   }
+  // 16 bit: the row and column sums the recombination needs (and the re-quantizing epilogue's biases) go to LDS
+  // before the main loop as well; fetched in the epilogue they are dependent memory round trips per sub-tile
+  __shared__ int32_t s_rowsum[BITS == 16 ? BM : 1];
+  __shared__ int32_t s_colsum[BITS == 16 ? BN : 1];
+  __shared__ float s_bias16[BITS == 16 && EPI == kPRequant ? BN : 1];
+  if constexpr (BITS == 16) {
+    const int32_t* rs = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
+    const int32_t* cs = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
+    for (unsigned i = tid; i < (unsigned)BM; i += NW * 64) s_rowsum[i] = m0 + i < p.M ? rs[m0 + i] : 0;
+    for (unsigned i = tid; i < (unsigned)BN; i += NW * 64) s_colsum[i] = n0 + i < p.N ? cs[n0 + i] : 0;
+    if constexpr (EPI == kPRequant)
+      for (unsigned i = tid; i < (unsigned)BN; i += NW * 64)
+        s_bias16[i] = (p.bias != nullptr && n0 + i < p.N) ? p.bias[n0 + i] : 0.0f;
+  }
   // the dequantizing epilogue's biases: one per lane and column block, in registers across the main loop
   float bias_pre[TN];
   if constexpr (EPI == kPDequant) {
@@ -360,19 +374,78 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
     const float u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
     const float s2 = *p.s_out;
     const bool relu = p.relu != 0;
-    const bool has_bias = p.bias != nullptr;
     const unsigned wm0 = m0 + wm * TM * 32, wn0 = n0 + wn * TN * 32;
-    const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
-    const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
     const PackedDims dO(16, p.M, p.N);
     int32_t* rowsum_out = reinterpret_cast<int32_t*>(p.packed_out + dO.plane_bytes());
     __syncthreads();                               // every wave is done reading the last stage
     uint8_t* scratch = smem + wave * 2 * kFragBytes;     // one sub-tile's two planes
+    // The usual case -- ReLU on, no row or column of the tile past the end, a positive finite multiplier -- needs less
+    // arithmetic per element, and this epilogue is bound by it (33 million elements with the matrix cores idle):
+    // after ReLU 0 <= y (NaN became 0), so quant_int is t = min(y s2, 32767) and one rounding addition:
+    // t + 1.5 * 2^23 rounds t to the nearest integer, ties to even like rint, and leaves it in the low mantissa bits;
+    // byte permutes cut the two planes out of four such words at a time, and the row sums are dot products of the
+    // planes' bytes with ones (every value is non-negative, so is its high byte).
+    const bool fast = relu && m0 + BM <= p.M && n0 + BN <= p.N && s2 > 0.0f && s2 < __builtin_inff();
+    if (fast) {
+      unsigned racc[TM];
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) racc[mt] = 0;
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) {
+        unsigned ccol[16];
+        float bcol[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const unsigned nl = wn0 - n0 + nt * 32 + 8 * (j / 4) + 4 * lh + j % 4;
+          ccol[j] = 128u * (unsigned)s_colsum[nl] - 16384u * p.K;
+          bcol[j] = s_bias16[nl];
+        }
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt) {
+          const unsigned m = wm0 + mt * 32 + lj;
+          const unsigned corr_m = 128u * (unsigned)s_rowsum[m - m0];
+          unsigned sum_lo = 0, sum_hi = 0;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            uint32_t w[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const int r = 4 * q + t;
+              const unsigned v = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
+                                 (unsigned)acc[mt][nt][NACC - 1][r] + corr_m + ccol[r];
+              const float y = fmaxf(fmaf((float)(int)v, u, bcol[r]), 0.0f);
+              w[t] = __float_as_uint(__fadd_rn(fminf(__fmul_rn(y, s2), 32767.0f), 12582912.0f));
+            }
+            const uint32_t lo = __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0400u) | __builtin_amdgcn_perm(w[3], w[2], 0x04000c0cu);
+            const uint32_t hi = __builtin_amdgcn_perm(w[1], w[0], 0x0c0c0501u) | __builtin_amdgcn_perm(w[3], w[2], 0x05010c0cu);
+            sum_lo = __builtin_amdgcn_udot4(lo, 0x01010101u, sum_lo, false);
+            sum_hi = __builtin_amdgcn_udot4(hi, 0x01010101u, sum_hi, false);
+            const unsigned at = (lj + 32 * (q / 2)) * 16 + 8 * (q % 2) + 4 * lh;
+            *reinterpret_cast<uint32_t*>(scratch + at) = hi;
+            *reinterpret_cast<uint32_t*>(scratch + kFragBytes + at) = lo ^ 0x80808080u;
+          }
+          __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the wave's own writes
+          const u4 vh = *reinterpret_cast<const u4*>(scratch + lane * 16);
+          const u4 vl = *reinterpret_cast<const u4*>(scratch + kFragBytes + lane * 16);
+          uint8_t* dst = p.packed_out + dO.frag_offset((wm0 + mt * 32) / 32, (wn0 + nt * 32) / 32) + lane * 16;
+          *reinterpret_cast<u4*>(dst) = vh;
+          *reinterpret_cast<u4*>(dst + kFragBytes) = vl;
+          __builtin_amdgcn_s_waitcnt(0xC07F);          // the reads must finish before the next sub-tile overwrites
+          racc[mt] += sum_lo + 256u * sum_hi;
+        }
+      }
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        int rowacc = (int)racc[mt];
+        rowacc += __shfl_xor(rowacc, 32, 64);
+        if (lh == 0) atomicAdd(&rowsum_out[wm0 + mt * 32 + lj], rowacc);
+      }
+    } else
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
       const unsigned m = wm0 + mt * 32 + lj;
       const bool m_ok = m < p.M;
-      const unsigned corr_m = 128u * (unsigned)rowsum[m_ok ? m : p.M - 1] - 16384u * p.K;
+      const unsigned corr_m = 128u * (unsigned)s_rowsum[m - m0] - 16384u * p.K;
       int rowacc = 0;
 #pragma unroll
       for (int nt = 0; nt < TN; ++nt) {
@@ -383,10 +456,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
           for (int t = 0; t < 4; ++t) {
             const int r = 4 * q + t;
             const unsigned n = wn0 + nt * 32 + 8 * q + 4 * lh + t;
-            const unsigned nc = n < p.N ? n : p.N - 1;
             const unsigned v = ((unsigned)acc[mt][nt][0][r] << 16) + ((unsigned)acc[mt][nt][NACC - 2][r] << 8) +
-                               (unsigned)acc[mt][nt][NACC - 1][r] + corr_m + 128u * (unsigned)colsum[nc];
-            float y = fmaf((float)(int)v, u, has_bias ? p.bias[nc] : 0.0f);
+                               (unsigned)acc[mt][nt][NACC - 1][r] + corr_m + 128u * (unsigned)s_colsum[n - n0];
+            float y = fmaf((float)(int)v, u, s_bias16[n - n0]);
             if (relu) y = fmaxf(y, 0.0f);                       // NaN -> 0 like (y > 0) ? y : 0
             const float rr = rintf(__fmul_rn(y, s2));
             int qi;
@@ -654,10 +726,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_pp(const Params p) {
       }
     }
   } else {
-    const int32_t* rowsum = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
-    const int32_t* colsum = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
     store_epilogue<BITS, TM, TN, NACC, EPI == kPRaw ? kEpiRaw : kEpiDequant, NW>(
-        acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, rowsum, colsum, EPI == kPDequant ? bias_pre : nullptr);
+        acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, s_rowsum, s_colsum, EPI == kPDequant ? bias_pre : nullptr, m0, n0);
   }
 }
 
@@ -837,6 +907,8 @@ int launch_gemm_requant_fixed_i16(const GemmArgs& a, const float* s_fixed, void*
   GemmArgs b = a;
   b.s_out = const_cast<float*>(s_fixed);
   b.packed_out = packed_out;
+  // (measured against the 256 x 128 tile of the fastest plain product on one device in alternation, config 4's first
+  // product: 136 us here, 143 us there -- its 192 accumulator registers leave this epilogue too few to work with)
   return launch_pp<16, 128, 128, 4, 2, 4, kPRequant>(b, s);
 }
 

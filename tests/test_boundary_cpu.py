@@ -140,6 +140,8 @@ def _rows():
         "mq_ffn_i8_f32": ffn,
         "mq_ffn_i8_f32_prepared": ffn,
         "mq_ffn_i16_f32": ffn,
+        "mq_ffn_i16_fixed_f32": [(G, P16), (64, N_), (64, N_), (64, N_), (G, P4), (G, P16), (G, P4), (G, OPT), (G, P4),
+                                 (G, P16), (G, P4), (G, OPT), (G, P4), (G, WSP), (BIG, WSB), (None, X)],
         "mq_ffn_ws_prepare": [(G, WSP), (BIG, WSB), (64, N_), (64, N_), (64, N_), (None, X)],
         "mq_gemm_topk_packed": [(G, P16), (G, P16), (G, OPT), (8, X), (4, N_), (16, N_), (4, N_), (G, P4), (G, P4), (2, X),
                                 (G, P4), (G, P4), (G, WSP), (BIG, WSB), (None, X)],
@@ -155,7 +157,7 @@ def _rows():
 QUERIES_AND_SETTERS = {"mq_version", "mq_autotune_report", "mq_status_string", "mq_last_hip_error", "mq_set_gemm_variant", "mq_packed_bytes",
                        "mq_set_quantize_single_pass", "mq_quantize_absmax_ws_bytes", "mq_gemm_amax_ws_bytes",
                        "mq_set_barrier_timeout_us", "mq_single_pass_fits", "mq_autotune_ws_bytes", "mq_argmax_ws_bytes",
-                       "mq_linear_ws_bytes", "mq_ffn_ws_bytes", "mq_set_ffn_single_pass", "mq_ffn_i16_ws_bytes",
+                       "mq_linear_ws_bytes", "mq_ffn_ws_bytes", "mq_set_ffn_single_pass", "mq_ffn_i16_ws_bytes", "mq_ffn_i16_fixed_ws_bytes",
                        "mq_topk_ws_bytes", "mq_aan_layer_ws_bytes"}
 
 

@@ -766,7 +766,7 @@ def test_ffn_single_pass_and_two_pass_agree_with_oracle(M, d, f):
         mq.mq_set_ffn_single_pass(1)
 
 
-@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (300, 256, 520)])
+@pytest.mark.parametrize("M,d,f", [(1, 1, 1), (37, 64, 200), (300, 256, 520), (2100, 512, 96)])
 def test_ffn_int16_one_call_matches_oracle_chain(M, d, f):
     c = workloads.ffn(4, M, d, f, 0.03, 16, seed_extra=M + d + 3 * f)
     o1 = oracle.linear(c["A"], c["W1t"], 16, c["b1"], True)
@@ -1270,6 +1270,34 @@ def test_ffn_int16_with_the_fixed_multiplier(M, d, f):
         Y = torch.empty((M, d), dtype=torch.float32, device=DEV)
         mq.mq_gemm_dequant_packed(qH, p2.packed, 16, M, d, f, sc, sc, dev(c["b2"]), False, Y, None)
         assert np.array_equal(host(Y), o2["Y"])
+    # the same block in one call
+    nb = mq.mq_ffn_i16_fixed_ws_bytes(M, d, f)
+    ws = torch.full((nb,), 0x6E, dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        Y = torch.full((M, d), float("nan"), dtype=torch.float32, device=DEV)
+        mq.mq_ffn_i16_fixed_f32(dev(c["A"]), M, d, f, sc, p1.packed, sc, dev(c["b1"]), sc, p2.packed, sc, dev(c["b2"]), Y,
+                                ws, nb)
+        assert np.array_equal(host(Y), o2["Y"])
+
+
+def test_ffn_int16_fixed_multiplier_full_size_equals_oracle_on_all_rows():
+    # the paper's 16-bit scheme at the benchmark's 8192 x 1024 x 4096, one call, every row against the oracle;
+    # with 2^10 no 32-bit sum wraps (Section 4.2 chose the multiplier for that)
+    c = workloads.config4()
+    M, d = c["A"].shape
+    f = c["W1t"].shape[0]
+    S = np.float32(1024.0)
+    o1 = oracle.linear(c["A"], c["W1t"], 16, c["b1"], True, sA=S, sW=S)
+    o2 = oracle.linear(o1["Y"], c["W2t"], 16, c["b2"], False, sA=S, sW=S)
+    assert o1["overflow_count"] == 0 and o2["overflow_count"] == 0
+    sc = torch.full((1,), 1024.0, dtype=torch.float32, device=DEV)
+    p1 = mq.prepare_weight(dev(c["W1t"]), 16, scale=sc)
+    p2 = mq.prepare_weight(dev(c["W2t"]), 16, scale=sc)
+    nb = mq.mq_ffn_i16_fixed_ws_bytes(M, d, f)
+    ws = torch.full((nb,), 0x6E, dtype=torch.uint8, device=DEV)
+    Y = torch.full((M, d), float("nan"), dtype=torch.float32, device=DEV)
+    mq.mq_ffn_i16_fixed_f32(dev(c["A"]), M, d, f, sc, p1.packed, sc, dev(c["b1"]), sc, p2.packed, sc, dev(c["b2"]), Y, ws, nb)
+    assert np.array_equal(host(Y), o2["Y"])
 
 
 def test_ffn_with_fixed_multipliers_single_pass():
