@@ -3,24 +3,32 @@
 
 One "step" is one pass of the whole hot path over one synthetic batch that is
 already resident in HBM: abs-max and quant_int of the activations, dot'_int on
-the int8 matrix cores with the dequantize + bias + ReLU epilogue, re-quantization
-of the intermediate, the second product (arxiv 1805.12096, Sections 4.2-4.3).
-The default workload is the Transformer-base FFN block in int8 at M = 8192
-tokens (the paper's GPU batch size, Section 2.3; widths from Table 1).  Parameter
-preparation is memoized (Section 4.3) and therefore outside the timed region.
+the int8 matrix cores with the dequantize + bias + ReLU epilogue, quant_int of
+the intermediate, the second product (arxiv 1805.12096, Sections 4.2-4.3).
+The headline workload is the Transformer-big FFN block in int16 at M = 8192
+tokens (the paper's GPU batch size, Section 2.3; widths from Table 1): the
+largest of the benchmark configurations and the only one bound by the matrix
+cores.  Parameter preparation is memoized (Section 4.3) and outside the timed
+region.
 
 Prints ONE JSON line.  `value` is useful integer operations (2 M N K per
-product) per second for the whole step.  Beside it: the roofline position of
-the longest-running kernel (durations measured here with HIP events on the
-launch stream), the greedy output-layer workload (tokens/s, GB/s), the int16
-Transformer-big FFN, and the CPU oracle timed on this host on a bounded sample
-of the same workload.
+product) per second for the whole step.  Beside it: `roofline` for the step's
+dominant kernel (its launches timed here, alone, with HIP events on the launch
+stream), `rooflines` for the dominant kernels of the other configurations, the
+other configurations themselves under `extras` (base FFN block in int8 warm and
+cold, greedy output layer warm and cold, single int16 product, the decode step
+of the averaging-attention decoder with a per-product breakdown), and the CPU
+oracle timed on this host on the same workload.
+
+`--only NAME` runs one configuration alone (config1 .. config5): the commands
+behind the summaries under profiles/ use it.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -31,16 +39,8 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
-
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file on the default workload
-# (profiles/ffn_int8_hbm_counters.txt: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 after calibration on a known copy).
-MEASURED_TRAFFIC = {
-    "gemm1 single pass: bias+relu -> max|H| -> quant_int(H)": 29.7e6,
-    "(two-pass) gemm1 pass 1: bias+relu -> max|H|": 12.8e6,
-    "(two-pass) gemm1 pass 2: bias+relu -> quant_int(H)": 29.6e6,
-    "gemm2+bias": 41.6e6,
-    "absmax+quant_int(A) [2 launches]": 21.2e6,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+TRACE_US_FILE = os.path.join(ROOT, "profiles", "kernel_trace_us.txt")
 
 
 def parse_args():
@@ -48,16 +48,32 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-extras", action="store_true", help="skip the output-layer and int16 side workloads")
+    ap.add_argument("--only", default=None, choices=["config1", "config2", "config3", "config4", "config5"],
+                    help="run one configuration alone (profiling runs)")
+    ap.add_argument("--no-extras", action="store_true", help="headline configuration only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
+    ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying HIP graphs")
     ap.add_argument("--no-autotune", action="store_true", help="keep the shape heuristic instead of timing tile variants")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy, the known-size reference for scaling HBM counters")
-    ap.add_argument("--no-parity", action="store_true",
-                    help="skip the per-config parity / overflow report of the CPU leg")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the workload the oracle is timed on")
+                    help="also run plain 256 MiB device copies and a fill, the known-size reference for HBM counters")
+    ap.add_argument("--no-parity", action="store_true", help="skip the per-config parity / overflow report of the CPU leg")
     return ap.parse_args()
+
+
+def measured(path):
+    """`key = number` lines of a summary under profiles/, by roofline key: hbm_traffic_per_launch.txt holds the HBM-side
+    bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs, kernel_trace_us.txt the rocprofv3 kernel-trace
+    average durations.  Missing file or key: nothing."""
+    out = {}
+    try:
+        for line in open(path):
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=", 1)
+                out[k.strip()] = float(v)
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -77,24 +93,12 @@ def main():
     mq.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    QT = {8: torch.int8, 16: torch.int16}
+    traffic = measured(TRAFFIC_FILE)
+    trace_us = measured(TRACE_US_FILE)
+    want = lambda name: args.only is None or args.only == name
 
     def to_dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-
-    def time_events(fn, iters, warm):
-        """Average duration of fn in microseconds, HIP events on the launch stream."""
-        for _ in range(warm):
-            fn()
-        torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / iters
 
     def graphed(fn, reps=1):
         """Capture `reps` calls of fn into a HIP graph; returns a replay callable (or a plain loop)."""
@@ -116,46 +120,111 @@ def main():
     STEPS_PER_GRAPH = 10
     SPIN_UP_MS = 40.0
 
-    def time_steps(fn, steps, warm):
-        """Microseconds per step over EXACTLY `steps` steps after `warm` untimed ones.  Steps are replayed as HIP
-        graphs of STEPS_PER_GRAPH consecutive steps (the remainder one step at a time): a graph launch costs
-        several microseconds of its own, which a loop over batches would not pay once per batch."""
-        one = graphed(fn, 1)
-        many = graphed(fn, STEPS_PER_GRAPH) if steps >= STEPS_PER_GRAPH and not args.no_graph else None
+    def spin_up(run):
         # The device needs some tens of milliseconds of steady work to settle at its working clock after the idle
-        # gaps of set-up (the first of two identical measurements in a process came out 5 % slower): the step runs
-        # untimed for SPIN_UP_MS before the warm-up steps.
+        # gaps of set-up (the first of two identical measurements in a process came out 5 % slower).
         t_spin = time.perf_counter()
         while (time.perf_counter() - t_spin) * 1e3 < SPIN_UP_MS:
             for _ in range(8):
-                (many or one)()
+                run()
             torch.cuda.synchronize()
+
+    def timed_replays(run, n, per):
+        """n replays of `run` (each `per` steps or launches), an event between every two; returns (total us, list of us
+        per replay).  One synchronisation at the end; the events sit on the launch stream."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i in range(n):
+            run()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        each = [ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n)]
+        return ev[0].elapsed_time(ev[n]) * 1e3, each
+
+    def time_steps(fn, steps, warm, per_graph=STEPS_PER_GRAPH):
+        """EXACTLY `steps` steps after `warm` untimed ones.  Steps are replayed as HIP graphs of `per_graph` consecutive
+        steps (the remainder one step at a time): a graph launch costs several microseconds of its own, which a loop
+        over batches would not pay once per batch.  Returns (us per step over the whole timed region, median us per
+        step over the graph replays)."""
+        one = graphed(fn, 1)
+        many = graphed(fn, per_graph) if steps >= per_graph and not args.no_graph else None
+        spin_up(many or one)
         for _ in range(warm):
             one()
         torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
+        total = 0.0
+        per_step = []
         done = 0
         if many is not None:
-            for _ in range(steps // STEPS_PER_GRAPH):
-                many()
-                done += STEPS_PER_GRAPH
-        while done < steps:
-            one()
-            done += 1
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / steps
+            n = steps // per_graph
+            t, each = timed_replays(many, n, per_graph)
+            total += t
+            per_step += [e / per_graph for e in each]
+            done = n * per_graph
+        if done < steps:
+            t, each = timed_replays(one, steps - done, 1)
+            total += t
+            if many is None:
+                per_step += each
+        return total / steps, statistics.median(per_step)
 
     def time_kernel(fn, reps=10, iters=20):
-        """Average duration of one call of fn (us): `reps` back-to-back copies replayed as one graph, so
-        that host launch overhead does not hide kernels of a few microseconds."""
-        return time_events(graphed(fn, reps), iters, 3) / reps
+        """Duration of one call of fn (us): `reps` back-to-back copies replayed as one graph `iters` times, HIP events
+        around every replay; (mean, median) per call.  For a call that is one launch this is the launch's duration
+        plus the gap to the next one (about a microsecond), which is what rocprofv3's kernel trace shows as well."""
+        run = graphed(fn, reps)
+        for _ in range(3):
+            run()
+        total, each = timed_replays(run, iters, reps)
+        return total / (iters * reps), statistics.median(each) / reps
+
+    def roof(name, us, alg_bytes, issued_ops, useful_ops=None):
+        """Roofline entry of one kernel: the roof that binds it at its algorithmic bytes / issued matrix-core ops."""
+        t_hbm = alg_bytes / (PEAK_HBM_GBS * 1e3)
+        t_mfma = issued_ops / (PEAK_INT8_TOPS * 1e6)
+        if issued_ops > 0 and t_mfma >= t_hbm:
+            r = {"bound": "mfma", "achieved": round(issued_ops / us / 1e6, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s"}
+            if useful_ops is not None and useful_ops != issued_ops:
+                r["useful_TOPS"] = round(useful_ops / us / 1e6, 1)
+        else:
+            r = {"bound": "hbm", "achieved": round(alg_bytes / us / 1e3, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+            if issued_ops > 0:
+                r["mfma_TOPS_issued"] = round(issued_ops / us / 1e6, 1)
+        r["frac"] = round(r["achieved"] / r["peak"], 4)
+        r.update({"kernel": name, "us": round(us, 2), "alg_bytes": int(alg_bytes), "traffic": traffic.get(name)})
+        if name in trace_us:
+            # rocprofv3's average for the same kernel on the profiled device (profiles/): start of the first wave to
+            # end of the last; the HIP-event time above also holds the kernel boundary (drain, L2 write-back, dispatch)
+            r["us_kernel_trace_profiled_run"] = trace_us[name]
+        return r
 
     QWS = mq.mq_quantize_absmax_ws_bytes()     # workspace of the abs-max + quant_int call
+    tuned = {}
 
-    # ------------------------------------------------------------ FFN workloads
+    def autotune(bits, M_, N_, K_):
+        """Section 4.4 in miniature: time every implementation of this product shape once and freeze the fastest.
+        Records the winner and every loser's time."""
+        if args.no_autotune:
+            return
+        nb_ = mq.mq_autotune_ws_bytes(bits, M_, N_, K_)
+        ws_ = torch.empty(nb_, dtype=torch.uint8, device=dev)
+        best, us_ = mq.mq_autotune_gemm(bits, M_, N_, K_, 20, ws_, nb_)
+        allv = mq.mq_autotune_report()
+        entry = {"variant": best, "us": round(us_, 2), "all_variants_us": {str(k): round(v, 2) for k, v in allv.items()}}
+        if bits == 16:
+            mfma = {k: v for k, v in allv.items() if k != 7}
+            entry["int16_path"] = {
+                "winner": "decomposition onto four int8 MFMA products" if best != 7 else "vector ALU (v_dot2c_i32_i16)",
+                "best_mfma_decomposition_us": round(min(mfma.values()), 2) if mfma else None,
+                "vector_alu_dot2_us": round(allv[7], 2) if 7 in allv else None}
+        tuned[f"i{bits} {M_}x{N_}x{K_}"] = entry
+        del ws_
+
+    result = {}
+    extras = {}
+    rooflines = {}
+
+    # ------------------------------------------------- FFN blocks (configs 2 and 4)
     class FFN:
         def __init__(self, c, bits):
             self.bits = bits
@@ -169,7 +238,6 @@ def main():
             self.s1 = torch.empty(1, dtype=torch.float32, device=dev)
             self.s2 = torch.empty(1, dtype=torch.float32, device=dev)
             self.hmax = torch.zeros(1, dtype=torch.float32, device=dev)
-            # activations live in the packed (fragment-order) layout the product kernels stream
             self.q1 = torch.empty(mq.mq_packed_bytes(bits, M, d), dtype=torch.uint8, device=dev)
             self.q2 = torch.empty(mq.mq_packed_bytes(bits, M, f), dtype=torch.uint8, device=dev)
             self.H = torch.empty((M, f), dtype=torch.float32, device=dev)
@@ -178,22 +246,21 @@ def main():
             self.ws_bytes = mq.mq_ffn_ws_bytes(M, d, f) if bits == 8 else mq.mq_ffn_i16_ws_bytes(M, d, f)
             self.ws = torch.empty(max(self.ws_bytes, QWS), dtype=torch.uint8, device=dev)
             if bits == 8:
-                # the timed block runs on a workspace of its own, prepared once (agreement words zeroed) and left
-                # prepared by every call: nothing else may write to it
-                self.ws_ffn = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
-                mq.mq_ffn_ws_prepare(self.ws_ffn, self.ws_bytes, M, d, f)
+                mq.mq_ffn_ws_prepare(self.ws, self.ws_bytes, M, d, f)
             self.part_bytes = mq.mq_gemm_amax_ws_bytes(M, f)
-            self.part = torch.empty(self.part_bytes, dtype=torch.uint8, device=dev)
+            self.part = torch.empty(max(self.part_bytes, QWS), dtype=torch.uint8, device=dev)
 
-        # the individual launches, so each can be timed alone
-        def k_absmax(self):
-            mq.mq_absmax_f32(self.A, self.A.numel(), self.s1)
+        def block(self):
+            if self.bits == 16:
+                mq.mq_ffn_i16_f32(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
+                                  self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws, self.ws_bytes)
+            else:
+                mq.mq_ffn_i8_f32_prepared(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
+                                          self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws, self.ws_bytes)
 
-        def k_scale1(self):
-            mq.mq_scale_from_amax(self.s1, self.bits, self.s1)
-
+        # the launches of the call-by-call chain, so that each can be timed alone
         def k_quant1(self):
-            mq.mq_quantize_pack_f32(self.A, self.M, self.d, self.bits, self.s1, self.q1)
+            mq.mq_quantize_absmax_pack_f32(self.A, self.M, self.d, self.bits, self.q1, self.s1, self.part, QWS)
 
         def k_gemm1(self):
             mq.mq_gemm_dequant_packed(self.q1, self.p1.packed, self.bits, self.M, self.f, self.d, self.s1,
@@ -209,22 +276,7 @@ def main():
             mq.mq_gemm_dequant_packed(self.q2, self.p2.packed, self.bits, self.M, self.d, self.f, self.s2,
                                       self.p2.scale, self.b2, False, self.Y, None)
 
-        def fused_step(self):
-            if self.bits == 16:
-                mq.mq_ffn_i16_f32(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
-                                  self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws, self.ws_bytes)
-                return
-            mq.mq_ffn_i8_f32_prepared(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
-                                      self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws_ffn, self.ws_bytes)
-
-        def plain_step(self):
-            # the entry point that takes any workspace: one more launch, which zeroes the agreement words
-            mq.mq_ffn_i8_f32(self.A, self.M, self.d, self.f, self.p1.packed, self.p1.scale, self.b1,
-                             self.p2.packed, self.p2.scale, self.b2, self.Y, self.ws_ffn, self.ws_bytes)
-
-        def step(self):
-            self.k_absmax()
-            self.k_scale1()
+        def chain(self):
             self.k_quant1()
             self.hmax.zero_()
             self.k_gemm1()
@@ -232,129 +284,148 @@ def main():
             self.k_quant2()
             self.k_gemm2()
 
-        # building blocks of the fused step, for per-kernel timing
-        def k_absmax_quant1(self):
-            mq.mq_quantize_absmax_pack_f32(self.A, self.M, self.d, self.bits, self.q1, self.s1, self.ws, QWS)
-
-        def k_gemm1_amax(self):
-            mq.mq_gemm_amax_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1, self.p1.scale,
-                                   self.b1, True, self.part, self.part_bytes)
-
-        def k_gemm1_requant(self):
-            mq.mq_gemm_requant_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1, self.p1.scale,
-                                      self.b1, True, self.part, self.part_bytes, self.s2, self.q2)
-
-        def k_gemm1_single(self):
-            mq.mq_gemm_requant_single_packed(self.q1, self.p1.packed, self.M, self.f, self.d, self.s1,
-                                             self.p1.scale, self.b1, True, self.part, self.part_bytes,
-                                             self.s2, self.q2)
-
-        def k_clear(self):
-            self.part[:8].zero_()       # stands in for the 1-block clear launch inside k_gemm1_single
-
-        def kernel_table(self, fused):
-            """name -> (callable, algorithmic HBM bytes, integer ops issued on the matrix cores)."""
-            M, d, f, e = self.M, self.d, self.f, self.bits // 8
-            mm = 2 * M * d * f * (4 if self.bits == 16 else 1)       # int16 = four int8 products
-            if fused:
-                return {
-                    "absmax+quant_int(A) [2 launches]": (self.k_absmax_quant1, 2 * 4 * M * d + e * M * d, 0),
-                    "gemm1 single pass: bias+relu -> max|H| -> quant_int(H)":
-                        (self.k_gemm1_single, e * M * d + e * d * f + e * M * f, mm),
-                    "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, mm),
-                    # the two-pass form of gemm1, used when the result has more tiles than the chip holds
-                    "(two-pass) gemm1 pass 1: bias+relu -> max|H|": (self.k_gemm1_amax, e * M * d + e * d * f, mm),
-                    "(two-pass) gemm1 pass 2: bias+relu -> quant_int(H)":
-                        (self.k_gemm1_requant, e * M * d + e * d * f + e * M * f, mm),
-                }
-            return {
-                "absmax(A)": (self.k_absmax, 4 * M * d, 0),
-                "quant_int(A)": (self.k_quant1, 4 * M * d + e * M * d, 0),
-                "gemm1+bias+relu+amax": (self.k_gemm1, e * M * d + e * d * f + 4 * M * f, mm),
-                "quant_int(H)": (self.k_quant2, 4 * M * f + e * M * f, 0),
-                "gemm2+bias": (self.k_gemm2, e * M * f + e * d * f + 4 * M * d, mm),
-            }
-
-    def run_ffn(c, bits, steps, warmup, fused):
-        w = FFN(c, bits)
-        step = w.fused_step if fused else w.step
-        step()
+    # ----------------------------------------------------------------- config 4 (headline)
+    w4 = None
+    if want("config4"):
+        autotune(16, 8192, 4096, 1024)
+        autotune(16, 8192, 1024, 4096)
+        c4 = workloads.config4()
+        w4 = FFN(c4, 16)
+        w4.block()
         torch.cuda.synchronize()
-        us = time_steps(step, steps, warmup)
-        if fused:
-            w.step()            # leaves s2 / q2 of the unfused chain in place for the gemm2 timing
-        per_kernel = {}
-        for kname, (fn, nbytes, mops) in w.kernel_table(fused and bits == 8).items():
-            kus = time_kernel(fn)
-            if fn == w.k_gemm1_single:
-                # the stand-alone entry point spends one extra tiny launch on clearing its two counters (inside
-                # the block that is the first kernel's job); its share is measured the same way and taken off
-                kus -= time_kernel(w.k_clear)
-            per_kernel[kname] = {"us": round(kus, 2), "alg_bytes": nbytes, "GBps": round(nbytes / kus / 1e3, 1),
-                                 "mfma_TOPS": round(mops / kus / 1e6, 1)}
-        return w, us, per_kernel
+        us4, us4_med = time_steps(w4.block, args.steps, args.warmup)
+        w4.chain()                       # leaves q1 / s1 / H / q2 / s2 in place for the single-kernel timings
+        M, d, f = w4.M, w4.d, w4.f
+        mm = 2 * M * d * f
+        k4 = {}
+        for name, fn, nbytes, useful in (
+                ("config4.absmax+quant_int(A)", w4.k_quant1, 2 * 4 * M * d + 2 * M * d, 0),
+                ("config4.gemm1+bias+relu+max|H| (fp32 H)", w4.k_gemm1, 2 * M * d + 2 * d * f + 4 * M * f, mm),
+                ("config4.quant_int(H)", w4.k_quant2, 4 * M * f + 2 * M * f, 0),
+                ("config4.gemm2+bias", w4.k_gemm2, 2 * M * f + 2 * d * f + 4 * M * d, mm)):
+            mean_us, med_us = time_kernel(fn, reps=5)
+            k4[name] = roof(name, med_us, nbytes, 4 * useful, useful)
+            k4[name]["us_mean"] = round(mean_us, 2)
+        dom4 = max((k for k in k4 if "gemm" in k), key=lambda k: k4[k]["us"])
+        rooflines.update(k4)
+        # the paper's 16-bit scheme (Section 4.2): every multiplier 2^10, no abs-max, the first product writes the second
+        # one's packed 16-bit input from its epilogue -- H never exists as floats, and no 32-bit sum wraps
+        sc16 = torch.full((1,), 1024.0, dtype=torch.float32, device=dev)
+        p1x = mq.prepare_weight(to_dev(c4["W1t"]), 16, scale=sc16)
+        p2x = mq.prepare_weight(to_dev(c4["W2t"]), 16, scale=sc16)
+        nbx = mq.mq_ffn_i16_fixed_ws_bytes(M, d, f)
+        wsx = torch.empty(nbx, dtype=torch.uint8, device=dev)
 
-    # Section 4.4 in miniature: time the tile variants once per product shape and freeze the fastest
-    tuned = {}
+        def fixed16_block():
+            mq.mq_ffn_i16_fixed_f32(w4.A, M, d, f, sc16, p1x.packed, sc16, w4.b1, sc16, p2x.packed, sc16, w4.b2, w4.Y,
+                                    wsx, nbx)
 
-    def autotune(bits, M_, N_, K_):
-        if args.no_autotune:
-            return
-        nb_ = mq.mq_autotune_ws_bytes(bits, M_, N_, K_)
-        ws_ = torch.empty(nb_, dtype=torch.uint8, device=dev)
-        best, us_ = mq.mq_autotune_gemm(bits, M_, N_, K_, 20, ws_, nb_)
-        tuned[f"i{bits} {M_}x{N_}x{K_}"] = {"variant": best, "us": round(us_, 2)}
-        del ws_
+        fixed16_block()
+        usf16, usf16_med = time_steps(fixed16_block, args.steps, args.warmup)
+        mq.mq_quantize_pack_f32(w4.A, M, d, 16, sc16, w4.q1)
+        mean_us, med_us = time_kernel(lambda: mq.mq_gemm_requant_fixed_packed_i16(
+            w4.q1, p1x.packed, M, f, d, sc16, sc16, w4.b1, True, sc16, w4.q2), reps=5)
+        name = "config4.gemm1+bias+relu+quant_int(H) (fixed multiplier, packed int16 H) [2 launches]"
+        rooflines[name] = roof(name, med_us, 2 * M * d + 2 * d * f + 2 * M * f, 4 * mm, mm)
+        result.update({
+            "metric": "int GEMM TOPS (useful 2MNK ops of the FFN block / step time); beside it % of int8 MFMA peak",
+            "value": round(w4.ops / us4 / 1e6, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(us4 / 1e3, 5), "ms_per_step_median": round(us4_med / 1e3, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i16", "data": "synthetic",
+            "config": {"workload": "config 4: transformer-big FFN int16, M=8192: [8192x1024]x[1024x4096]+bias+ReLU, "
+                                   "quant_int, [8192x4096]x[4096x1024]+bias; per-tensor abs-max multipliers 32767/max|x|",
+                       "M": M, "d": d, "ffn": f, "graph": not args.no_graph,
+                       "steps_per_graph": 1 if args.no_graph else STEPS_PER_GRAPH,
+                       "path": "mq_ffn_i16_f32 (5 launches: clear, abs-max + quant_int(A) in one kernel, product 1 with "
+                               "max|H| from its epilogue, quant_int(H), product 2); int16 = four int8 MFMA products on "
+                               "byte planes, recombined exactly mod 2^32"},
+            "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / us4 / 1e6 / PEAK_INT8_TOPS, 2),
+            "pct_int8_mfma_peak_useful": round(100 * w4.ops / us4 / 1e6 / PEAK_INT8_TOPS, 2),
+            "note_on_wrapping": "with 32767/max|x| multipliers part of the 32-bit sums wrap (fractions in "
+                                "cpu_baseline.parity.config4); the paper's fixed 2^10 avoids that: next entry",
+            "paper_scheme_fixed_multiplier_2^10": {
+                "path": "mq_ffn_i16_fixed_f32 (4 launches, H written once as packed int16, no abs-max pass, no wrapped sum)",
+                "us_per_step": round(usf16, 1), "us_per_step_median": round(usf16_med, 1),
+                "TOPS_useful": round(w4.ops / usf16 / 1e6, 1),
+                "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / usf16 / 1e6 / PEAK_INT8_TOPS, 2)},
+            "roofline": dict(k4[dom4]),
+        })
+        del p1x, p2x, wsx
 
     # ----------------------------------------------------------------- config 2
-    autotune(8, 8192, 2048, 512)
-    autotune(8, 8192, 512, 2048)
-    c2 = workloads.config2()
-    w2, us2, pk2 = run_ffn(c2, 8, args.steps, args.warmup, fused=True)
-    tops2 = w2.ops / us2 / 1e6
-    us2_chain = time_steps(w2.step, args.steps, args.warmup)     # the same block call by call, H in fp32
-    us2_plain = time_steps(w2.plain_step, args.steps, args.warmup)
+    if want("config2") and not (args.no_extras and args.only is None):
+        autotune(8, 8192, 2048, 512)
+        autotune(8, 8192, 512, 2048)
+        c2 = workloads.config2()
+        w2 = FFN(c2, 8)
+        w2.block()
+        torch.cuda.synchronize()
+        us2, us2_med = time_steps(w2.block, args.steps, args.warmup)
+        M, d, f = w2.M, w2.d, w2.f
+        # cold: 16 sets of input, output and workspace in rotation (0.87 GB), so that neither the 256 MB last-level
+        # cache nor the L2s can hold what a step touches; the parameters (2 MB) stay
+        sets = []
+        for i in range(16):
+            ws_i = torch.empty(w2.ws_bytes, dtype=torch.uint8, device=dev)
+            mq.mq_ffn_ws_prepare(ws_i, w2.ws_bytes, M, d, f)
+            sets.append((torch.randn(M, d, device=dev), torch.empty((M, d), dtype=torch.float32, device=dev), ws_i))
 
-    # the dominant launch of the timed step: the single-pass first product (the longest one; the second product is
-    # within a few percent of it, so the choice is fixed rather than left to run-to-run noise), else the longest
-    single = [k for k in pk2 if k.startswith("gemm1 single pass")]
-    dom = single[0] if single else max((k for k in pk2 if not k.startswith("(two-pass)") and "launches]" not in k),
-                                       key=lambda k: pk2[k]["us"])
-    dk = pk2[dom]
-    hbm_frac = dk["GBps"] / PEAK_HBM_GBS
-    mfma_frac = dk["mfma_TOPS"] / PEAK_INT8_TOPS
-    # the roof that binds this kernel at its algorithmic traffic / op count
-    t_hbm = dk["alg_bytes"] / (PEAK_HBM_GBS * 1e3)
-    t_mfma = (dk["mfma_TOPS"] * dk["us"]) / PEAK_INT8_TOPS
-    if t_hbm >= t_mfma:
-        roofline = {"bound": "hbm", "achieved": dk["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(hbm_frac, 4)}
-    else:
-        roofline = {"bound": "mfma", "achieved": dk["mfma_TOPS"], "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                    "frac": round(mfma_frac, 4)}
-    roofline.update({"kernel": dom, "us": dk["us"], "traffic": MEASURED_TRAFFIC.get(dom)})
+        def cold_round():
+            for A_i, Y_i, ws_i in sets:
+                mq.mq_ffn_i8_f32_prepared(A_i, M, d, f, w2.p1.packed, w2.p1.scale, w2.b1, w2.p2.packed, w2.p2.scale,
+                                          w2.b2, Y_i, ws_i, w2.ws_bytes)
 
-    result = {
-        "metric": "int8 GEMM TOPS (useful 2MNK ops of the FFN block / step time)",
-        "value": round(tops2, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(us2 / 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "i8", "data": "synthetic",
-        "config": {"workload": "transformer-base FFN int8: [8192x512]x[512x2048]+bias+ReLU, requantize, "
-                               "[8192x2048]x[2048x512]+bias; per-tensor abs-max scales",
-                   "M": w2.M, "d": w2.d, "ffn": w2.f, "graph": not args.no_graph,
-                   "steps_per_graph": 1 if args.no_graph else STEPS_PER_GRAPH,
-                   "path": "mq_ffn_i8_f32_prepared (3 launches, H never stored in fp32; the workspace's agreement "
-                           "words are zeroed once by mq_ffn_ws_prepare outside the timed region and left zero by "
-                           "every call)"},
-        "unfused_chain": {"us_per_step": round(us2_chain, 2), "TOPS": round(w2.ops / us2_chain / 1e6, 2),
-                          "what": "abs-max, scale, quant_int, product(+max|H|), scale, quant_int, product as 9 launches, "
-                                  "H stored and re-read in fp32"},
-        "plain_entry": {"us_per_step": round(us2_plain, 2), "TOPS": round(w2.ops / us2_plain / 1e6, 2),
-                        "what": "mq_ffn_i8_f32 on any workspace: 4 launches, the first one zeroes the agreement words"},
-        "pct_int8_mfma_peak": round(100 * tops2 / PEAK_INT8_TOPS, 2),
-        "roofline": roofline,
-        "kernels": pk2,
-    }
+        cold_round()
+        us2c, us2c_med = time_steps(cold_round, max(16, args.steps // 16), 2, per_graph=1)
+        us2c, us2c_med = us2c / 16, us2c_med / 16
+        del sets
+        us2_chain, _ = time_steps(w2.chain, args.steps, args.warmup)
+        w2.chain()
+        mm = 2 * M * d * f
+        k2 = {}
+
+        def k2_gemm1_single():
+            mq.mq_gemm_requant_single_packed(w2.q1, w2.p1.packed, M, f, d, w2.s1, w2.p1.scale, w2.b1, True, w2.part,
+                                             w2.part_bytes, w2.s2, w2.q2)
+
+        for name, fn, nbytes, ops in (
+                ("config2.absmax+quant_int(A) [clear + one kernel]", w2.k_quant1, 4 * M * d + M * d, 0),
+                ("config2.gemm1 single pass: bias+relu -> max|H| -> quant_int(H) [clear + one kernel]", k2_gemm1_single,
+                 M * d + d * f + M * f, mm),
+                ("config2.gemm2+bias", w2.k_gemm2, M * f + d * f + 4 * M * d, mm)):
+            mean_us, med_us = time_kernel(fn)
+            k2[name] = roof(name, med_us, nbytes, ops)
+            k2[name]["us_mean"] = round(mean_us, 2)
+        rooflines.update(k2)
+        # the paper's 8-bit scheme: 127/2 on inputs clipped to [-2, 2], no abs-max anywhere
+        sc = torch.full((1,), 63.5, dtype=torch.float32, device=dev)
+        p1f = mq.prepare_weight(to_dev(c2["W1t"] * np.float32(8)), 8, scale=sc)
+        p2f = mq.prepare_weight(to_dev(c2["W2t"] * np.float32(8)), 8, scale=sc)
+
+        def fixed_step():
+            mq.mq_quantize_pack_f32(w2.A, M, d, 8, sc, w2.q1)
+            mq.mq_gemm_requant_fixed_packed(w2.q1, p1f.packed, M, f, d, sc, p1f.scale, w2.b1, True, sc, w2.q2)
+            mq.mq_gemm_dequant_packed(w2.q2, p2f.packed, 8, M, d, f, sc, p2f.scale, w2.b2, False, w2.Y, None)
+
+        fixed_step()
+        usf, _ = time_steps(fixed_step, args.steps, args.warmup)
+        alg2 = (4 * M * d + M * d) + (M * d + d * f + M * f) + (M * f + d * f + 4 * M * d)
+        extras["ffn_base_int8"] = {
+            "workload": "config 2: transformer-base FFN int8, M=8192: [8192x512]x[512x2048]+bias+ReLU, quant_int, "
+                        "[8192x2048]x[2048x512]+bias; per-tensor abs-max multipliers",
+            "path": "mq_ffn_i8_f32_prepared (3 launches, H never stored as floats)",
+            "us_per_step_warm": round(us2, 2), "us_per_step_warm_median": round(us2_med, 2),
+            "TOPS_warm": round(w2.ops / us2 / 1e6, 1), "pct_int8_mfma_peak_warm": round(100 * w2.ops / us2 / 1e6 / PEAK_INT8_TOPS, 2),
+            "us_per_step_cold": round(us2c, 2), "us_per_step_cold_median": round(us2c_med, 2),
+            "TOPS_cold": round(w2.ops / us2c / 1e6, 1),
+            "GBps_alg_cold": round(alg2 / us2c / 1e3, 1), "pct_hbm_peak_cold": round(100 * alg2 / us2c / 1e3 / PEAK_HBM_GBS, 1),
+            "cold_rotation": "16 sets of input, output and workspace (0.87 GB) in rotation",
+            "call_by_call_chain_us": round(us2_chain, 2), "fixed_multipliers_63.5_us": round(usf, 2),
+            "kernels": {k: {"us": v["us"], "us_mean": v["us_mean"]} for k, v in k2.items()}}
+        if args.only == "config2":
+            result.update({"metric": "int8 GEMM TOPS (config 2 alone)", "value": round(w2.ops / us2 / 1e6, 2), "unit": "TOPS",
+                           "ms_per_step": round(us2 / 1e3, 5)})
+        del w2, p1f, p2f
 
     if args.copy_calibration:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
@@ -364,70 +435,70 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ------------------------------------------------------------------- extras
-    if not args.no_extras:
-        extras = {}
-        # greedy output layer (one decode step, 300 sentences, 36000-word tied embedding)
+    # ----------------------------------------------------------------- config 3
+    if want("config3") and not (args.no_extras and args.only is None):
         c3 = workloads.config3()
         Hd = to_dev(c3["Hd"])
         M, d = Hd.shape
         V = c3["E"].shape[0]
         pe = mq.prepare_weight(to_dev(c3["E"]), 8)
         s = torch.empty(1, dtype=torch.float32, device=dev)
-        q = torch.empty((M, d), dtype=torch.int8, device=dev)
         nws = mq.mq_argmax_ws_bytes(M, V)
         ws = torch.empty(nws, dtype=torch.uint8, device=dev)
         tok = torch.empty(M, dtype=torch.int32, device=dev)
         val = torch.empty(M, dtype=torch.float32, device=dev)
-
         qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
-        qws = torch.empty(QWS, dtype=torch.uint8, device=dev)
-        # the output layer's quantizer runs on a workspace of its own, prepared once (one kernel per call, which
-        # leaves its agreement words zero); the other workloads below use the entry point that takes any workspace
         qws_out = torch.empty(QWS, dtype=torch.uint8, device=dev)
         mq.mq_quantize_absmax_ws_prepare(qws_out, QWS)
+        pes = [pe] + [mq.prepare_weight(torch.randn(V, d, device=dev) * 0.05, 8) for _ in range(15)]
 
-        def out_step():
+        def out_step(p_=pe):
             mq.mq_quantize_absmax_pack_f32_prepared(Hd, M, d, 8, qp, s, qws_out, QWS)
-            mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws)
-
-        out_step()
+            mq.mq_gemm_argmax_packed(qp, p_.packed, M, V, d, s, p_.scale, tok, val, ws, nws)
 
         def warm_round():             # the same 16 steps as the cold round, on one embedding that stays cached
             for _ in range(16):
                 out_step()
 
-        us3 = time_events(graphed(warm_round), max(5, args.steps // 10), 2) / 16
-        us3k = time_kernel(lambda: mq.mq_gemm_argmax_packed(qp, pe.packed, M, V, d, s, pe.scale, tok, val, ws, nws))
-        # cold: 16 distinct embeddings (295 MB) in rotation, so the 256 MB last-level cache cannot hold them
-        pes = [pe] + [mq.prepare_weight(torch.randn(V, d, device=dev) * 0.05, 8) for _ in range(15)]
+        def cold_round3():            # 16 distinct embeddings (295 MB) in rotation: the 256 MB cache cannot hold them
+            for p_ in pes:
+                out_step(p_)
 
-        def cold_round():
-            for q_ in pes:
-                mq.mq_quantize_absmax_pack_f32_prepared(Hd, M, d, 8, qp, s, qws_out, QWS)
-                mq.mq_gemm_argmax_packed(qp, q_.packed, M, V, d, s, q_.scale, tok, val, ws, nws)
+        def cold_kernels():
+            for p_ in pes:
+                mq.mq_gemm_argmax_packed(qp, p_.packed, M, V, d, s, p_.scale, tok, val, ws, nws)
 
-        us3c = time_events(graphed(cold_round), max(5, args.steps // 10), 2) / len(pes)
+        out_step()
+        n3 = max(13, args.steps // 16)
+        us3, us3_med = time_steps(warm_round, n3, 2, per_graph=1)
+        us3c, us3c_med = time_steps(cold_round3, n3, 2, per_graph=1)
+        us3k, us3k_med = time_steps(cold_kernels, n3, 2, per_graph=1)
+        us3, us3_med, us3c, us3c_med, us3k_med = us3 / 16, us3_med / 16, us3c / 16, us3c_med / 16, us3k_med / 16
+        _, usq = time_kernel(lambda: mq.mq_quantize_absmax_pack_f32_prepared(Hd, M, d, 8, qp, s, qws_out, QWS))
         del pes
         alg3 = V * d + 4 * M * d + 8 * M
+        name = "config3.argmax product [stream + reduce, 2 launches], cold"
+        rooflines[name] = roof(name, us3k_med, V * d + M * d + 8 * M, 2 * M * V * d)
         extras["output_layer_argmax"] = {
-            "workload": f"[{M}x{d}] hidden x tied embedding [{V}x{d}] int8, abs-max + quant_int (one kernel on a prepared workspace) + fused arg-max",
-            "us_per_step_warm": round(us3, 2), "tokens_per_s_warm": round(M / us3 * 1e6, 0),
-            "GBps_alg_warm": round(alg3 / us3 / 1e3, 1),
-            "us_per_step_cold": round(us3c, 2), "tokens_per_s_cold": round(M / us3c * 1e6, 0),
+            "workload": f"config 3: [{M}x{d}] hidden x tied embedding [{V}x{d}] int8: abs-max + quant_int (one kernel on a "
+                        "prepared workspace), product with fused arg-max (streaming kernel + reduce kernel): 3 launches",
+            "us_per_step_warm": round(us3, 2), "us_per_step_warm_median": round(us3_med, 2),
+            "tokens_per_s_warm": round(M / us3 * 1e6, 0), "GBps_alg_warm": round(alg3 / us3 / 1e3, 1),
+            "us_per_step_cold": round(us3c, 2), "us_per_step_cold_median": round(us3c_med, 2),
+            "tokens_per_s_cold": round(M / us3c * 1e6, 0),
             "GBps_alg_cold": round(alg3 / us3c / 1e3, 1), "pct_hbm_peak_cold": round(100 * alg3 / us3c / 1e3 / PEAK_HBM_GBS, 1),
-            "TOPS_warm": round(2 * M * V * d / us3 / 1e6, 1), "argmax_product_only_us": round(us3k, 2)}
+            "cold_rotation": "16 embeddings (295 MB) in rotation",
+            "TOPS_warm": round(2 * M * V * d / us3 / 1e6, 1), "quantizer_us": round(usq, 2),
+            "argmax_product_cold_us": round(us3k_med, 2)}
         # short-listed output layer: 100 most frequent ids + 100 candidates per source word of a 384-word batch
         rng = np.random.default_rng(workloads.BASE_SEED + 33)
         sl_host = np.unique(np.concatenate([np.arange(100), rng.integers(0, V, size=384 * 100 // 8)])).astype(np.int32)
         sl = to_dev(sl_host)
-        us3s = time_kernel(lambda: mq.mq_gemm_argmax_shortlist(qp, pe.packed, sl, sl.numel(), M, V, d, s, pe.scale,
-                                                                tok, val, ws, nws))
-        extras["output_layer_shortlist"] = {"shortlist_rows": int(sl.numel()), "argmax_product_only_us": round(us3s, 2)}
-
-        # beam search (Table 2, b = 2 / b = 4): 300 sentences x beam hypotheses, the k = beam best words per row with
-        # log-probabilities (softmax normaliser fused into the streaming kernel)
+        _, us3s = time_kernel(lambda: mq.mq_gemm_argmax_shortlist(qp, pe.packed, sl, sl.numel(), M, V, d, s, pe.scale,
+                                                                  tok, val, ws, nws))
+        extras["output_layer_shortlist"] = {"shortlist_rows": int(sl.numel()), "argmax_product_us": round(us3s, 2)}
         beam_out = {}
+        qws = torch.empty(QWS, dtype=torch.uint8, device=dev)
         for beam in (2, 4):
             rows_b = M * beam
             Hb = torch.randn(rows_b, d, device=dev)
@@ -438,61 +509,18 @@ def main():
             wsb = torch.empty(nwb, dtype=torch.uint8, device=dev)
             tokb = torch.empty((rows_b, beam), dtype=torch.int32, device=dev)
             lpb = torch.empty((rows_b, beam), dtype=torch.float32, device=dev)
-            usb = time_kernel(lambda: mq.mq_gemm_topk_packed(qb, pe.packed, None, 0, rows_b, V, d, sb, pe.scale, beam,
-                                                             tokb, lpb, wsb, nwb))
-            beam_out[f"beam{beam}"] = {"rows": rows_b, "us": round(usb, 2),
-                                       "TOPS": round(2 * rows_b * V * d / usb / 1e6, 1)}
+            _, usb = time_kernel(lambda: mq.mq_gemm_topk_packed(qb, pe.packed, None, 0, rows_b, V, d, sb, pe.scale, beam,
+                                                                tokb, lpb, wsb, nwb))
+            beam_out[f"beam{beam}"] = {"rows": rows_b, "us": round(usb, 2), "TOPS": round(2 * rows_b * V * d / usb / 1e6, 1)}
             del Hb, qb, wsb
         extras["output_layer_beam_topk"] = beam_out
+        if args.only == "config3":
+            result.update({"metric": "greedy output layer tokens/s (config 3 alone, cold)", "value": round(M / us3c * 1e6, 0),
+                           "unit": "tokens/s", "ms_per_step": round(us3c / 1e3, 5)})
 
-        # the same FFN block with the paper's fixed multipliers (127/2 on inputs clipped to [-2, 2]): no abs-max
-        # pass, the intermediate is quantized in the first product's epilogue -> three launches
-        sc = torch.full((1,), 63.5, dtype=torch.float32, device=dev)
-        w2.p1f = mq.prepare_weight(to_dev(c2["W1t"] * np.float32(8)), 8, scale=sc)
-        w2.p2f = mq.prepare_weight(to_dev(c2["W2t"] * np.float32(8)), 8, scale=sc)
-
-        def fixed_step():
-            mq.mq_quantize_pack_f32(w2.A, w2.M, w2.d, 8, sc, w2.q1)
-            mq.mq_gemm_requant_fixed_packed(w2.q1, w2.p1f.packed, w2.M, w2.f, w2.d, sc, w2.p1f.scale, w2.b1, True, sc, w2.q2)
-            mq.mq_gemm_dequant_packed(w2.q2, w2.p2f.packed, 8, w2.M, w2.d, w2.f, sc, w2.p2f.scale, w2.b2, False, w2.Y, None)
-
-        fixed_step()
-        usf = time_steps(fixed_step, args.steps, args.warmup)
-        extras["ffn_base_int8_fixed_multipliers"] = {
-            "what": "same block, multipliers fixed at 63.5 as in the paper (no abs-max), 3 launches",
-            "us_per_step": round(usf, 2), "TOPS": round(w2.ops / usf / 1e6, 1)}
-
-        # int16 Transformer-big FFN
-        autotune(16, 8192, 4096, 1024)
-        autotune(16, 8192, 1024, 4096)
-        c4 = workloads.config4()
-        w4, us4, pk4 = run_ffn(c4, 16, max(10, args.steps // 10), max(3, args.warmup // 5), fused=True)
-        extras["ffn_big_int16"] = {
-            "workload": "[8192x1024]x[1024x4096]+bias+ReLU, requantize, [8192x4096]x[4096x1024]+bias, int16, "
-                        "one mq_ffn_i16_f32 call (5 launches); the kernel table times the call-by-call pieces",
-            "us_per_step": round(us4, 1), "TOPS_useful": round(w4.ops / us4 / 1e6, 1),
-            "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / us4 / 1e6 / PEAK_INT8_TOPS, 2),
-            "kernels": pk4}
-        # the paper's 16-bit scheme (Section 4.2): every tensor times 2^10, no abs-max; the first product writes the
-        # second one's packed 16-bit input from its epilogue, H is never stored in fp32
-        sc16 = torch.full((1,), 1024.0, dtype=torch.float32, device=dev)
-        p1x = mq.prepare_weight(to_dev(c4["W1t"]), 16, scale=sc16)
-        p2x = mq.prepare_weight(to_dev(c4["W2t"]), 16, scale=sc16)
-
-        def fixed16_step():
-            mq.mq_quantize_pack_f32(w4.A, w4.M, w4.d, 16, sc16, w4.q1)
-            mq.mq_gemm_requant_fixed_packed_i16(w4.q1, p1x.packed, w4.M, w4.f, w4.d, sc16, sc16, w4.b1, True, sc16, w4.q2)
-            mq.mq_gemm_dequant_packed(w4.q2, p2x.packed, 16, w4.M, w4.d, w4.f, sc16, sc16, w4.b2, False, w4.Y, None)
-
-        fixed16_step()
-        usf16 = time_steps(fixed16_step, max(10, args.steps // 10), max(3, args.warmup // 5))
-        extras["ffn_big_int16_fixed_multiplier"] = {
-            "what": "same block, every multiplier 2^10 as in the paper (no abs-max, 4 launches, H written as packed int16)",
-            "us_per_step": round(usf16, 1), "TOPS_useful": round(w4.ops / usf16 / 1e6, 1),
-            "pct_int8_mfma_peak_issued": round(100 * 4 * w4.ops / usf16 / 1e6 / PEAK_INT8_TOPS, 2)}
-        del w4, p1x, p2x
-
-        # single int16 product of the 384-word CPU batch (latency case: reported in microseconds)
+    # ----------------------------------------------------------------- config 1
+    if want("config1") and not (args.no_extras and args.only is None):
+        autotune(16, 384, 512, 512)
         c1 = workloads.config1()
         A1 = to_dev(c1["A"])
         p1_ = mq.prepare_weight(to_dev(c1["Wt"]), 16)
@@ -500,102 +528,145 @@ def main():
         q1_ = torch.empty(mq.mq_packed_bytes(16, 384, 512), dtype=torch.uint8, device=dev)
         s1_ = torch.empty(1, dtype=torch.float32, device=dev)
         Y1_ = torch.empty((384, 512), dtype=torch.float32, device=dev)
+        qws1 = torch.empty(QWS, dtype=torch.uint8, device=dev)
+        mq.mq_quantize_absmax_ws_prepare(qws1, QWS)
 
         def c1_step():
-            mq.mq_quantize_absmax_pack_f32(A1, 384, 512, 16, q1_, s1_, qws, QWS)
+            mq.mq_quantize_absmax_pack_f32_prepared(A1, 384, 512, 16, q1_, s1_, qws1, QWS)
             mq.mq_gemm_dequant_packed(q1_, p1_.packed, 16, 384, 512, 512, s1_, p1_.scale, b1_, False, Y1_, None)
 
         c1_step()
-        us1 = time_steps(c1_step, args.steps, args.warmup)
-        extras["single_int16_product_384x512x512"] = {"us_per_call": round(us1, 2), "launches": 3,
-                                                      "TOPS_useful": round(2 * 384 * 512 * 512 / us1 / 1e6, 2)}
+        us1, us1_med = time_steps(c1_step, args.steps, args.warmup)
+        extras["single_int16_product_384x512x512"] = {
+            "workload": "config 1: abs-max + quant_int of [384x512] (one kernel on a prepared workspace), int16 product with "
+                        "a [512x512] parameter, dequantize + bias: 2 launches",
+            "us_per_call": round(us1, 2), "us_per_call_median": round(us1_med, 2), "launches": 2,
+            "TOPS_useful": round(2 * 384 * 512 * 512 / us1 / 1e6, 2)}
+        if args.only == "config1":
+            result.update({"metric": "single int16 product us (config 1 alone)", "value": round(us1, 2), "unit": "us",
+                           "higher_is_better": False})
 
-        # all parameter products of one greedy decode step of the 6-layer base AAN decoder + output layer
+    # ----------------------------------------------------------------- config 5
+    if want("config5") and not (args.no_extras and args.only is None):
+        M, d, V = 300, 512, 36000
         c5 = workloads.config5()
+        s = torch.empty(1, dtype=torch.float32, device=dev)
+        qp = torch.empty(mq.mq_packed_bytes(8, M, d), dtype=torch.uint8, device=dev)
+        qws = torch.empty(QWS, dtype=torch.uint8, device=dev)
+        nws = mq.mq_argmax_ws_bytes(M, V)
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        tok = torch.empty(M, dtype=torch.int32, device=dev)
+        val = torch.empty(M, dtype=torch.float32, device=dev)
         g5 = []
         for g in c5["gemms"]:
-            Ad = to_dev(g["A"])
             N5, K5 = g["Wt"].shape
-            g5.append((Ad, mq.prepare_weight(to_dev(g["Wt"]), 8), to_dev(g["bias"]), bool(g["relu"]), N5, K5,
-                       torch.empty((300, N5), dtype=torch.float32, device=dev)))
-        nlw = max(mq.mq_linear_ws_bytes(8, 300, k_) for _, _, _, _, _, k_, _ in g5)
+            g5.append((g["name"], to_dev(g["A"]), mq.prepare_weight(to_dev(g["Wt"]), 8), to_dev(g["bias"]), bool(g["relu"]),
+                       N5, K5, torch.empty((300, N5), dtype=torch.float32, device=dev)))
+        nlw = max(mq.mq_linear_ws_bytes(8, 300, k_) for *_, k_, _ in g5)
         lws = torch.empty(nlw, dtype=torch.uint8, device=dev)
         Hd5 = to_dev(c5["output"]["Hd"])
         pe5 = mq.prepare_weight(to_dev(c5["output"]["E"]), 8)
 
         def c5_step():
-            for Ad, pw_, b_, relu_, N5, K5, Ybuf in g5:      # abs-max, quant_int, product, bias (+ReLU) per call
+            for _, Ad, pw_, b_, relu_, N5, K5, Ybuf in g5:      # abs-max, quant_int, product, bias (+ReLU) per call
                 mq.mq_linear_f32(Ad, 300, K5, None, pw_.packed, pw_.scale, 8, N5, b_, relu_, Ybuf, None, lws, nlw)
             mq.mq_quantize_absmax_pack_f32(Hd5, M, d, 8, qp, s, qws, QWS)
             mq.mq_gemm_argmax_packed(qp, pe5.packed, M, V, d, s, pe5.scale, tok, val, ws, nws)
 
         c5_step()
-        us5 = time_events(graphed(c5_step), max(10, args.steps // 4), 3)
-        ops5 = sum(2 * 300 * n_ * k_ for _, _, _, _, n_, k_, _ in g5) + 2 * M * V * d
+        n5 = max(20, args.steps // 4)
+        us5, us5_med = time_steps(c5_step, n5, 3, per_graph=1)
+        ops5 = sum(2 * 300 * n_ * k_ for *_, n_, k_, _ in g5) + 2 * M * V * d
+        # per-product breakdown: the seven products of one layer, each with its quantizer, timed alone (warm)
+        per_gemm = {}
+        for name, Ad, pw_, b_, relu_, N5, K5, Ybuf in g5[:7]:
+            _, us_g = time_kernel(lambda: mq.mq_linear_f32(Ad, 300, K5, None, pw_.packed, pw_.scale, 8, N5, b_, relu_, Ybuf,
+                                                           None, lws, nlw))
+            algb = 4 * 300 * K5 + N5 * K5 + 4 * 300 * N5
+            per_gemm[name.split(".")[1] + f" [300x{K5}]x[{K5}x{N5}]"] = {
+                "us": round(us_g, 2), "launches": 2 if K5 <= 1024 else 3, "GBps_alg": round(algb / us_g / 1e3, 1),
+                "hbm_floor_us": round(algb / (PEAK_HBM_GBS * 1e3), 3)}
         extras["aan_decode_step_products"] = {
-            "workload": "42 int8 parameter products of a 6-layer base AAN decoder step (300 sentences) + greedy output layer",
-            "us_per_step": round(us5, 1), "launches": sum(2 if k_ <= 1024 else 3 for _, _, _, _, _, k_, _ in g5) + 4, "tokens_per_s": round(300 / us5 * 1e6, 0),
-            "TOPS_useful": round(ops5 / us5 / 1e6, 1)}
+            "workload": "config 5: the 42 int8 parameter products of a 6-layer base AAN decoder step (300 sentences), each "
+                        "with its own input and quantizer, + greedy output layer; one HIP graph",
+            "us_per_step": round(us5, 1), "us_per_step_median": round(us5_med, 1),
+            "launches": sum(2 if k_ <= 1024 else 3 for *_, k_, _ in g5) + 4, "tokens_per_s": round(300 / us5 * 1e6, 0),
+            "TOPS_useful": round(ops5 / us5 / 1e6, 1), "per_product_of_one_layer": per_gemm}
         del g5
+        # the same decode step with its real dependencies: six chained decoder layers and the greedy output layer, one
+        # HIP graph; the paper's variants of the averaging block (Section 3.2 / Table 2) beside it
+        chained = {}
+        for label, aan_ffn, use_ffn, use_gate in (("ffn2048", 2048, True, True), ("paper_ffn512", 512, True, True),
+                                                  ("minus_ffn", 2048, False, True), ("minus_gate", 2048, True, False)):
+            cc = workloads.config5_chained(aan_ffn=aan_ffn)
+            Lc = []
+            for Pl in cc["layers"]:
+                prods = {n_: (mq.prepare_weight(to_dev(Pl[n_]["Wt"]), 8), to_dev(Pl[n_]["bias"]))
+                         for n_ in ("aan_ffn1", "aan_ffn2", "aan_gate", "ctx_q", "ctx_o", "ffn1", "ffn2")}
+                norms = {n_: (to_dev(Pl[n_]["gamma"]), to_dev(Pl[n_]["beta"])) for n_ in ("ln1", "ln2", "ln3")}
+                Lc.append(mq.aan_layer(prods, norms, 512, 2048, aan_ffn))
+            KVc = [(to_dev(k_), to_dev(v_)) for k_, v_ in cc["KV"]]
+            gpc = [to_dev(g_) for g_ in cc["g_prev"]]
+            gnc = [torch.empty_like(g_) for g_ in gpc]
+            xs = [to_dev(cc["x0"])] + [torch.empty((300, 512), dtype=torch.float32, device=dev) for _ in Lc]
+            nwl = mq.mq_aan_layer_ws_bytes(300, 512, 2048, aan_ffn)
+            wsl = torch.empty(nwl, dtype=torch.uint8, device=dev)
+            pec = mq.prepare_weight(to_dev(cc["E"]), 8)
 
-        # the same decode step with its real dependencies: six chained decoder layers (running average, averaging
-        # block's network and gate, source attention over 25 positions, feed-forward block, layer normalisations)
-        # and the greedy output layer, as one HIP graph
-        cc = workloads.config5_chained()
-        Lc = []
-        for Pl in cc["layers"]:
-            prods = {n_: (mq.prepare_weight(to_dev(Pl[n_]["Wt"]), 8), to_dev(Pl[n_]["bias"]))
-                     for n_ in ("aan_ffn1", "aan_ffn2", "aan_gate", "ctx_q", "ctx_o", "ffn1", "ffn2")}
-            norms = {n_: (to_dev(Pl[n_]["gamma"]), to_dev(Pl[n_]["beta"])) for n_ in ("ln1", "ln2", "ln3")}
-            Lc.append(mq.aan_layer(prods, norms, 512, 2048, 2048))
-        KVc = [(to_dev(k_), to_dev(v_)) for k_, v_ in cc["KV"]]
-        gpc = [to_dev(g_) for g_ in cc["g_prev"]]
-        gnc = [torch.empty_like(g_) for g_ in gpc]
-        xs = [to_dev(cc["x0"])] + [torch.empty((300, 512), dtype=torch.float32, device=dev) for _ in Lc]
-        nwl = mq.mq_aan_layer_ws_bytes(300, 512, 2048, 2048)
-        wsl = torch.empty(nwl, dtype=torch.uint8, device=dev)
-        pec = mq.prepare_weight(to_dev(cc["E"]), 8)
+            def chained_step():
+                for l_, layer_ in enumerate(Lc):
+                    mq.mq_aan_layer_f32(layer_, xs[l_], gpc[l_], cc["t"], KVc[l_][0], KVc[l_][1], 300, 25, cc["heads"],
+                                        use_ffn, use_gate, 1e-6, xs[l_ + 1], gnc[l_], wsl, nwl)
+                mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, QWS)
+                mq.mq_gemm_argmax_packed(qp, pec.packed, M, V, d, s, pec.scale, tok, val, ws, nws)
 
-        def chained_step():
-            for l_, layer_ in enumerate(Lc):
-                mq.mq_aan_layer_f32(layer_, xs[l_], gpc[l_], cc["t"], KVc[l_][0], KVc[l_][1], 300, 25, cc["heads"], True,
-                                    True, 1e-6, xs[l_ + 1], gnc[l_], wsl, nwl)
-            mq.mq_quantize_absmax_pack_f32(xs[-1], M, d, 8, qp, s, qws, QWS)
-            mq.mq_gemm_argmax_packed(qp, pec.packed, M, V, d, s, pec.scale, tok, val, ws, nws)
+            chained_step()
+            usc, usc_med = time_steps(chained_step, n5, 3, per_graph=1)
+            per_layer = 14 - (0 if use_ffn else 3) - (0 if use_gate else 1)
+            chained[label] = {"us_per_step": round(usc, 1), "us_per_step_median": round(usc_med, 1),
+                              "launches": 6 * per_layer + 4, "tokens_per_s": round(300 / usc * 1e6, 0)}
+            del Lc, KVc, wsl, pec
+        extras["aan_decode_step_chained"] = dict(
+            chained["ffn2048"],
+            workload="config 5 with its real dependencies: one greedy decode step of the 6-layer base AAN decoder for 300 "
+                     "sentences at position 20 (running average, averaging network 512-2048-512, gate, source attention "
+                     "over 25 positions x 8 heads, FFN, layer normalisations) and the greedy output layer, one HIP graph",
+            variants={"averaging network 512-512-512 (the paper's choice, Section 3.2)": chained["paper_ffn512"],
+                      "-ffn (Table 2)": chained["minus_ffn"], "-gate (Table 2)": chained["minus_gate"]})
+        if args.only == "config5":
+            result.update({"metric": "decode step us (config 5 chained, alone)", "value": chained["ffn2048"]["us_per_step"],
+                           "unit": "us", "higher_is_better": False})
 
-        chained_step()
-        usc = time_events(graphed(chained_step), max(10, args.steps // 4), 3)
-        extras["aan_decode_step_chained"] = {
-            "workload": "one greedy decode step of the 6-layer base AAN decoder for 300 sentences at position 20: "
-                        "42 int8 products with their float glue (running average, gate, source attention over 25 "
-                        "positions x 8 heads, layer normalisations) and the greedy output layer, one HIP graph",
-            "us_per_step": round(usc, 1), "launches": 6 * 14 + 4, "tokens_per_s": round(300 / usc * 1e6, 0)}
-        del Lc, KVc, wsl
+    for k, v in (("n_gpus", 1), ("steps", args.steps), ("warmup", args.warmup), ("higher_is_better", True),
+                 ("scaling", "weak"), ("vs_baseline", None), ("data", "synthetic"), ("dtype", "i8"),
+                 ("config", {"workload": args.only or "config 4"})):
+        result.setdefault(k, v)
+    if extras:
         result["extras"] = extras
+    if rooflines:
+        result["rooflines"] = rooflines
     if tuned:
         result["autotuned"] = tuned
 
     # ------------------------------------------------------------- CPU baseline
-    if not args.no_cpu:
+    if not args.no_cpu and args.only is None and w4 is not None:
         import oracle
-        rows = min(args.cpu_rows, c2["A"].shape[0])
-        A = c2["A"][:rows]
-        qW1, sW1 = oracle.quant_int_absmax(c2["W1t"], 8)      # memoized, not timed
-        qW2, sW2 = oracle.quant_int_absmax(c2["W2t"], 8)
+        c4 = workloads.config4()
+        qW1, sW1 = oracle.quant_int_absmax(c4["W1t"], 16)      # memoized, not timed
+        qW2, sW2 = oracle.quant_int_absmax(c4["W2t"], 16)
         t0 = time.perf_counter()
-        qA, sA = oracle.quant_int_absmax(A, 8)
-        Hh = oracle.dequant_bias(oracle.dot_int(qA, qW1), sA, sW1, c2["b1"], True)
-        qH, sH = oracle.quant_int_absmax(Hh, 8)
-        oracle.dequant_bias(oracle.dot_int(qH, qW2), sH, sW2, c2["b2"], False)
+        qA, sA = oracle.quant_int_absmax(c4["A"], 16)
+        Hh = oracle.dequant_bias(oracle.dot_int(qA, qW1), sA, sW1, c4["b1"], True)
+        qH, sH = oracle.quant_int_absmax(Hh, 16)
+        oracle.dequant_bias(oracle.dot_int(qH, qW2), sH, sW2, c4["b2"], False)
         dt = time.perf_counter() - t0
-        ops = 2 * (2 * rows * w2.d * w2.f)
-        result["cpu_baseline"] = {"value": round(ops / dt / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
+        result["cpu_baseline"] = {"value": round(w4.ops / dt / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
                                   "kind": "oracle", "seconds": round(dt, 2),
-                                  "sample": f"first {rows} of {w2.M} token rows of the same FFN workload, "
-                                            "weights pre-quantized (memoized)"}
-        # the latency-bound configs on the oracle, all host threads and one thread (seconds per call)
+                                  "sample": f"all {w4.M} token rows of the same int16 FFN workload (config 4), weights "
+                                            "pre-quantized (memoized)"}
+        del qA, Hh, qH
         nthr = oracle.num_threads()
-        c1o, c3o = workloads.config1(), workloads.config3()
+        c1o, c2o, c3o = workloads.config1(), workloads.config2(), workloads.config3()
         side = {}
         for label, n_ in (("all_threads", nthr), ("one_thread", 1)):
             oracle.set_num_threads(n_)
@@ -606,7 +677,14 @@ def main():
             t2 = time.perf_counter()
             side[label] = {"config1_int16_product_s": round(t1 - t0, 4), "config3_output_layer_s": round(t2 - t1, 3)}
         oracle.set_num_threads(nthr)
+        t0 = time.perf_counter()
+        o1 = oracle.linear(c2o["A"], c2o["W1t"], 8, c2o["b1"], True)
+        oracle.linear(o1["Y"], c2o["W2t"], 8, c2o["b2"], False)
+        side["all_threads"]["config2_int8_ffn_block_s"] = round(time.perf_counter() - t0, 3)
         result["cpu_baseline"]["other_configs"] = side
+        result["cpu_baseline"]["paper_context"] = ("the paper's own CPU figures are whole-translation seconds on a Xeon "
+                                                   "Platinum 8175M (AWS m5.large), Table 3: 273.2 s for base-AAN int16, "
+                                                   "1169.9 s for big int8; no kernel-level number is published")
         if not args.no_parity:
             result["cpu_baseline"]["parity"] = parity_report(mq, torch, dev, to_dev, oracle)
     print(json.dumps(result))
@@ -615,7 +693,6 @@ def main():
 def parity_report(mq, torch, dev, to_dev, oracle):
     """Per benchmark config: does the GPU path reproduce the oracle (quantized tensors, 32-bit sums, float outputs,
     tokens), how many 32-bit sums wrapped, which seed.  Part of the CPU leg: the oracle recomputes everything."""
-    import numpy as np
     import workloads
     QT = {8: torch.int8, 16: torch.int16}
     qws = torch.empty(mq.mq_quantize_absmax_ws_bytes(), dtype=torch.uint8, device=dev)
@@ -655,8 +732,44 @@ def parity_report(mq, torch, dev, to_dev, oracle):
     report["config1"] = dict(r, seed=workloads.BASE_SEED + 1)
     for name, cfg, bits in (("config2", workloads.config2(), 8), ("config4", workloads.config4(), 16)):
         r1, H = check_product(cfg["A"], cfg["W1t"], cfg["b1"], bits, True)
-        r2, _ = check_product(H, cfg["W2t"], cfg["b2"], bits, False)
+        r2, Yo = check_product(H, cfg["W2t"], cfg["b2"], bits, False)
         report[name] = dict(merge([r1, r2]), seed=workloads.BASE_SEED + int(name[-1]))
+        # the one-call block the benchmark times, against the oracle's output of the whole chain
+        M, d = cfg["A"].shape
+        f = cfg["W1t"].shape[0]
+        p1, p2 = mq.prepare_weight(to_dev(cfg["W1t"]), bits), mq.prepare_weight(to_dev(cfg["W2t"]), bits)
+        Y = torch.empty((M, d), dtype=torch.float32, device=dev)
+        if bits == 8:
+            nb = mq.mq_ffn_ws_bytes(M, d, f)
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+            mq.mq_ffn_ws_prepare(ws, nb, M, d, f)
+            mq.mq_ffn_i8_f32_prepared(to_dev(cfg["A"]), M, d, f, p1.packed, p1.scale, to_dev(cfg["b1"]), p2.packed, p2.scale,
+                                      to_dev(cfg["b2"]), Y, ws, nb)
+        else:
+            nb = mq.mq_ffn_i16_ws_bytes(M, d, f)
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+            mq.mq_ffn_i16_f32(to_dev(cfg["A"]), M, d, f, p1.packed, p1.scale, to_dev(cfg["b1"]), p2.packed, p2.scale,
+                              to_dev(cfg["b2"]), Y, ws, nb)
+        report[name]["one_call_block_out"] = bool(np.array_equal(Y.cpu().numpy(), Yo))
+        del ws, Y, p1, p2
+    # config 4 with the paper's fixed multiplier: no sum wraps
+    cfg = workloads.config4()
+    S = np.float32(1024.0)
+    o1 = oracle.linear(cfg["A"], cfg["W1t"], 16, cfg["b1"], True, sA=S, sW=S)
+    o2 = oracle.linear(o1["Y"], cfg["W2t"], 16, cfg["b2"], False, sA=S, sW=S)
+    M, d = cfg["A"].shape
+    f = cfg["W1t"].shape[0]
+    sc = torch.full((1,), 1024.0, dtype=torch.float32, device=dev)
+    p1, p2 = mq.prepare_weight(to_dev(cfg["W1t"]), 16, scale=sc), mq.prepare_weight(to_dev(cfg["W2t"]), 16, scale=sc)
+    nb = mq.mq_ffn_i16_fixed_ws_bytes(M, d, f)
+    ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+    Y = torch.empty((M, d), dtype=torch.float32, device=dev)
+    mq.mq_ffn_i16_fixed_f32(to_dev(cfg["A"]), M, d, f, sc, p1.packed, sc, to_dev(cfg["b1"]), sc, p2.packed, sc,
+                            to_dev(cfg["b2"]), Y, ws, nb)
+    report["config4_fixed_multiplier_2^10"] = {"out": bool(np.array_equal(Y.cpu().numpy(), o2["Y"])),
+                                               "overflow_count": [int(o1["overflow_count"]), int(o2["overflow_count"])],
+                                               "seed": workloads.BASE_SEED + 4}
+    del ws, Y, p1, p2, o1, o2
     c = workloads.config3()
     o = oracle.greedy_output_layer(c["Hd"], c["E"])
     M, d = c["Hd"].shape

@@ -762,7 +762,8 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
   float* part = reinterpret_cast<float*>(base + L.off_part);
   float* sA = reinterpret_cast<float*>(base + L.off_scal);
   float* sH = sA + 1;
-  float* hmax = sA + 2;                       // max|H|, raised by the first product's epilogue
+  float* hmax = sA + 2;                       // max|H|: kHmaxSlots words raised by the first product's workgroups
+  constexpr unsigned kHmaxSlots = 32;
   uint8_t* qA = base + L.off_qA;
   float* H = reinterpret_cast<float*>(base + L.off_H);
   uint8_t* qH = base + L.off_qH;
@@ -779,17 +780,18 @@ int mq_ffn_i16_f32(const float* A, size_t M, size_t d, size_t f, const void* pac
     rc = launch_absmax_quantize_pack_fused(A, M, d, 16, bar, sA, qA, s);
   }
   if (rc == MQ_ERR_UNSUPPORTED)
-    rc = launch_absmax_quantize_pack(A, M, d, 16, part, sA, qA, s, reinterpret_cast<unsigned*>(hmax), 1);
+    rc = launch_absmax_quantize_pack(A, M, d, 16, part, sA, qA, s, reinterpret_cast<unsigned*>(hmax), kHmaxSlots);
   if (rc != MQ_OK) return rc;
   // a4 + a5: H = relu(A W1 + b1) in binary32, max|H| as a by-product of the epilogue
   GemmArgs g1{};
   g1.qA = qA;
   g1.packedW = packedW1; g1.bits = 16; g1.M = M; g1.N = f; g1.K = d;
-  g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1; g1.Y = H; g1.out_amax = hmax;
+  g1.sA = sA; g1.sW = sW1; g1.bias = b1; g1.relu = 1; g1.Y = H; g1.out_amax = hmax; g1.amax_slots = kHmaxSlots;
   rc = launch_gemm_packed(g1, kEpiDequant, s);
   if (rc != MQ_OK) return rc;
-  // a1 + a2 on H: the multiplier comes from the one maximum already there
-  rc = launch_quantize_pack_partials(H, M, f, 16, hmax, 1, sH, qH, s);
+  // a1 + a2 on H: the multiplier comes from the maxima already there (kernels that do not know about the slots
+  // raise the first word only; the others then stay zero)
+  rc = launch_quantize_pack_partials(H, M, f, 16, hmax, kHmaxSlots, sH, qH, s);
   if (rc != MQ_OK) return rc;
   GemmArgs g2{};
   g2.qA = qH;

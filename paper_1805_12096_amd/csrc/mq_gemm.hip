@@ -309,7 +309,7 @@ int launch_one(const Params& p, dim3 grid, hipStream_t s) {
 
 template <int BITS, int BM, int BN, int WM, int WN, int EPI>
 int launch_tiles(const GemmArgs& a, hipStream_t s) {
-  Params p;
+  Params p{};
   p.qA = static_cast<const uint8_t*>(a.qA);
   p.rowsumA = a.rowsumA;
   p.packedW = static_cast<const uint8_t*>(a.packedW);

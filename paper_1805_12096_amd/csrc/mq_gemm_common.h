@@ -33,6 +33,7 @@ struct Params {
   unsigned long long barrier_ticks;   // longest wait there, in ticks of the 100 MHz wall clock
   unsigned* clear_words;    // single-pass epilogue: nclear words that workgroup 0 zeroes at its start (or null)
   unsigned nclear;
+  unsigned amax_slots;      // out_amax is that many words, workgroup b raises word b % amax_slots (0 or 1: one word)
 };
 
 __device__ __forceinline__ v4i as_v4i(u4 v) { return __builtin_bit_cast(v4i, v); }
@@ -154,7 +155,9 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
       float m = wave_amax[0];
 #pragma unroll
       for (int w = 1; w < NWAVES; ++w) m = fmaxf(m, wave_amax[w]);
-      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax);
+      // same-address atomics are served one after the other (about 12 ns each): a thousand workgroups on one word
+      // cost 12 us, on 32 words next to nothing
+      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax) + (p.amax_slots > 1 ? blockIdx.x % p.amax_slots : 0);
       const unsigned bits = __float_as_uint(m);
       if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
     }

@@ -744,6 +744,7 @@ int launch_pp(const GemmArgs& a, hipStream_t s) {
   p.tiles_m = (unsigned)tiles_m;
   p.tiles_n = (unsigned)tiles_n;
   p.C = a.C; p.sA = a.sA; p.sW = a.sW; p.bias = a.bias; p.relu = a.relu; p.Y = a.Y; p.out_amax = a.out_amax;
+  p.amax_slots = a.amax_slots;
   p.partial = a.partial; p.npartial = a.npartial; p.s_out = a.s_out; p.packed_out = static_cast<uint8_t*>(a.packed_out);
   if (tiles_m * tiles_n > 0x7FFFFFFFull) return MQ_ERR_SHAPE;
   auto kern = k_gemm_pp<BITS, BM, BN, WM, WN, S, EPI, PF>;

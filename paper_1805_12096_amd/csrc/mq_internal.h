@@ -82,6 +82,9 @@ struct GemmArgs {
   // single-pass product only: words (of some OTHER kernel's grid-wide agreement) that workgroup 0 zeroes at its start
   unsigned* clear_words;
   unsigned nclear;
+  // dequantizing epilogue of the packed tiled products: out_amax points to this many words (cleared by the caller),
+  // workgroups spread their atomic maxima over them; the consumer takes the maximum of all.  0 = one word.
+  unsigned amax_slots;
 };
 int launch_gemm(const GemmArgs& a, Epilogue epi, hipStream_t s);
 void set_forced_variant(int v);
