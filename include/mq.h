@@ -103,7 +103,7 @@ int mq_last_hip_error(void);
 /* Tuning knob for measurements in the spirit of the paper's auto-tuner (Section
  * 4.4: alternative implementations are timed per shape and the fastest is
  * kept).  variant 0 (default) lets the library choose the tile configuration of
- * the product kernels from the problem shape; 1..14 (8 bit) or 1..7 (16 bit)
+ * the product kernels from the problem shape; 1..14 (8 bit) or 1..8 (16 bit)
  * force one configuration for every following product of this process (results
  * are identical, only speed changes; a variant that does not exist for the
  * operand width makes the product calls return MQ_ERR_UNSUPPORTED; the fused

@@ -2,6 +2,8 @@
 // parameters, the block-to-tile map and the store epilogues.
 #pragma once
 
+#include <type_traits>
+
 #include "mq_internal.h"
 
 namespace mq {
@@ -62,6 +64,29 @@ __device__ __forceinline__ void tile_coords(unsigned tiles_m, unsigned tiles_n, 
   tile_n = in_band / rows;
 }
 
+// max |y| over the workgroup's results -> the caller's word: block-wide maximum, then at most one atomic per
+// block; the running maximum only grows, so a block that cannot raise it skips the atomic.  Every thread of the
+// workgroup must call this.
+template <int NWAVES>
+__device__ __forceinline__ void publish_block_amax(const Params& p, float local_amax) {
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  __shared__ float wave_amax[NWAVES];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
+  if (lane == 0) wave_amax[wave] = local_amax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float m = wave_amax[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) m = fmaxf(m, wave_amax[w]);
+    // same-address atomics are served one after the other (about 12 ns each): a thousand workgroups on one word
+    // cost 12 us, on 32 words next to nothing
+    unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax) + (p.amax_slots > 1 ? blockIdx.x % p.amax_slots : 0);
+    const unsigned bits = __float_as_uint(m);
+    if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
+  }
+}
+
 // Raw-sum and dequantizing epilogues for a wave that holds TM x TN result tiles
 // of the 32x32 MFMA with (a = activations, b = parameter): register r of lane l
 // is element (i, j) = (8 (r / 4) + 4 (l / 32) + r % 4, l % 32) of its tile, i
@@ -73,15 +98,20 @@ __device__ __forceinline__ void tile_coords(unsigned tiles_m, unsigned tiles_n, 
 // row_base / col_base: index of rowsum[0] / colsum[0] (a caller that has copied its tile's sums to LDS before its
 // main loop, for the same reason, passes the tile's origin; sums of rows and columns past the end must then be there
 // too, as zeros).
+// u_pre (optional): the dequantization factor 1 / (sA sW), for a caller that runs the epilogue once per tile of several
+// (the two loads here wait for every load the wave has in flight).
+// amax_acc (optional): this thread's running max |y|; with it the epilogue only updates it, and the caller publishes
+// the workgroup's maximum once, after its last tile (publish_block_amax).
 template <int BITS, int TM, int TN, int NACC, int EPI, int NWAVES>
 __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const Params& p, unsigned wave_m0,
                                                unsigned wave_n0, const int32_t* rowsum, const int32_t* colsum,
                                                const float* bias_pre = nullptr, unsigned row_base = 0,
-                                               unsigned col_base = 0) {
-  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+                                               unsigned col_base = 0, const float* u_pre = nullptr,
+                                               float* amax_acc = nullptr) {
+  const int lane = threadIdx.x % 64;
   const int lj = lane % 32, lh = lane / 32;
   float u = 0.f, local_amax = 0.f;
-  if (EPI == kEpiDequant) u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+  if (EPI == kEpiDequant) u = u_pre != nullptr ? *u_pre : __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
   // Addresses split into a wave-uniform part (tile origin, register's row) and a per-lane constant
   // (4 (l / 32) rows down, l % 32 columns right), so that a store needs no per-element arithmetic.
   const size_t lane_off = (size_t)(4 * lh) * p.N + lj;
@@ -106,22 +136,65 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
       local_amax = fmaxf(local_amax, fabsf(y));
     }
   };
-  if (interior) {
+  if (interior && p.N <= (1u << 26)) {
+    // The epilogue is bound by vector instructions (a 256 x 128 tile is 64 results per lane with the matrix cores
+    // idle), so this path keeps them to a minimum per result: two shift-adds and one three-operand add for the
+    // recombination, convert, multiply-add, (maximum for the ReLU,) store.  The tile origin is wave-uniform, so
+    // a row's address is scalar arithmetic and the store takes it with one 32-bit lane offset (four rows down and
+    // 31 columns right fit 32 bits for N up to 2^26); the ReLU is a maximum with zero under a uniform branch (NaN
+    // and -0 come out as 0 either way).
+    const unsigned um0 = __builtin_amdgcn_readfirstlane(wave_m0), un0 = __builtin_amdgcn_readfirstlane(wave_n0);
+    const uint32_t lane_bytes = ((4u * (unsigned)lh) * p.N + (unsigned)lj) * 4u;
+    char* const out = reinterpret_cast<char*>(EPI == kEpiRaw ? static_cast<void*>(p.C) : static_cast<void*>(p.Y)) +
+                      ((size_t)um0 * p.N + un0) * 4;
+    const size_t row_bytes = (size_t)p.N * 4;
+    float bias[TN];
+    unsigned corr[TN];
 #pragma unroll
     for (int nt = 0; nt < TN; ++nt) {
-      const unsigned n = wave_n0 + nt * 32 + lj;
-      float bias = 0.f;
-      unsigned corr_n = 0;
+      const unsigned n = un0 + nt * 32 + lj;
+      bias[nt] = 0.f;
+      corr[nt] = 0;
       if (EPI == kEpiDequant) {
-        if (bias_pre != nullptr) bias = bias_pre[nt];
-        else if (p.bias != nullptr) bias = p.bias[n];
+        if (bias_pre != nullptr) bias[nt] = bias_pre[nt];
+        else if (p.bias != nullptr) bias[nt] = p.bias[n];
       }
-      if (BITS == 16) corr_n = 128u * (unsigned)colsum[n - col_base] - 16384u * p.K;
+      if (BITS == 16) corr[nt] = 128u * (unsigned)colsum[n - col_base] - 16384u * p.K;
+    }
+    auto rows = [&](auto relu_on) {
 #pragma unroll
       for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) element(mt, nt, r, bias, corr_n, wave_m0 + mt * 32 + 8 * (r / 4) + 4 * lh + r % 4);
-    }
+        for (int r = 0; r < 16; ++r) {
+          const int row = mt * 32 + 8 * (r / 4) + r % 4;
+          char* const rowp = out + row * row_bytes;
+          unsigned rs128 = 0;
+          if (BITS == 16) rs128 = 128u * (unsigned)rowsum[um0 + row + 4 * lh - row_base];
+#pragma unroll
+          for (int nt = 0; nt < TN; ++nt) {
+            int v;
+            if constexpr (BITS == 8) {
+              v = acc[mt][nt][0][r];
+            } else {
+              unsigned t;
+              asm("v_lshl_add_u32 %0, %1, 8, %2" : "=v"(t) : "v"(acc[mt][nt][NACC - 2][r]), "v"(acc[mt][nt][NACC - 1][r]));
+              asm("v_lshl_add_u32 %0, %1, 16, %2" : "=v"(t) : "v"(acc[mt][nt][0][r]), "v"(t));
+              v = (int)(t + rs128 + corr[nt]);
+            }
+            char* const dst = rowp + nt * 128 + lane_bytes;
+            if (EPI == kEpiRaw) {
+              *reinterpret_cast<int32_t*>(dst) = v;
+            } else {
+              float y = fmaf((float)v, u, bias[nt]);
+              if (decltype(relu_on)::value) y = __builtin_fmaxf(y, 0.0f);
+              *reinterpret_cast<float*>(dst) = y;
+              local_amax = fmaxf(local_amax, fabsf(y));
+            }
+          }
+        }
+    };
+    if (EPI == kEpiDequant && p.relu) rows(std::true_type{});
+    else rows(std::false_type{});
   } else {
 #pragma unroll
     for (int nt = 0; nt < TN; ++nt) {
@@ -144,23 +217,8 @@ __device__ __forceinline__ void store_epilogue(v16i (&acc)[TM][TN][NACC], const 
     }
   }
   if (EPI == kEpiDequant && p.out_amax != nullptr) {
-    // block-wide maximum, then at most one atomic per block; the running
-    // maximum only grows, so a block that cannot raise it skips the atomic.
-    __shared__ float wave_amax[NWAVES];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) local_amax = fmaxf(local_amax, __shfl_xor(local_amax, off, 64));
-    if (lane == 0) wave_amax[wave] = local_amax;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      float m = wave_amax[0];
-#pragma unroll
-      for (int w = 1; w < NWAVES; ++w) m = fmaxf(m, wave_amax[w]);
-      // same-address atomics are served one after the other (about 12 ns each): a thousand workgroups on one word
-      // cost 12 us, on 32 words next to nothing
-      unsigned* dst = reinterpret_cast<unsigned*>(p.out_amax) + (p.amax_slots > 1 ? blockIdx.x % p.amax_slots : 0);
-      const unsigned bits = __float_as_uint(m);
-      if (bits > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, bits);
-    }
+    if (amax_acc != nullptr) *amax_acc = fmaxf(*amax_acc, local_amax);
+    else publish_block_amax<NWAVES>(p, local_amax);
   }
 }
 

@@ -808,7 +808,7 @@ size_t tiles_of(int variant, size_t M, size_t N) {
 }
 }  // namespace
 
-int packed_variant_count(int bits) { return bits == 8 ? 14 : 7; }
+int packed_variant_count(int bits) { return bits == 8 ? 14 : 8; }
 
 // Upper bound on the partials the amax pass writes for an [M x N] result (any variant).
 size_t gemm_amax_partials(size_t M, size_t N) { return ((M + 127) / 128) * ((N + 63) / 64); }
@@ -921,7 +921,9 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // every compute unit work, smaller tiles for small problems.
     if (a.bits == 16) {
       const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
-      v = a.M <= 512 ? 6 : (t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3));
+      // four or more big tiles per compute unit: the workgroup that walks through them (measured 2 - 3 % ahead of
+      // one workgroup per tile there, level with it below)
+      v = a.M <= 512 ? 6 : (t >= 1024 ? 8 : (t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3)));
     } else {
       // small problems (a decode step's 300 sentences) are latency bound: the split-K kernel (variant 10)
       // fetches all operands of a workgroup in one round trip
@@ -932,6 +934,10 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   }
   if ((a.bits == 8 && v == 10) || (a.bits == 16 && v == 6)) return launch_gemm_small(a, epi, s);
   if (a.bits == 16 && v == 7) return launch_gemm_dot2(a, epi, s);                        // vector ALU instead of matrix cores
+  if (a.bits == 16 && v == 8) {                                                          // one workgroup per CU, tile after tile
+    if (a.K > 64) return launch_gemm_pers16(a, epi, s);
+    v = 4;                                                                               // a single K step: the tile kernel it derives from
+  }
   if (a.bits == 8 && v >= 11 && v <= 13) return launch_gemm_prod(a, epi, v - 11, s);     // loading waves apart
   if (a.bits == 8 && v == 14) return launch_gemm_ks(a, epi, s);                          // K split over two wave groups
   if (a.bits == 8)

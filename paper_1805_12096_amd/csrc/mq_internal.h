@@ -172,6 +172,9 @@ int launch_gemm_prod(const GemmArgs& a, Epilogue epi, int which, hipStream_t s);
 int launch_gemm_ks(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // 16-bit product on the vector ALU (v_dot2c_i32_i16), both operands packed; variant 7 of the packed 16-bit products.
 int launch_gemm_dot2(const GemmArgs& a, Epilogue epi, hipStream_t s);
+// 16-bit product with one workgroup per compute unit that walks through its tiles, loading across tile boundaries
+// (mq_gemm_pers.hip); variant 8 of the packed 16-bit products.  MQ_ERR_UNSUPPORTED for K up to 64 (a single K step).
+int launch_gemm_pers16(const GemmArgs& a, Epilogue epi, hipStream_t s);
 // Auto-tuner table (shape + operand width -> tile variant of the packed kernels); 0 = not tuned.
 int tuned_variant(int bits, size_t M, size_t N, size_t K);
 void set_tuned_variant(int bits, size_t M, size_t N, size_t K, int variant);

@@ -528,7 +528,7 @@ def gpu_dot_int_packed(qA, qB):
     return host(C)
 
 
-PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14], 16: [0, 1, 2, 3, 4, 5, 6, 7]}
+PACKED_VARIANTS = {8: [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14], 16: [0, 1, 2, 3, 4, 5, 6, 7, 8]}
 
 
 @pytest.mark.parametrize("dtype", [np.int8, np.int16])
@@ -590,6 +590,38 @@ def test_int16_vector_alu_product_matches_oracle(M, N, K, relu):
         mq.mq_set_gemm_variant(7)
         assert np.array_equal(gpu_dot_int_packed(qA, qB), oracle.dot_int(qA, qB))
         mq.mq_gemm_dequant_packed(pa, pw.packed, 16, M, N, K, s, pw.scale, dev(p["bias"]), relu, Y, am)
+    finally:
+        mq.mq_set_gemm_variant(0)
+    assert np.array_equal(host(Y), o["Y"])
+    assert host(am)[0] == np.abs(o["Y"]).max()
+
+
+@pytest.mark.parametrize("M,N,K,relu,with_bias", [(4200, 2100, 200, True, True), (4097, 2049, 128, False, False),
+                                                  (8200, 1100, 130, True, True), (300, 140, 1100, False, True),
+                                                  (2100, 4200, 64, True, True)])
+def test_int16_product_walking_through_several_tiles_matches_oracle(M, N, K, relu, with_bias):
+    # variant 8 of the 16-bit packed products: one workgroup per compute unit that takes its tiles one after the other
+    # and loads across tile boundaries.  The first three shapes have more 256 x 128 tiles than the chip has compute
+    # units (289, 289 and 297, ragged in both directions), so workgroups take two tiles, with 4, 2 and 3 K steps per
+    # tile (2 = the ring's look-ahead: every step of a tile already loads the next tile); then the one-tile case, and
+    # a single K step, which the tile kernel takes over.
+    rng = np.random.default_rng(M * 31 + N * 7 + K)
+    qA = rng.integers(-32767, 32768, size=(M, K)).astype(np.int16)
+    qB = rng.integers(-32767, 32768, size=(N, K)).astype(np.int16)
+    qA[0, : min(K, 6)] = -32767
+    qB[0, : min(K, 6)] = -32767
+    qA[-1, -1], qB[-1, -1] = 32767, -32767
+    p = workloads.random_problem(M + N + K + 8, M, N, K)
+    bias = p["bias"] if with_bias else None
+    o = oracle.linear(p["A"], p["Wt"], 16, bias, relu)
+    pw = mq.prepare_weight(dev(p["Wt"]), 16)
+    pa, s = gpu_quantize_pack(p["A"], 16)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    try:
+        mq.mq_set_gemm_variant(8)
+        assert np.array_equal(gpu_dot_int_packed(qA, qB), oracle.dot_int(qA, qB))
+        mq.mq_gemm_dequant_packed(pa, pw.packed, 16, M, N, K, s, pw.scale, dev(bias) if with_bias else None, relu, Y, am)
     finally:
         mq.mq_set_gemm_variant(0)
     assert np.array_equal(host(Y), o["Y"])
