@@ -921,9 +921,9 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     // every compute unit work, smaller tiles for small problems.
     if (a.bits == 16) {
       const size_t t = ((a.M + 255) / 256) * ((a.N + 127) / 128);
-      // four or more big tiles per compute unit: the workgroup that walks through them (measured 2 - 3 % ahead of
-      // one workgroup per tile there, level with it below)
-      v = a.M <= 512 ? 6 : (t >= 1024 ? 8 : (t >= 200 ? 4 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3)));
+      // enough big tiles to fill the chip: the workgroup per compute unit that walks through them (measured 2 - 7 %
+      // ahead of one workgroup per tile, the more the shorter K is)
+      v = a.M <= 512 ? 6 : (t >= 200 ? 8 : (((a.M + 127) / 128) * ((a.N + 127) / 128) >= 128 ? 1 : 3));
     } else {
       // small problems (a decode step's 300 sentences) are latency bound: the split-K kernel (variant 10)
       // fetches all operands of a workgroup in one round trip

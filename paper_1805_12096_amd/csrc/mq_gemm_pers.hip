@@ -47,7 +47,9 @@ __device__ __forceinline__ void tile_of(unsigned t, unsigned tiles_m, unsigned t
   tile_n = in_band / rows;
 }
 
-template <int EPI>
+// MULTI: the grid is smaller than the number of tiles, so workgroups take several; without it (at most one tile per
+// compute unit) the tile-to-tile code drops out at compile time.
+template <int EPI, bool MULTI>
 __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   constexpr int NPL = 2, NACC = 3, TM = kTM, TN = kTN, L = kL, S = kS;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   const unsigned T = p.tiles_m * p.tiles_n, G = gridDim.x;
   const unsigned first = xcd_remap(blockIdx.x, G);
   if (first >= T) return;
-  const unsigned nmine = (T - first + G - 1) / G;        // this workgroup's tiles: first, first + G, ...
+  const unsigned nmine = MULTI ? (T - first + G - 1) / G : 1u;        // this workgroup's tiles: first, first + G, ...
   const int32_t* rs = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
   const int32_t* cs = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
   const unsigned lane16 = (unsigned)lane * 16u;
@@ -151,16 +153,6 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
 
   // ---- the multiplying side ----
   v16i acc[TM][TN][NACC];
-  auto zero_acc = [&]() {
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-      for (int b = 0; b < TN; ++b)
-#pragma unroll
-        for (int c = 0; c < NACC; ++c)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[a][b][c][r] = 0;
-  };
   struct Frags {
     v4i a[TM][NPL];
     v4i b[TN][NPL];
@@ -182,15 +174,18 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   };
   // i-th MFMA of a slice: high x high, high x low, low x high, low x low; the product index is the slowest, so
   // consecutive instructions never accumulate into the same registers
-  auto mfma_one = [&](const Frags& F, int i) {
+  // fresh: the accumulator's first instruction of a tile takes zero instead of the accumulator (of the three sums per
+  // result tile the middle one gets two products per slice: only its first starts from zero)
+  auto mfma_one = [&](const Frags& F, int i, bool fresh) {
     const int pr = i / (TM * TN), mt = (i / TN) % TM, nt = i % TN;
     const int pa = (pr == 0 || pr == 1) ? 0 : 1;
     const int pb = (pr == 0 || pr == 2) ? 0 : 1;
     const int ai = pr == 0 ? 0 : (pr == 3 ? 2 : 1);
-    acc[mt][nt][ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][pa], F.b[nt][pb], acc[mt][nt][ai], 0, 0, 0);
+    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    acc[mt][nt][ai] =
+        __builtin_amdgcn_mfma_i32_32x32x32_i8(F.a[mt][pa], F.b[nt][pb], fresh && pr != 2 ? zero : acc[mt][nt][ai], 0, 0, 0);
   };
 
-  zero_acc();
   set_loader_tile(0);
   dbase = wave * L * kFragBytes;
 #pragma unroll
@@ -210,16 +205,19 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   constexpr int EVERY = SPAN / L;
 #pragma unroll
   for (int r = 0; r < R; ++r) read_one(f, smem + lane16, 0, r);
-  const unsigned GT = nmine * KT;         // this workgroup's K steps, all tiles
-  unsigned slot = 0, kt = 0, co = 0;
-  for (unsigned g = 0; g < GT; ++g) {
+  unsigned slot = 0;
+  // One K step on the stage in `slot`, straight-line code.  FIRST (a tile's first step): the accumulators start from
+  // zero inside their first instructions; clearing 192 registers per lane between tiles would be 0.7 us of vector
+  // instructions with the matrix cores idle.
+  auto step = [&](auto first_c) {
+    constexpr bool FIRST = decltype(first_c)::value;
     const unsigned nslot = slot + 1 == (unsigned)S ? 0u : slot + 1;
     const uint8_t* cur = smem + slot * kStage + lane16;
     const uint8_t* nxt = smem + nslot * kStage + lane16;
     int issued = 0;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
-      mfma_one(f, i);
+      mfma_one(f, i, FIRST);
       if (i % EVERY == EVERY - 1 && issued < L) {
         issue_one(issued);
         ++issued;
@@ -229,7 +227,7 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
     for (int r = 0; r < R; ++r) read_one(f, cur, 1, r);
 #pragma unroll
     for (int i = 0; i < NM - TAIL; ++i) {
-      mfma_one(f, i);
+      mfma_one(f, i, false);
       if ((NM + i) % EVERY == EVERY - 1 && issued < L) {
         issue_one(issued);
         ++issued;
@@ -243,28 +241,27 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
     wait_all_but_one_stage();
     fenced_barrier();
 #pragma unroll
-    for (int i = NM - TAIL; i < NM; ++i) mfma_one(f, i);
+    for (int i = NM - TAIL; i < NM; ++i) mfma_one(f, i, false);
     // the next stage's first fragments, behind the last MFMAs (after the last stage this reads a slot nobody writes
     // any more; the result is unused)
 #pragma unroll
     for (int r = 0; r < R; ++r) read_one(f, nxt, 0, r);
     slot = nslot;
     stage_issued();
-    if (++kt == KT) {
-      // the tile is complete; its successor's first stages are in LDS or on their way
-      unsigned tm, tn;
-      tile_of(first + co * G, p.tiles_m, p.tiles_n, 1024u / kBM, tm, tn);
-      const unsigned m0 = tm * kBM, n0 = tn * kBN, par = co & 1u;
-      float bias_pre[TN];
+  };
+  for (unsigned o = 0; o < nmine; ++o) {
+    step(std::true_type{});
+    for (unsigned kt = 1; kt < KT; ++kt) step(std::false_type{});
+    // the tile is complete; its successor's first stages are in LDS or on their way
+    unsigned tm, tn;
+    tile_of(first + o * G, p.tiles_m, p.tiles_n, 1024u / kBM, tm, tn);
+    const unsigned m0 = tm * kBM, n0 = tn * kBN, par = o & 1u;
+    float bias_pre[TN];
 #pragma unroll
-      for (int nt = 0; nt < TN; ++nt) bias_pre[nt] = p.bias != nullptr ? s_bias[par][(wn * TN + nt) * 32 + lane % 32] : 0.f;
-      store_epilogue<16, TM, TN, NACC, EPI, kNW>(acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, s_rowsum[par], s_colsum[par],
-                                                 bias_pre, m0, n0, &u, &amax_run);
-      zero_acc();
-      kt = 0;
-      ++co;
-      if (co < nmine) stage_sums(co);
-    }
+    for (int nt = 0; nt < TN; ++nt) bias_pre[nt] = p.bias != nullptr ? s_bias[par][(wn * TN + nt) * 32 + lane % 32] : 0.f;
+    store_epilogue<16, TM, TN, NACC, EPI, kNW>(acc, p, m0 + wm * TM * 32, n0 + wn * TN * 32, s_rowsum[par], s_colsum[par],
+                                               bias_pre, m0, n0, &u, &amax_run);
+    if (o + 1 < nmine) stage_sums(o + 1);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the dummy loads of the tail must not outlive the workgroup's LDS
   if (EPI == kEpiDequant && p.out_amax != nullptr) publish_block_amax<kNW>(p, amax_run);
@@ -307,7 +304,9 @@ int launch_gemm_pers16(const GemmArgs& a, Epilogue epi, hipStream_t s) {
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), kPersLds, s, p);
     return check_hip(hipGetLastError());
   };
-  return epi == kEpiRaw ? launch(k_gemm_pers16<kEpiRaw>) : launch(k_gemm_pers16<kEpiDequant>);
+  if (tiles_m * tiles_n > (size_t)grid)
+    return epi == kEpiRaw ? launch(k_gemm_pers16<kEpiRaw, true>) : launch(k_gemm_pers16<kEpiDequant, true>);
+  return epi == kEpiRaw ? launch(k_gemm_pers16<kEpiRaw, false>) : launch(k_gemm_pers16<kEpiDequant, false>);
 }
 
 }  // namespace mq
