@@ -316,8 +316,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restr
   const size_t nwaves = (size_t)gridDim.x * (kThreads / kWave);
   const size_t row_groups = d.Np / 8;
   const size_t per = (d.kfrags + ksplit - 1) / ksplit;   // fragments along K per work item
-  for (size_t item = wave; item < row_groups * ksplit; item += nwaves) {
-    const size_t rg = item / ksplit, part = item % ksplit;
+  // fragments [part * per, ...) of row group rg; returns the lane's share of the rows' sums (16 bit)
+  auto convert = [&](size_t rg, size_t part) -> int {
     const size_t row = rg * 8 + lane / 8;
     const size_t kb_end = (part + 1) * per < d.kfrags ? (part + 1) * per : d.kfrags;
     const size_t nb = row / kFragRows;
@@ -359,12 +359,38 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const float* __restr
         }
       }
     }
-    if (BITS == 16) {  // ksplit is 1 for 16 bit: one wave owns whole rows
+    if (BITS == 16) {
       sum += __shfl_xor(sum, 1, kWave);
       sum += __shfl_xor(sum, 2, kWave);
       sum += __shfl_xor(sum, 4, kWave);
-      if (sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
     }
+    return sum;
+  };
+  if (BITS == 16 && ksplit > 1) {
+    // 16 bit, long rows: the workgroup's waves share a row group, each takes its part of K (four times the loads in
+    // flight of one wave per row group, which leaves a chip with a thousand row groups at four waves per compute
+    // unit), and the rows' sums meet in LDS.  ksplit is the number of waves of the workgroup here.
+    __shared__ int s_part[kThreads / kWave][8];
+    const int w = threadIdx.x / kWave;
+    for (size_t rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
+      const int sum = convert(rg, (size_t)w);
+      if (sub == 0) s_part[w][lane / 8] = sum;
+      __syncthreads();
+      if (w == 0 && sub == 0) {
+        int total = 0;
+#pragma unroll
+        for (int k = 0; k < kThreads / kWave; ++k) total += s_part[k][lane / 8];
+        reinterpret_cast<int32_t*>(packed + d.plane_bytes())[rg * 8 + lane / 8] = total;
+      }
+      __syncthreads();
+    }
+    return;
+  }
+  for (size_t item = wave; item < row_groups * ksplit; item += nwaves) {
+    const size_t rg = item / ksplit, part = item % ksplit;
+    const int sum = convert(rg, part);
+    // 16 bit here: one wave owns whole rows
+    if (BITS == 16 && sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[rg * 8 + lane / 8] = sum;
   }
 }
 
@@ -490,12 +516,15 @@ int launch_quantize_pack(const float* x, size_t rows, size_t cols, int bits, con
                          void* packed, hipStream_t s) {
   const PackedDims d(bits, rows, cols);
   const size_t row_groups = d.Np / 8;
-  // 8-bit: split K so that even a 300-row batch fills the chip; 16-bit keeps rows whole for the row sums
+  // 8-bit: split K so that even a 300-row batch fills the chip; 16-bit: rows of 512 elements or more are shared by the
+  // waves of a workgroup (their sums meet in LDS), shorter ones stay whole
   unsigned ksplit = 1;
   if (bits == 8) {
     while (row_groups * ksplit < 2048 && ksplit * 4 <= d.kfrags) ksplit *= 2;
+  } else if (d.kfrags >= 16) {
+    ksplit = kThreads / kWave;
   }
-  const unsigned grid = grid_for(row_groups * ksplit, kThreads / kWave, 8192);
+  const unsigned grid = bits == 16 && ksplit > 1 ? grid_for(row_groups, 1, 8192) : grid_for(row_groups * ksplit, kThreads / kWave, 8192);
   uint8_t* p = static_cast<uint8_t*>(packed);
   const bool vec = cols % 4 == 0;
   float* none = nullptr;
@@ -532,8 +561,10 @@ int launch_quantize_pack_partials(const float* x, size_t rows, size_t cols, int 
   unsigned ksplit = 1;
   if (bits == 8) {
     while (row_groups * ksplit < 2048 && ksplit * 4 <= d.kfrags) ksplit *= 2;
+  } else if (d.kfrags >= 16) {
+    ksplit = kThreads / kWave;      // the workgroup's waves share a row group
   }
-  const unsigned grid = grid_for(row_groups * ksplit, kThreads / kWave, 8192);
+  const unsigned grid = bits == 16 && ksplit > 1 ? grid_for(row_groups, 1, 8192) : grid_for(row_groups * ksplit, kThreads / kWave, 8192);
   uint8_t* p = static_cast<uint8_t*>(packed);
   const bool vec = cols % 4 == 0;
   if (bits == 8) {
