@@ -467,10 +467,10 @@ __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __res
   if (self_clean && blockIdx.x != 0 && threadIdx.x == 0) retired_before = grid_max_retire(barrier);
   const float lim = BITS == 8 ? 127.0f : 32767.0f;
   const float s = (amax > 0.0f) ? __fdiv_rn(lim, amax) : 1.0f;
+  int sum = 0;
   if (active) {
     const size_t nb = row / kFragRows;
     const int slot = (int)(row % kFragRows) + 32 * (sub / 4);
-    int sum = 0;
 #pragma unroll
     for (int t = 0; t < NI; ++t)
 #pragma unroll
@@ -490,11 +490,24 @@ __global__ __launch_bounds__(512) void k_absmax_quantize_pack(const float* __res
           }
         }
       }
-    if (BITS == 16) {  // ksplit is 1 for 16 bit: one wave owns whole rows
-      sum += __shfl_xor(sum, 1, kWave);
-      sum += __shfl_xor(sum, 2, kWave);
-      sum += __shfl_xor(sum, 4, kWave);
-      if (sub == 0) reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
+  }
+  if (BITS == 16) {
+    sum += __shfl_xor(sum, 1, kWave);
+    sum += __shfl_xor(sum, 2, kWave);
+    sum += __shfl_xor(sum, 4, kWave);
+    if (ksplit > 1) {
+      // the ksplit waves that share a row group sit side by side in the workgroup (ksplit divides its eight waves):
+      // their parts of the rows' sums meet in LDS
+      __shared__ int s_rowpart[kW][8];
+      if (sub == 0) s_rowpart[wave][lane / 8] = sum;
+      __syncthreads();
+      if (active && part == 0 && sub == 0) {
+        int total = 0;
+        for (unsigned j = 0; j < ksplit; ++j) total += s_rowpart[wave + j][lane / 8];
+        reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = total;
+      }
+    } else if (active && sub == 0) {
+      reinterpret_cast<int32_t*>(packed + d.plane_bytes())[row] = sum;
     }
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -622,12 +635,12 @@ int launch_absmax_quantize_pack_fused(const float* x, size_t rows, size_t cols, 
   const size_t row_groups = d.Np / 8;
   const size_t max_waves = (size_t)kBarrierSlots * (512 / kWave);
   if (row_groups > max_waves) return MQ_ERR_UNSUPPORTED;
-  // split K as far as one trip of four fragments per wave allows while the waves still fit (8 bit; 16 bit
-  // keeps rows whole for the row sums)
+  // split K as far as one trip of four fragments per wave allows while the waves still fit; 16 bit: at most over
+  // the eight waves of a workgroup, where the parts of a row's sum meet in LDS
   unsigned ksplit = 1;
-  if (bits == 8) {
-    while (row_groups * ksplit * 2 <= max_waves && (d.kfrags + 2 * ksplit - 1) / (2 * ksplit) >= 4) ksplit *= 2;
-  }
+  while (row_groups * ksplit * 2 <= max_waves && (d.kfrags + 2 * ksplit - 1) / (2 * ksplit) >= 4 &&
+         (bits == 8 || ksplit * 2 <= 512 / kWave))
+    ksplit *= 2;
   const size_t per = (d.kfrags + ksplit - 1) / ksplit;
   if (per > 32) return MQ_ERR_UNSUPPORTED;
   const int ni = per <= 4 ? 1 : per <= 8 ? 2 : per <= 16 ? 4 : 8;
