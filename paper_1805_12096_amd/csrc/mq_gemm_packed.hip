@@ -935,8 +935,8 @@ int launch_gemm_packed(const GemmArgs& a, Epilogue epi, hipStream_t s) {
   if ((a.bits == 8 && v == 10) || (a.bits == 16 && v == 6)) return launch_gemm_small(a, epi, s);
   if (a.bits == 16 && v == 7) return launch_gemm_dot2(a, epi, s);                        // vector ALU instead of matrix cores
   if (a.bits == 16 && v == 8) {                                                          // one workgroup per CU, tile after tile
-    if (a.K > 64) return launch_gemm_pers16(a, epi, s);
-    v = 4;                                                                               // a single K step: the tile kernel it derives from
+    if (a.K > 64 && a.K < ((size_t)1 << 26)) return launch_gemm_pers16(a, epi, s);
+    v = 4;                                                       // a single K step (or an absurdly long K): the tile kernel it derives from
   }
   if (a.bits == 8 && v >= 11 && v <= 13) return launch_gemm_prod(a, epi, v - 11, s);     // loading waves apart
   if (a.bits == 8 && v == 14) return launch_gemm_ks(a, epi, s);                          // K split over two wave groups
