@@ -628,6 +628,39 @@ def test_int16_product_walking_through_several_tiles_matches_oracle(M, N, K, rel
     assert host(am)[0] == np.abs(o["Y"]).max()
 
 
+def _seeded_shapes():
+    rng = np.random.default_rng(2024)
+    out = [(int(rng.integers(1, 1500)), int(rng.integers(1, 1500)), int(rng.integers(1, 700))) for _ in range(6)]
+    out += [(int(rng.integers(3900, 4600)), int(rng.integers(2050, 2300)), int(rng.integers(65, 400))) for _ in range(4)]
+    out += [(int(rng.integers(8100, 8300)), int(rng.integers(2050, 2200)), int(rng.integers(65, 200))) for _ in range(2)]
+    return out
+
+
+@pytest.mark.parametrize("idx,shape", list(enumerate(_seeded_shapes())))
+def test_int16_walking_product_seeded_shapes(idx, shape):
+    # variant 8 on shapes drawn from a seeded generator (ragged in every direction; the last six have more tiles than
+    # compute units), through the library's own quantizer: 32-bit sums, dequantized outputs and max|y| against the oracle
+    M, N, K = shape
+    p = workloads.random_problem(1000 + idx, M, N, K)
+    relu, with_bias = bool(idx % 2), idx % 3 != 0
+    bias = p["bias"] if with_bias else None
+    o = oracle.linear(p["A"], p["Wt"], 16, bias, relu)
+    pw = mq.prepare_weight(dev(p["Wt"]), 16)
+    pa, s = gpu_quantize_pack(p["A"], 16)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    am = torch.zeros(1, dtype=torch.float32, device=DEV)
+    try:
+        mq.mq_set_gemm_variant(8)
+        mq.mq_gemm_i32_packed(pa, pw.packed, 16, M, N, K, C)
+        mq.mq_gemm_dequant_packed(pa, pw.packed, 16, M, N, K, s, pw.scale, dev(bias) if with_bias else None, relu, Y, am)
+    finally:
+        mq.mq_set_gemm_variant(0)
+    assert np.array_equal(host(C), o["acc"])
+    assert np.array_equal(host(Y), o["Y"])
+    assert host(am)[0] == np.abs(o["Y"]).max()
+
+
 def test_gemm_packed_one_hot_layout():
     # one non-zero per operand: checks where the direct-to-LDS copy puts each lane's bytes
     for dtype in (np.int8, np.int16):
@@ -962,7 +995,7 @@ def test_ffn_block_on_a_prepared_workspace_replayed_as_a_graph():
 
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("shape", [(1, 1), (33, 65), (300, 512), (300, 2048), (2000, 1024), (8192, 512), (70, 1030),
-                                   (17000, 96)])
+                                   (17000, 96), (384, 512), (48, 4096), (1000, 700), (8192, 1024)])
 def test_quantize_absmax_pack(bits, shape):
     # Tensors that fit the registers of one resident grid are read once (the last shapes do not fit and take
     # the two-pass form anyway); with the switch off it is always two passes.  Both forms must give the
