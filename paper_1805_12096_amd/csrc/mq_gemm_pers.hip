@@ -5,8 +5,10 @@
 // tile's start (launch, first operands' round trip to memory) or its end.  Here the K steps of all of a workgroup's
 // tiles form one sequence: the loads run S - 1 steps ahead of the matrix instructions across tile boundaries, so the
 // next tile's first stages arrive while the current tile's results are being stored.  A tile's row sums, column sums
-// and biases come in by direct-to-LDS loads at its first K step, into the half of a double buffer the previous tile does
-// not use.  Same operands, same results as every other variant.
+// and biases come in by direct-to-LDS loads issued before its first K step, into the half of a double buffer the
+// previous tile does not use; the accumulators start from zero inside a tile's first matrix instructions instead of
+// being cleared between tiles; max|y| (when asked for) is published once per workgroup, after its last tile.  Same
+// operands, same results as every other variant.
 #include <type_traits>
 
 #include "mq_gemm_common.h"
