@@ -71,8 +71,11 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   const int32_t* rs = reinterpret_cast<const int32_t*>(p.qA + dA.plane_bytes());
   const int32_t* cs = reinterpret_cast<const int32_t*>(p.packedW + dW.plane_bytes());
   const unsigned lane16 = (unsigned)lane * 16u;
-  float u = 0.f, amax_run = 0.f;      // max |y| over all of this thread's results, published once at the end
-  if (EPI == kEpiDequant) u = __fdiv_rn(1.0f, __fmul_rn(*p.sA, *p.sW));
+  float amax_run = 0.f;               // max |y| over all of this thread's results, published once at the end
+  // the two multipliers are asked for now and divided after the first stages are on their way: the wait for them
+  // would otherwise stand between the kernel's start and its first operand loads
+  float s_a = 0.f, s_w = 0.f;
+  if (EPI == kEpiDequant) { s_a = *p.sA; s_w = *p.sW; }
 
   // ---- the loading side: K step lk of this workgroup's lo-th tile goes to ring slot lslot ----
   const uint8_t* sbase[L];      // wave-uniform source of this wave's j-th fragment of K step 0 of the tile being loaded
@@ -200,6 +203,8 @@ __global__ __launch_bounds__(kNW * 64) void k_gemm_pers16(const Params p) {
   // stage 0 has landed once all but the newest L loads have (the sums' load makes that wait for one load more)
   wait_all_but_one_stage();
   fenced_barrier();
+  float u = 0.f;
+  if (EPI == kEpiDequant) u = __fdiv_rn(1.0f, __fmul_rn(s_a, s_w));
 
   Frags f;
   constexpr int TAIL = NM / 2;
