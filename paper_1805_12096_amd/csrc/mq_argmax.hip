@@ -66,6 +66,9 @@ struct ArgmaxParams {
   float2* norm;
   const float* sA;
   const float* sW;
+  // beam search with more rows than one workgroup's registers hold: the grid's y index picks a chunk of chunk_rows
+  // rows out of Mtotal (M, packedA, partial and norm above then describe the whole problem); 0 = M is the chunk
+  unsigned chunk_rows, Mtotal;
 };
 
 // What lane l feeds to the 16x16x64 MFMA for rows 16 u .. 16 u + 15 of a packed
@@ -89,7 +92,17 @@ __device__ __forceinline__ size_t operand16_uniform_offset(const PackedDims& d, 
 // keys instead of one (sorted insertion: BEAM max / min pairs per candidate), and every sentence tile keeps
 // a running (max, sum) of 2^(logit log2 e) so that the k best words come with normalised log-probabilities.
 template <int TPW, bool GATHER, int BEAM = 1>
-__global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p) {
+__global__ __launch_bounds__(kWaves * 64) void k_argmax_stream(const ArgmaxParams p_in) {
+  ArgmaxParams p = p_in;
+  if (BEAM > 1 && p_in.chunk_rows != 0) {
+    // this workgroup's chunk of rows: the keys and normalisers are laid out by row, so a chunk's share starts at its
+    // first row, and so do its packed hidden states (chunks are whole 32-row blocks)
+    const unsigned row0 = blockIdx.y * p_in.chunk_rows;
+    p.M = p_in.Mtotal - row0 < p_in.chunk_rows ? p_in.Mtotal - row0 : p_in.chunk_rows;
+    p.packedA = p_in.packedA + PackedDims(8, p_in.Mtotal, p_in.K).frag_offset(row0 / 32, 0);
+    p.partial = p_in.partial + (size_t)row0 * gridDim.x * BEAM;
+    p.norm = p_in.norm + (size_t)row0 * gridDim.x;
+  }
   constexpr int KG = kKG, S = kStages;
   constexpr int STAGE = KG * kFragBytes;
   static_assert(KG == kWaves, "one direct-to-LDS load per wave and stage");
@@ -534,7 +547,7 @@ __global__ __launch_bounds__(256) void k_topk_reduce(const unsigned long long* _
 }
 
 template <int TPW, bool GATHER, int BEAM = 1>
-int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
+int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s, unsigned ny = 1) {
   constexpr size_t smem = (size_t)(kStages + 1) * kKG * kFragBytes + (GATHER ? 255 * 16 * sizeof(int32_t) : 0);
   auto kern = k_argmax_stream<TPW, GATHER, BEAM>;
   static bool attr_done = false;
@@ -544,7 +557,7 @@ int launch_stream(const ArgmaxParams& p, unsigned grid, hipStream_t s) {
     if (rc != MQ_OK) return rc;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), smem, s, p);
+  hipLaunchKernelGGL(kern, dim3(grid, ny), dim3(kWaves * 64), smem, s, p);
   return check_hip(hipGetLastError());
 }
 
@@ -584,7 +597,7 @@ int launch_argmax_stream(const void* packedA, const void* packedW, size_t M, siz
   constexpr size_t kChunk = (size_t)kWaves * 3 * 16;
   for (size_t row0 = 0; row0 < M; row0 += kChunk) {
     const size_t rows = M - row0 < kChunk ? M - row0 : kChunk;
-    ArgmaxParams p;
+    ArgmaxParams p{};
     p.packedA = static_cast<const uint8_t*>(packedA) + dAll.frag_offset(row0 / 32, 0);
     p.packedW = static_cast<const uint8_t*>(packedW);
     p.M = (unsigned)rows; p.N = (unsigned)N; p.K = (unsigned)K;
@@ -653,9 +666,9 @@ int launch_argmax_stream_static(const void* packedA, const void* packedW, size_t
 }
 
 size_t topk_stream_ws_bytes(size_t M, int k) {
-  const size_t rows = M < 256 ? M : 256;           // rows are processed 256 at a time
+  // every row's candidates and normalisers from up to 256 workgroups (rows go 256 to a workgroup, all chunks in one launch)
   const int beam = k <= 2 ? 2 : 4;
-  return round_up((size_t)256 * rows * beam * sizeof(unsigned long long), 256) + (size_t)256 * rows * sizeof(float2);
+  return round_up((size_t)256 * M * beam * sizeof(unsigned long long), 256) + (size_t)256 * M * sizeof(float2);
 }
 
 bool topk_stream_supported(size_t M, size_t N, size_t K, int k) {
@@ -664,13 +677,13 @@ bool topk_stream_supported(size_t M, size_t N, size_t K, int k) {
 }
 
 // Beam-search output layer: the k <= 4 best words of every row with log-probabilities.  Rows are processed in
-// chunks of 256 (two sentence tiles per wave), each chunk streaming the embedding once.
+// chunks of 256 (two sentence tiles per wave), each chunk streaming the embedding once, all chunks in one launch.
 int launch_topk_stream(const void* packedA, const void* packedW, size_t M, size_t N, size_t K, const float* sA,
                        const float* sW, int k, int32_t* tok, float* logprob, void* ws, const int32_t* shortlist,
                        size_t shortlist_len, hipStream_t s) {
   if (!topk_stream_supported(M, N, K, k)) return MQ_ERR_UNSUPPORTED;
   if (shortlist != nullptr && (size_t)k > shortlist_len) return MQ_ERR_SHAPE;
-  const PackedDims dW(8, N, K), dAll(8, M, K);
+  const PackedDims dW(8, N, K);
   static int cus = 0;
   if (cus == 0) {
     int dev = 0, v = 0;
@@ -684,41 +697,41 @@ int launch_topk_stream(const void* packedA, const void* packedW, size_t M, size_
   if (grid > 256u) grid = 256u;
   if ((units + grid - 1) / grid > 255) return MQ_ERR_UNSUPPORTED;
   const int beam = k <= 2 ? 2 : 4;
-  const size_t rows_max = M < 256 ? M : 256;
   unsigned long long* keys = static_cast<unsigned long long*>(ws);
   float2* norm = reinterpret_cast<float2*>(static_cast<uint8_t*>(ws) +
-                                           round_up((size_t)256 * rows_max * beam * sizeof(unsigned long long), 256));
-  for (size_t row0 = 0; row0 < M; row0 += 256) {
-    const size_t rows = M - row0 < 256 ? M - row0 : 256;
-    ArgmaxParams p;
-    p.packedA = static_cast<const uint8_t*>(packedA) + dAll.frag_offset(row0 / 32, 0);
-    p.packedW = static_cast<const uint8_t*>(packedW);
-    p.M = (unsigned)rows; p.N = (unsigned)N; p.K = (unsigned)K;
-    p.partial = keys; p.norm = norm; p.sA = sA; p.sW = sW;
-    p.shortlist = shortlist;
-    p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
-    const int tpw = (int)(((rows + 15) / 16 + kWaves - 1) / kWaves);
-    int rc;
-    if (shortlist != nullptr) {
-      if (beam == 2) rc = tpw == 1 ? launch_stream<1, true, 2>(p, grid, s) : launch_stream<2, true, 2>(p, grid, s);
-      else rc = tpw == 1 ? launch_stream<1, true, 4>(p, grid, s) : launch_stream<2, true, 4>(p, grid, s);
-    } else {
-      if (beam == 2) rc = tpw == 1 ? launch_stream<1, false, 2>(p, grid, s) : launch_stream<2, false, 2>(p, grid, s);
-      else rc = tpw == 1 ? launch_stream<1, false, 4>(p, grid, s) : launch_stream<2, false, 4>(p, grid, s);
-    }
-    if (rc != MQ_OK) return rc;
-    int32_t* tok_c = tok + row0 * (size_t)k;
-    float* lp_c = logprob + row0 * (size_t)k;
-    if (beam == 2)
-      hipLaunchKernelGGL((k_topk_reduce<2>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, keys, norm, grid,
-                         (unsigned)rows, (unsigned)k, sA, sW, tok_c, lp_c, shortlist);
-    else
-      hipLaunchKernelGGL((k_topk_reduce<4>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, keys, norm, grid,
-                         (unsigned)rows, (unsigned)k, sA, sW, tok_c, lp_c, shortlist);
-    rc = check_hip(hipGetLastError());
-    if (rc != MQ_OK) return rc;
+                                           round_up((size_t)256 * M * beam * sizeof(unsigned long long), 256));
+  // Rows go 256 to a workgroup (two sentence tiles per wave); all chunks run in ONE launch, the grid's y index picking
+  // the chunk, and one reduce launch follows for all rows: a launch per chunk (ten for 1200 rows) cost more than the
+  // chunks' work.
+  constexpr unsigned kChunkRows = 256;
+  const unsigned nchunks = (unsigned)((M + kChunkRows - 1) / kChunkRows);
+  if (nchunks > 65535u) return MQ_ERR_UNSUPPORTED;
+  ArgmaxParams p{};
+  p.packedA = static_cast<const uint8_t*>(packedA);
+  p.packedW = static_cast<const uint8_t*>(packedW);
+  p.M = (unsigned)(M < kChunkRows ? M : kChunkRows); p.N = (unsigned)N; p.K = (unsigned)K;
+  p.partial = keys; p.norm = norm; p.sA = sA; p.sW = sW;
+  p.shortlist = shortlist;
+  p.L = shortlist != nullptr ? (unsigned)shortlist_len : (unsigned)N;
+  p.chunk_rows = nchunks > 1 ? kChunkRows : 0u;
+  p.Mtotal = (unsigned)M;
+  const int tpw = (int)(((size_t)(p.M + 15) / 16 + kWaves - 1) / kWaves);
+  int rc;
+  if (shortlist != nullptr) {
+    if (beam == 2) rc = tpw == 1 ? launch_stream<1, true, 2>(p, grid, s, nchunks) : launch_stream<2, true, 2>(p, grid, s, nchunks);
+    else rc = tpw == 1 ? launch_stream<1, true, 4>(p, grid, s, nchunks) : launch_stream<2, true, 4>(p, grid, s, nchunks);
+  } else {
+    if (beam == 2) rc = tpw == 1 ? launch_stream<1, false, 2>(p, grid, s, nchunks) : launch_stream<2, false, 2>(p, grid, s, nchunks);
+    else rc = tpw == 1 ? launch_stream<1, false, 4>(p, grid, s, nchunks) : launch_stream<2, false, 4>(p, grid, s, nchunks);
   }
-  return MQ_OK;
+  if (rc != MQ_OK) return rc;
+  if (beam == 2)
+    hipLaunchKernelGGL((k_topk_reduce<2>), dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, keys, norm, grid, (unsigned)M,
+                       (unsigned)k, sA, sW, tok, logprob, shortlist);
+  else
+    hipLaunchKernelGGL((k_topk_reduce<4>), dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s, keys, norm, grid, (unsigned)M,
+                       (unsigned)k, sA, sW, tok, logprob, shortlist);
+  return check_hip(hipGetLastError());
 }
 
 }  // namespace mq

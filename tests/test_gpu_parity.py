@@ -1431,11 +1431,11 @@ def gpu_topk(Hd, E, k, shortlist=None):
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 @pytest.mark.parametrize("M,V,d", [(1, 4, 1), (12, 777, 64), (33, 4100, 96), (300, 36000, 512), (130, 9000, 192),
-                                   (600, 5000, 128), (12, 70000, 64)])
+                                   (600, 5000, 128), (12, 70000, 64), (1200, 3000, 64)])
 def test_beam_output_layer_topk(M, V, d, k):
     # Table 2's b = 2 / b = 4 rows: the k best words per row, exact, with log-probabilities within 1e-4
-    # (binary32 logits of magnitude <= ~30 here; the normaliser sums V terms in binary32).  M = 600 goes
-    # through three chunks of rows.
+    # (binary32 logits of magnitude <= ~30 here; the normaliser sums V terms in binary32).  M = 600 and 1200 go
+    # through three and five chunks of rows (the last ones ragged), all in one launch.
     c = workloads.config3(M=M, V=V, d=d, seed_extra=M + V + k)
     o = oracle.topk_log_softmax(c["Hd"], c["E"], k)
     tok, lp = gpu_topk(c["Hd"], c["E"], k)
